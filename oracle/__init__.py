@@ -1,0 +1,23 @@
+"""CPU oracle for one AgentSAM speculative-decoding step.
+
+TEST INFRASTRUCTURE ONLY.  These are plain, slow, obviously-correct CPU
+implementations of what the hot path computes; they exist so the HIP library
+can be checked element by element.  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; the product path never
+does, and this package never imports the product package.  The two share no
+code.
+
+  draft      - brute-force backward scan for the longest matched suffix and its
+               continuation (C, see draft_oracle.c)          [Sec. 5.4.2, Alg. 4]
+  attention  - fp64 softmax attention of the 1+k verification rows over a
+               paged KV cache                                [Alg. 4 "Validate with main LLM"]
+  accept     - first-index argmax per row and the matched draft prefix
+                                                             [Alg. 4 "commit matched prefix"]
+
+Every function is pinned by tests that run without a GPU (worked examples,
+closed forms, invariants, an independent brute force, library special cases);
+none is "parity unpinned".
+"""
+from .draft import draft_oracle, draft_oracle_batch, build_oracle_lib  # noqa: F401
+from .attention import attention_oracle, attention_oracle_head          # noqa: F401
+from .accept import accept_oracle                                        # noqa: F401

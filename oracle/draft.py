@@ -1,0 +1,45 @@
+"""ctypes wrapper around draft_oracle.c (test infrastructure; see the package docstring)."""
+from __future__ import annotations
+
+import ctypes
+from typing import Tuple
+
+import numpy as np
+
+from ._clib import build_oracle_lib, load as _load, ptr as _p  # noqa: F401
+
+
+def draft_oracle(T, q, k: int, sep: int, min_match: int = 1) -> Tuple[np.ndarray, int, int, int]:
+    """One window against one memory.  Returns (draft[k] (-1 padded), n_draft, match_len, match_end)."""
+    lib = _load()
+    T = np.ascontiguousarray(T, dtype=np.int32)
+    q = np.ascontiguousarray(q, dtype=np.int32)
+    draft = np.full(max(k, 1), -1, dtype=np.int32)
+    nd = ctypes.c_int32(0)
+    ml = ctypes.c_int32(0)
+    me = ctypes.c_int64(0)
+    lib.draft_oracle(_p(T, ctypes.c_int32), T.shape[0], sep, _p(q, ctypes.c_int32), q.shape[0], k, min_match,
+                     _p(draft, ctypes.c_int32), ctypes.byref(nd), ctypes.byref(ml), ctypes.byref(me))
+    return draft[:k], nd.value, ml.value, me.value
+
+
+def draft_oracle_batch(T, mem_begin, mem_end, recent, recent_len, k: int, sep: int, min_match: int = 1):
+    """Batch form.  `T` is one int32 array holding every memory; session b searches
+    T[mem_begin[b]:mem_end[b]] with the last recent_len[b] tokens of recent[b].
+    Returns draft[B,k], n_draft[B], match_len[B], match_end[B] (relative to mem_begin[b])."""
+    lib = _load()
+    T = np.ascontiguousarray(T, dtype=np.int32)
+    mb = np.ascontiguousarray(mem_begin, dtype=np.int64)
+    me = np.ascontiguousarray(mem_end, dtype=np.int64)
+    recent = np.ascontiguousarray(recent, dtype=np.int32)
+    rl = np.ascontiguousarray(recent_len, dtype=np.int32)
+    B, m = recent.shape
+    draft = np.full((B, max(k, 1)), -1, dtype=np.int32)
+    nd = np.zeros(B, dtype=np.int32)
+    ml = np.zeros(B, dtype=np.int32)
+    mend = np.zeros(B, dtype=np.int64)
+    lib.draft_oracle_batch(_p(T, ctypes.c_int32), _p(mb, ctypes.c_int64), _p(me, ctypes.c_int64), sep,
+                           _p(recent, ctypes.c_int32), _p(rl, ctypes.c_int32), B, m, k, min_match,
+                           _p(draft, ctypes.c_int32), _p(nd, ctypes.c_int32), _p(ml, ctypes.c_int32),
+                           _p(mend, ctypes.c_int64))
+    return draft[:, :k], nd, ml, mend
