@@ -1,0 +1,161 @@
+/*
+ * agentsam.h - C ABI of the MI355X (gfx950) hot path of AgentSAM speculative
+ * decoding: one speculative step over a batch of agent sessions.
+ *
+ *   sam_build / sam_append / sam_flatten   host-side online suffix automaton over a
+ *                                          session (or multi-session) token memory
+ *   sam_draft                              device: longest matched suffix of each session's
+ *                                          recent tokens and up to k continuation tokens
+ *   spec_verify_attn                       device: causal GQA attention of the 1+k
+ *                                          verification rows over a paged KV cache
+ *   spec_accept                            device: greedy argmax per row and the accepted
+ *                                          draft prefix
+ *
+ * Conventions
+ *   - Every function returns 0 (AGENTSAM_OK) or a negative AGENTSAM_ERR_* code; nothing is
+ *     thrown across the boundary.  agentsam_strerror() gives the text.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP device memory
+ *     of the current device.  The library never allocates or frees device memory: every
+ *     device buffer (flattened automaton, workspace, outputs) belongs to the caller.
+ *   - Device entry points only enqueue work on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and return; argument errors are reported synchronously,
+ *     device-side results are valid after the caller synchronises the stream.
+ *   - All integer arrays are int32 unless stated; all arrays are dense, row-major.
+ */
+#ifndef AGENTSAM_H
+#define AGENTSAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AGENTSAM_OK                0
+#define AGENTSAM_ERR_NULL         -1   /* a required pointer is NULL                           */
+#define AGENTSAM_ERR_ARG          -2   /* a size or parameter is out of range                  */
+#define AGENTSAM_ERR_UNSUPPORTED  -3   /* a valid but unsupported shape / dtype                */
+#define AGENTSAM_ERR_WORKSPACE    -4   /* workspace smaller than spec_verify_attn_workspace()  */
+#define AGENTSAM_ERR_NOMEM        -5   /* host allocation failed                               */
+#define AGENTSAM_ERR_HIP          -6   /* a HIP launch failed (see hipGetLastError)            */
+#define AGENTSAM_ERR_TOKEN        -7   /* a token id is negative                               */
+
+#define AGENTSAM_F32   0
+#define AGENTSAM_BF16  1
+
+const char *agentsam_strerror(int code);
+
+/* Tuning knobs for experiments and for tests of split invariance.
+ *   "attn_kv_chunk"  KV positions handled by one workgroup of spec_verify_attn
+ *                    (0 = choose automatically; otherwise a multiple of 128, >= 128).
+ * Returns AGENTSAM_ERR_ARG for an unknown key or a bad value. */
+int agentsam_set_option(const char *key, int64_t value);
+
+/* ------------------------------------------------------------------------------------------
+ * Suffix automaton over a token memory (paper Sec. 5.4.2: the request context is indexed in a
+ * suffix automaton, built incrementally token by token; verified tokens are inserted as the
+ * context grows.  Alg. 4: BuildSAM, "incrementally extend S with streamed tokens").
+ *
+ * A memory is a sequence of non-negative token ids.  Several sessions may be concatenated in
+ * one memory, each terminated by `sep_token`, an id no query ever contains (Sec. 5.4.2,
+ * cross-session memory): matches then never span two sessions and drafts stop at a separator.
+ * sam_t is opaque, host-resident and owned by the library until sam_free().
+ * ---------------------------------------------------------------------------------------- */
+typedef struct sam sam_t;
+
+/* Build the automaton of tokens[0..n) (host pointer; n may be 0).  *out receives the handle. */
+int sam_build(const int32_t *tokens, int64_t n, int32_t sep_token, sam_t **out);
+
+/* Extend the automaton with n more tokens (host pointer), amortised O(1) per token. */
+int sam_append(sam_t *s, const int32_t *tokens, int64_t n);
+
+/* Sizes of the flattened form: states (root included), transitions, memory tokens. */
+int sam_flat_sizes(const sam_t *s, int64_t *n_states, int64_t *n_edges, int64_t *n_tokens);
+
+/* Write the flattened automaton into caller-provided HOST arrays (the caller uploads them):
+ *   len[ns]       longest string of each state
+ *   link[ns]      suffix link (state id, -1 for the root, which is local state 0)
+ *   row_ptr[ns+1] CSR offsets of each state's transitions
+ *   edge_tok[ne], edge_dst[ne]   transitions, sorted by token within a state
+ *   lastpos[ns]   the largest end position of the state's strings that still has a
+ *                 continuation (next token exists and is not sep_token), or -1
+ *   corpus[nt]    the token memory itself
+ * Several automata can be packed back to back in one set of arrays: state ids (link,
+ * edge_dst) are offset by state_base, row_ptr values by edge_base, lastpos by corpus_base,
+ * and the pointers passed here address this automaton's slice (row_ptr[ns] of one slice is
+ * row_ptr[0] of the next). */
+int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t corpus_base,
+                int32_t *len, int32_t *link, int32_t *row_ptr, int32_t *edge_tok,
+                int32_t *edge_dst, int32_t *lastpos, int32_t *corpus);
+
+void sam_free(sam_t *s);
+
+/* ------------------------------------------------------------------------------------------
+ * sam_draft (paper Sec. 5.4.2 and Alg. 4, FollowTransitions: "given the current verified
+ * suffix, follow SAM transitions to retrieve a matching continuation with a specified length").
+ *
+ * For each session b: feed its window recent[b, m-recent_len[b] .. m) (right-aligned) through
+ * the automaton whose root is root[b]; this yields the longest suffix of the window that occurs
+ * in the memory.  Among the occurrences that still have a continuation, the most recent one is
+ * taken (falling back to shorter suffixes along the suffix links when none has), and the k tokens
+ * after it are emitted, stopping before corpus_end[b] and before sep_token.
+ *
+ * Device inputs : the seven flattened arrays; root[B], corpus_end[B] (exclusive end of the
+ *                 session's memory in `corpus`), recent[B,m], recent_len[B] (0..m).
+ * Device outputs: draft[B,k] (-1 padded), n_draft[B], match_len[B], match_end[B] (index into
+ *                 `corpus`, -1 when nothing matched).  match_len < min_match gives no draft.
+ * Limits: 0 <= k <= 64, 1 <= m <= 64 (one wavefront holds a window), B >= 0. */
+int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
+              const int32_t *edge_tok, const int32_t *edge_dst, const int32_t *lastpos,
+              const int32_t *corpus, const int32_t *root, const int32_t *corpus_end,
+              const int32_t *recent, const int32_t *recent_len,
+              int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
+              int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+              void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * spec_verify_attn (Alg. 4: "Validate with main LLM" - the attention of the pass in which the
+ * target model scores the base token and the k drafts of every session at once).
+ *
+ *   R = 1+k query rows per session; row i sits at KV position seq_lens[b]-R+i and attends
+ *   positions 0 .. seq_lens[b]-R+i (the K/V of the R new positions are already in the cache).
+ *   out[b,i,h,:] = softmax_j(scale * q[b,i,h,:] . K_b[j, h/(Hq/Hkv), :]) . V_b[j, h/(Hq/Hkv), :]
+ *
+ * Device inputs : q[B,R,Hq,D]; k_cache, v_cache [num_pages,Hkv,page_size,D]; block_table
+ *                 [B,max_pages] (page id of KV positions p*page_size..); seq_lens[B] (>= R).
+ *                 dtype selects f32 or bf16 storage of q/k/v; accumulation is fp32.
+ * Device output : out[B,R,Hq,D] in out_dtype.
+ * workspace     : device scratch of at least spec_verify_attn_workspace() bytes (partial
+ *                 results of the KV splits); contents need no initialisation.
+ * A page id outside [0,num_pages) is treated as a page of zeros (never dereferenced).
+ * Supported: D in {64,128}; Hq % Hkv == 0; bf16 needs page_size % 32 == 0; scale > 0;
+ * (Hq/Hkv)*R <= 192 for bf16, R <= 32 for f32. */
+int spec_verify_attn_workspace(int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D,
+                               int32_t page_size, int32_t max_pages, int32_t dtype, size_t *bytes);
+
+int spec_verify_attn(const void *q, const void *k_cache, const void *v_cache,
+                     const int32_t *block_table, int32_t max_pages, const int32_t *seq_lens,
+                     int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
+                     int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype,
+                     void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * spec_accept (Alg. 4: "commit matched prefix; on mismatch fall back to standard decoding";
+ * Sec. 5.4.1: lossless, i.e. the output equals greedy decoding).
+ *
+ *   tgt[b,i]        = lowest index of the maximum of logits[b,i,:]   (NaN never wins)
+ *   accept_len[b]   = number of leading drafts j < n_draft[b] with draft[b,j] == tgt[b,j]
+ *   out_tokens[b,:] = tgt[b,0..accept_len[b]] (accepted drafts + bonus token), then -1
+ *
+ * Device inputs : logits[B,1+k,V] (f32 or bf16), draft[B,k], n_draft[B].
+ * Device outputs: accept_len[B], out_tokens[B,1+k], tgt[B,1+k].
+ * Limits: 0 <= k <= 63, V >= 1. */
+int spec_accept(const void *logits, int32_t logits_dtype, const int32_t *draft,
+                const int32_t *n_draft, int32_t B, int32_t k, int64_t V,
+                int32_t *accept_len, int32_t *out_tokens, int32_t *tgt, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGENTSAM_H */

@@ -1,1 +1,9 @@
-"""MI355X-native hot path of AgentSAM speculative decoding (one step over a batch of sessions)."""
+"""MI355X-native hot path of AgentSAM speculative decoding (one step over a batch of sessions).
+
+The Python layer is a thin ctypes binding over libagentsam.so (see include/agentsam.h); the
+library is loaded on first use and there is no fallback when it is missing.
+"""
+from .binding import (  # noqa: F401
+    AgentSamError, FlatSam, Sam, agentsam_set_option, sam_append, sam_build, sam_draft, sam_flat_sizes,
+    sam_flatten, spec_accept, spec_verify_attn, spec_verify_attn_workspace, strerror, BF16, F32,
+)

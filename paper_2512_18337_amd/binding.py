@@ -1,0 +1,250 @@
+"""ctypes binding of libagentsam.so: argument marshalling only.
+
+Every function has the name and the meaning of the C entry point it calls (see
+include/agentsam.h).  torch is used for device memory and the current stream; no
+step of the path is computed here.  If the library has not been built this module
+raises on first use: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libagentsam.so")
+_lib = None
+
+F32, BF16 = 0, 1
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_vp = ctypes.c_void_p
+
+EXPORTS = ["agentsam_strerror", "agentsam_set_option", "sam_build", "sam_append", "sam_flat_sizes",
+           "sam_flatten", "sam_free", "sam_draft", "spec_verify_attn_workspace", "spec_verify_attn",
+           "spec_accept"]
+
+
+class AgentSamError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2512_18337_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.agentsam_strerror.restype = ctypes.c_char_p
+        L.agentsam_strerror.argtypes = [ctypes.c_int]
+        L.agentsam_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+        L.sam_build.argtypes = [_i32p, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(_vp)]
+        L.sam_append.argtypes = [_vp, _i32p, ctypes.c_int64]
+        L.sam_flat_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 3
+        L.sam_flatten.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_i32p] * 7
+        L.sam_free.argtypes = [_vp]
+        L.sam_free.restype = None
+        L.sam_draft.argtypes = [_vp] * 11 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp]
+        L.spec_verify_attn_workspace.argtypes = [ctypes.c_int32] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
+        L.spec_verify_attn.argtypes = ([_vp, _vp, _vp, _vp, ctypes.c_int32, _vp] + [ctypes.c_int32] * 6 +
+                                       [ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
+                                        _vp, _vp, ctypes.c_size_t, _vp])
+        L.spec_accept.argtypes = [_vp, ctypes.c_int32, _vp, _vp, ctypes.c_int32, ctypes.c_int32,
+                                  ctypes.c_int64, _vp, _vp, _vp, _vp]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().agentsam_strerror(code).decode()
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise AgentSamError(rc, where)
+
+
+def agentsam_set_option(key: str, value: int) -> None:
+    _check(lib().agentsam_set_option(key.encode(), int(value)), f"agentsam_set_option({key})")
+
+
+# ----------------------------------------------------------------------------- host automaton
+def _np_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _npp(a: np.ndarray):
+    return a.ctypes.data_as(_i32p)
+
+
+class Sam:
+    """Owner of one sam_t handle."""
+
+    def __init__(self, handle: int):
+        self._h = _vp(handle)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h is not None and h.value and _lib is not None:
+            _lib.sam_free(h)
+
+
+def sam_build(tokens, sep_token: int) -> Sam:
+    t = _np_i32(tokens)
+    h = _vp()
+    _check(lib().sam_build(_npp(t), t.shape[0], int(sep_token), ctypes.byref(h)), "sam_build")
+    return Sam(h.value)
+
+
+def sam_append(s: Sam, tokens) -> None:
+    t = _np_i32(tokens)
+    _check(lib().sam_append(s._h, _npp(t), t.shape[0]), "sam_append")
+
+
+def sam_flat_sizes(s: Sam):
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().sam_flat_sizes(s._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "sam_flat_sizes")
+    return a.value, b.value, c.value
+
+
+@dataclass
+class FlatSam:
+    """The flattened arrays of one or several automata packed back to back (host numpy or device torch)."""
+    len: object
+    link: object
+    row_ptr: object
+    edge_tok: object
+    edge_dst: object
+    lastpos: object
+    corpus: object
+    roots: np.ndarray          # [n_automata] root state id of each automaton
+    corpus_begin: np.ndarray   # [n_automata]
+    corpus_end: np.ndarray     # [n_automata] exclusive
+
+    def to(self, device):
+        import torch
+        cv = lambda a: torch.as_tensor(a, dtype=torch.int32).to(device)
+        # zero-length arrays still need a valid (non-null) device pointer
+        pad = lambda a: a if a.shape[0] > 0 else np.zeros(1, dtype=np.int32)
+        return FlatSam(cv(self.len), cv(self.link), cv(self.row_ptr), cv(pad(self.edge_tok)),
+                       cv(pad(self.edge_dst)), cv(self.lastpos), cv(pad(self.corpus)),
+                       self.roots, self.corpus_begin, self.corpus_end)
+
+
+def sam_flatten(sams: Sequence[Sam]) -> FlatSam:
+    """sam_flatten of each automaton into one packed set of host arrays."""
+    sizes = [sam_flat_sizes(s) for s in sams]
+    ns, ne, nt = (sum(x[i] for x in sizes) for i in range(3))
+    out = FlatSam(np.zeros(ns, np.int32), np.zeros(ns, np.int32), np.zeros(ns + 1, np.int32),
+                  np.zeros(ne, np.int32), np.zeros(ne, np.int32), np.zeros(ns, np.int32),
+                  np.zeros(nt, np.int32), np.zeros(len(sams), np.int32), np.zeros(len(sams), np.int32),
+                  np.zeros(len(sams), np.int32))
+    sb = eb = cb = 0
+    for i, (s, (a, b, c)) in enumerate(zip(sams, sizes)):
+        _check(lib().sam_flatten(s._h, sb, eb, cb, _npp(out.len[sb:]), _npp(out.link[sb:]),
+                                 _npp(out.row_ptr[sb:]), _npp(out.edge_tok[eb:]) if b else None,
+                                 _npp(out.edge_dst[eb:]) if b else None, _npp(out.lastpos[sb:]),
+                                 _npp(out.corpus[cb:]) if c else None), "sam_flatten")
+        out.roots[i], out.corpus_begin[i], out.corpus_end[i] = sb, cb, cb + c
+        sb, eb, cb = sb + a, eb + b, cb + c
+    return out
+
+
+# ----------------------------------------------------------------------------- device entry points
+def _stream_ptr():
+    import torch
+    return _vp(torch.cuda.current_stream().cuda_stream)
+
+
+def _dp(t) -> _vp:
+    return _vp(t.data_ptr()) if t is not None else _vp(0)
+
+
+def _dev_i32(a, device):
+    import torch
+    if isinstance(a, torch.Tensor):
+        assert a.dtype == torch.int32 and a.is_contiguous() and a.is_cuda
+        return a
+    return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+
+
+def sam_draft(flat: FlatSam, root, corpus_end, recent, recent_len, k: int, sep_token: int, min_match: int = 1):
+    """Returns device tensors draft[B,k], n_draft[B], match_len[B], match_end[B]."""
+    import torch
+    dev = flat.len.device
+    root, corpus_end = _dev_i32(root, dev), _dev_i32(corpus_end, dev)
+    recent, recent_len = _dev_i32(recent, dev), _dev_i32(recent_len, dev)
+    B, m = recent.shape
+    draft = torch.empty((B, k), dtype=torch.int32, device=dev)
+    n_draft = torch.empty((B,), dtype=torch.int32, device=dev)
+    match_len = torch.empty((B,), dtype=torch.int32, device=dev)
+    match_end = torch.empty((B,), dtype=torch.int32, device=dev)
+    rc = lib().sam_draft(_dp(flat.len), _dp(flat.link), _dp(flat.row_ptr), _dp(flat.edge_tok), _dp(flat.edge_dst),
+                         _dp(flat.lastpos), _dp(flat.corpus), _dp(root), _dp(corpus_end), _dp(recent),
+                         _dp(recent_len), B, m, k, min_match, sep_token,
+                         _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
+                         _stream_ptr())
+    _check(rc, "sam_draft")
+    return draft, n_draft, match_len, match_end
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def spec_verify_attn_workspace(B, R, Hq, Hkv, D, page_size, max_pages, dtype_code) -> int:
+    n = ctypes.c_size_t()
+    _check(lib().spec_verify_attn_workspace(B, R, Hq, Hkv, D, page_size, max_pages, dtype_code, ctypes.byref(n)),
+           "spec_verify_attn_workspace")
+    return n.value
+
+
+def spec_verify_attn(q, k_cache, v_cache, block_table, seq_lens, scale: float, out=None, workspace=None,
+                     out_dtype=None):
+    """q[B,R,Hq,D]; caches [num_pages,Hkv,P,D]; block_table[B,max_pages] int32; seq_lens[B] int32 (device)."""
+    import torch
+    B, R, Hq, D = q.shape
+    num_pages, Hkv, P, D2 = k_cache.shape
+    assert D2 == D and v_cache.shape == k_cache.shape and k_cache.dtype == q.dtype == v_cache.dtype
+    assert q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous() and seq_lens.dtype == torch.int32
+    max_pages = block_table.shape[1]
+    code = _dtype_code(q)
+    if out is None:
+        out = torch.empty((B, R, Hq, D), dtype=out_dtype or torch.float32, device=q.device)
+    need = spec_verify_attn_workspace(B, R, Hq, Hkv, D, P, max_pages, code)
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty((max(need, 16) + 3) // 4, dtype=torch.float32, device=q.device)
+    rc = lib().spec_verify_attn(_dp(q), _dp(k_cache), _dp(v_cache), _dp(block_table), max_pages, _dp(seq_lens),
+                                B, R, Hq, Hkv, D, P, num_pages, float(scale), code, _dtype_code(out),
+                                _dp(out), _dp(workspace), workspace.numel() * workspace.element_size(),
+                                _stream_ptr())
+    _check(rc, "spec_verify_attn")
+    return out
+
+
+def spec_accept(logits, draft, n_draft):
+    """logits[B,1+k,V] (f32|bf16), draft[B,k] int32, n_draft[B] int32 -> accept_len[B], out_tokens[B,1+k], tgt[B,1+k]."""
+    import torch
+    B, R, V = logits.shape
+    k = R - 1
+    assert logits.is_contiguous() and draft.dtype == torch.int32 and n_draft.dtype == torch.int32
+    dev = logits.device
+    accept_len = torch.empty((B,), dtype=torch.int32, device=dev)
+    out_tokens = torch.empty((B, R), dtype=torch.int32, device=dev)
+    tgt = torch.empty((B, R), dtype=torch.int32, device=dev)
+    rc = lib().spec_accept(_dp(logits), _dtype_code(logits), _dp(draft) if k > 0 else _vp(0), _dp(n_draft),
+                           B, k, V, _dp(accept_len), _dp(out_tokens), _dp(tgt), _stream_ptr())
+    _check(rc, "spec_accept")
+    return accept_len, out_tokens, tgt

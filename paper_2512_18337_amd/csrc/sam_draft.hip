@@ -1,0 +1,122 @@
+// sam_draft: batched suffix-automaton draft lookup, one wavefront per session.
+//
+// Paper Sec. 5.4.2 / Alg. 4 (FollowTransitions): given the current verified suffix, follow
+// the automaton's transitions to retrieve a matching continuation of a specified length.
+//
+// The walk itself is a chain of dependent loads (state -> transition row -> next state), so a
+// session cannot be made faster by adding lanes; the 64 lanes are used where there is width:
+// the window is fetched with one coalesced load and broadcast lane by lane, a state's sorted
+// transition row is searched 64 entries at a time (64-ary narrowing for the few very wide
+// states such as the root), and the continuation is read and cut with one load and a ballot.
+// Throughput comes from the sessions running side by side on different compute units.
+#include "common.h"
+
+namespace {
+
+__device__ __forceinline__ int wave_bcast(int v, int src_lane) { return __shfl(v, src_lane, 64); }
+
+// Destination of the transition (row [r0,r1) sorted by token) labelled c, or -1.  Wave-uniform.
+__device__ __forceinline__ int find_edge(const int32_t *__restrict__ edge_tok,
+                                         const int32_t *__restrict__ edge_dst,
+                                         int r0, int r1, int c, int lane) {
+    int lo = r0, hi = r1;
+    while (hi - lo > 64) {
+        const int step = (hi - lo + 63) >> 6;
+        const int idx = lo + lane * step;
+        const bool le = (idx < hi) && (edge_tok[idx] <= c);
+        const int j = __popcll(__ballot(le));              // sorted row: the lanes with tok <= c form a prefix
+        if (j == 0) return -1;
+        lo = lo + (j - 1) * step;
+        hi = min(hi, lo + step);
+    }
+    const int idx = lo + lane;
+    const bool in = idx < hi;
+    const int tk = in ? edge_tok[idx] : -1;
+    const int ds = in ? edge_dst[idx] : -1;
+    const unsigned long long eq = __ballot(in && tk == c);
+    if (eq == 0ull) return -1;
+    return wave_bcast(ds, __ffsll((long long)eq) - 1);
+}
+
+__global__ __launch_bounds__(64) void sam_draft_kernel(
+    const int32_t *__restrict__ len, const int32_t *__restrict__ link, const int32_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ edge_tok, const int32_t *__restrict__ edge_dst,
+    const int32_t *__restrict__ lastpos, const int32_t *__restrict__ corpus,
+    const int32_t *__restrict__ root_arr, const int32_t *__restrict__ corpus_end,
+    const int32_t *__restrict__ recent, const int32_t *__restrict__ recent_len,
+    int m, int k, int min_match, int sep,
+    int32_t *__restrict__ draft, int32_t *__restrict__ n_draft, int32_t *__restrict__ match_len,
+    int32_t *__restrict__ match_end) {
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int root = root_arr[b];
+    const int ql = max(0, min(m, recent_len[b]));
+    // lane i holds the i-th token of the (right-aligned) window
+    const int wtok = (lane < ql) ? recent[(int64_t)b * m + (m - ql) + lane] : -1;
+
+    // longest suffix of the window that occurs in the memory: state s, matched length l
+    int s = root, l = 0;
+    for (int t = 0; t < ql; ++t) {
+        const int c = wave_bcast(wtok, t);
+        for (;;) {
+            const int dst = find_edge(edge_tok, edge_dst, row_ptr[s], row_ptr[s + 1], c, lane);
+            if (dst >= 0) { s = dst; ++l; break; }
+            if (s == root) { l = 0; break; }
+            s = link[s];
+            l = len[s];
+        }
+        s = __builtin_amdgcn_readfirstlane(s);
+        l = __builtin_amdgcn_readfirstlane(l);
+    }
+
+    // most recent occurrence that still has a continuation; all strings of one state share their
+    // end positions, so if this state has none, the next candidate is the suffix link's longest string
+    int L = l, e = -1;
+    while (s != root) {
+        const int lp = lastpos[s];
+        if (lp >= 0) { e = lp; break; }
+        s = link[s];
+        L = len[s];
+    }
+    if (e < 0 || L < min_match) { e = -1; L = 0; }
+
+    int n = 0;
+    int tk = -1;
+    if (e >= 0 && k > 0) {
+        const int idx = e + 1 + lane;
+        const bool in = (lane < k) && (idx < corpus_end[b]);
+        tk = in ? corpus[idx] : sep;
+        const unsigned long long stop = __ballot(!(in && tk != sep));
+        n = stop ? (__ffsll((long long)stop) - 1) : 64;
+    }
+    if (lane < k) draft[(int64_t)b * k + lane] = (lane < n) ? tk : -1;
+    if (lane == 0) {
+        n_draft[b] = n;
+        match_len[b] = L;
+        match_end[b] = e;
+    }
+}
+
+}  // namespace
+
+extern "C" int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
+                         const int32_t *edge_tok, const int32_t *edge_dst, const int32_t *lastpos,
+                         const int32_t *corpus, const int32_t *root, const int32_t *corpus_end,
+                         const int32_t *recent, const int32_t *recent_len,
+                         int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
+                         int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+                         void *stream) {
+    if (B < 0 || m < 1 || m > 64 || k < 0 || k > 64 || min_match < 0) return AGENTSAM_ERR_ARG;
+    if (B == 0) return AGENTSAM_OK;
+    if (!len || !link || !row_ptr || !lastpos || !root || !corpus_end || !recent || !recent_len ||
+        !n_draft || !match_len || !match_end || (k > 0 && !draft))
+        return AGENTSAM_ERR_NULL;
+    // edge_tok / edge_dst / corpus may be NULL only for an automaton with no transitions (empty
+    // memory): then every row is empty and nothing matches, so they are never dereferenced.
+    hipLaunchKernelGGL(sam_draft_kernel, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
+                       len, link, row_ptr, edge_tok, edge_dst, lastpos, corpus, root, corpus_end,
+                       recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
+                       draft, n_draft, match_len, match_end);
+    AGENTSAM_LAUNCH_CHECK();
+    return AGENTSAM_OK;
+}

@@ -1,0 +1,224 @@
+// Host-side online suffix automaton over a token memory, and its flattening to the
+// arrays sam_draft reads on the device.
+//
+// Paper Sec. 5.4.2: the request context is indexed in a suffix automaton that is built
+// incrementally token by token (linear in the context length) and extended with verified
+// tokens as the context grows; Alg. 4: BuildSAM / "incrementally extend S with streamed
+// tokens".  The construction is the textbook online algorithm (new state, walk suffix
+// links adding transitions, clone on a length mismatch).
+//
+// Storage is sized for memories of millions of tokens over vocabularies of ~150k ids:
+// transitions live in one arena (per-state singly linked lists, needed to copy a state's
+// transitions when it is cloned) and are found through one open-addressing hash keyed by
+// (state, token), so a lookup is O(1) whatever the state's degree.
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "agentsam.h"
+
+struct sam {
+    int32_t sep = -1;
+    int32_t last = 0;
+    std::vector<int32_t> len, link, created_at, head;   // per state; created_at = -1 for clones/root
+    std::vector<int32_t> e_tok, e_dst, e_next;          // transition arena
+    std::vector<uint64_t> h_key;                        // hash: key -> arena index
+    std::vector<int32_t> h_val;
+    uint64_t h_mask = 0;
+    uint64_t h_used = 0;
+    std::vector<int32_t> corpus;
+
+    static constexpr uint64_t kEmpty = ~0ull;
+
+    static uint64_t mix(uint64_t k) {
+        k ^= k >> 33; k *= 0xff51afd7ed558ccdull; k ^= k >> 33; k *= 0xc4ceb9fe1a85ec53ull; k ^= k >> 33;
+        return k;
+    }
+    static uint64_t key_of(int32_t st, int32_t tok) { return ((uint64_t)(uint32_t)st << 32) | (uint32_t)tok; }
+
+    void rehash(uint64_t cap) {
+        std::vector<uint64_t> nk(cap, kEmpty);
+        std::vector<int32_t> nv(cap, -1);
+        uint64_t mask = cap - 1;
+        for (uint64_t i = 0; i < h_key.size(); ++i) {
+            if (h_key[i] == kEmpty) continue;
+            uint64_t j = mix(h_key[i]) & mask;
+            while (nk[j] != kEmpty) j = (j + 1) & mask;
+            nk[j] = h_key[i]; nv[j] = h_val[i];
+        }
+        h_key.swap(nk); h_val.swap(nv); h_mask = mask;
+    }
+    int32_t find(int32_t st, int32_t tok) const {       // arena index or -1
+        uint64_t k = key_of(st, tok), j = mix(k) & h_mask;
+        while (h_key[j] != kEmpty) {
+            if (h_key[j] == k) return h_val[j];
+            j = (j + 1) & h_mask;
+        }
+        return -1;
+    }
+    void add_edge(int32_t st, int32_t tok, int32_t dst) {
+        if ((h_used + 1) * 10 > (h_mask + 1) * 6) rehash((h_mask + 1) * 2);
+        int32_t e = (int32_t)e_tok.size();
+        e_tok.push_back(tok); e_dst.push_back(dst); e_next.push_back(head[st]);
+        head[st] = e;
+        uint64_t k = key_of(st, tok), j = mix(k) & h_mask;
+        while (h_key[j] != kEmpty) j = (j + 1) & h_mask;
+        h_key[j] = k; h_val[j] = e; ++h_used;
+    }
+    int32_t new_state(int32_t l, int32_t lk, int32_t created) {
+        len.push_back(l); link.push_back(lk); created_at.push_back(created); head.push_back(-1);
+        return (int32_t)len.size() - 1;
+    }
+    void init(int32_t sep_token) {
+        sep = sep_token;
+        h_key.assign(1024, kEmpty); h_val.assign(1024, -1); h_mask = 1023; h_used = 0;
+        new_state(0, -1, -1);
+        last = 0;
+    }
+    void extend(int32_t c) {
+        const int32_t pos = (int32_t)corpus.size();
+        corpus.push_back(c);
+        const int32_t cur = new_state(len[last] + 1, 0, pos);
+        int32_t p = last;
+        int32_t e = -1;
+        while (p != -1 && (e = find(p, c)) < 0) {
+            add_edge(p, c, cur);
+            p = link[p];
+        }
+        if (p != -1) {
+            const int32_t q = e_dst[e];
+            if (len[p] + 1 == len[q]) {
+                link[cur] = q;
+            } else {
+                const int32_t cl = new_state(len[p] + 1, link[q], -1);
+                for (int32_t x = head[q]; x != -1; x = e_next[x]) add_edge(cl, e_tok[x], e_dst[x]);
+                while (p != -1) {
+                    const int32_t ee = find(p, c);
+                    if (ee < 0 || e_dst[ee] != q) break;
+                    e_dst[ee] = cl;
+                    p = link[p];
+                }
+                link[q] = cl;
+                link[cur] = cl;
+            }
+        }
+        last = cur;
+    }
+};
+
+extern "C" {
+
+const char *agentsam_strerror(int code) {
+    switch (code) {
+        case AGENTSAM_OK: return "ok";
+        case AGENTSAM_ERR_NULL: return "a required pointer is NULL";
+        case AGENTSAM_ERR_ARG: return "argument out of range";
+        case AGENTSAM_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case AGENTSAM_ERR_WORKSPACE: return "workspace too small";
+        case AGENTSAM_ERR_NOMEM: return "host allocation failed";
+        case AGENTSAM_ERR_HIP: return "HIP launch failed";
+        case AGENTSAM_ERR_TOKEN: return "negative token id";
+        default: return "unknown error";
+    }
+}
+
+static int check_tokens(const int32_t *t, int64_t n) {
+    for (int64_t i = 0; i < n; ++i)
+        if (t[i] < 0) return AGENTSAM_ERR_TOKEN;
+    return AGENTSAM_OK;
+}
+
+int sam_append(sam_t *s, const int32_t *tokens, int64_t n) {
+    if (!s || (n > 0 && !tokens)) return AGENTSAM_ERR_NULL;
+    if (n < 0) return AGENTSAM_ERR_ARG;
+    if ((int64_t)s->corpus.size() + n > (int64_t)0x3fffffff) return AGENTSAM_ERR_ARG;  // 2N states fit int32
+    int rc = check_tokens(tokens, n);
+    if (rc) return rc;
+    try {
+        s->corpus.reserve(s->corpus.size() + (size_t)n);
+        for (int64_t i = 0; i < n; ++i) s->extend(tokens[i]);
+    } catch (const std::bad_alloc &) {
+        return AGENTSAM_ERR_NOMEM;
+    }
+    return AGENTSAM_OK;
+}
+
+int sam_build(const int32_t *tokens, int64_t n, int32_t sep_token, sam_t **out) {
+    if (!out || (n > 0 && !tokens)) return AGENTSAM_ERR_NULL;
+    if (n < 0) return AGENTSAM_ERR_ARG;
+    *out = nullptr;
+    sam *s = new (std::nothrow) sam();
+    if (!s) return AGENTSAM_ERR_NOMEM;
+    try {
+        s->init(sep_token);
+    } catch (const std::bad_alloc &) {
+        delete s;
+        return AGENTSAM_ERR_NOMEM;
+    }
+    int rc = sam_append(s, tokens, n);
+    if (rc) { delete s; return rc; }
+    *out = s;
+    return AGENTSAM_OK;
+}
+
+int sam_flat_sizes(const sam_t *s, int64_t *n_states, int64_t *n_edges, int64_t *n_tokens) {
+    if (!s) return AGENTSAM_ERR_NULL;
+    if (n_states) *n_states = (int64_t)s->len.size();
+    if (n_edges) *n_edges = (int64_t)s->e_tok.size();
+    if (n_tokens) *n_tokens = (int64_t)s->corpus.size();
+    return AGENTSAM_OK;
+}
+
+int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t corpus_base,
+                int32_t *len, int32_t *link, int32_t *row_ptr, int32_t *edge_tok,
+                int32_t *edge_dst, int32_t *lastpos, int32_t *corpus) {
+    if (!s || !len || !link || !row_ptr || !lastpos) return AGENTSAM_ERR_NULL;
+    const int64_t ns = (int64_t)s->len.size(), ne = (int64_t)s->e_tok.size(), nt = (int64_t)s->corpus.size();
+    if ((ne > 0 && (!edge_tok || !edge_dst)) || (nt > 0 && !corpus)) return AGENTSAM_ERR_NULL;
+    if (state_base < 0 || edge_base < 0 || corpus_base < 0) return AGENTSAM_ERR_ARG;
+    if ((int64_t)state_base + ns > INT32_MAX || (int64_t)edge_base + ne > INT32_MAX ||
+        (int64_t)corpus_base + nt > INT32_MAX) return AGENTSAM_ERR_ARG;
+    try {
+        // states by decreasing len (counting sort), to push end positions up the suffix links
+        std::vector<int32_t> cnt((size_t)nt + 2, 0), order((size_t)ns);
+        for (int64_t v = 0; v < ns; ++v) ++cnt[(size_t)s->len[v] + 1];
+        for (size_t i = 1; i < cnt.size(); ++i) cnt[i] += cnt[i - 1];
+        for (int64_t v = 0; v < ns; ++v) order[(size_t)cnt[(size_t)s->len[v]]++] = (int32_t)v;
+        std::vector<int32_t> lp((size_t)ns, -1);
+        for (int64_t v = 0; v < ns; ++v) {
+            const int32_t p = s->created_at[v];
+            if (p >= 0 && (int64_t)p + 1 < nt && s->corpus[(size_t)p + 1] != s->sep) lp[(size_t)v] = p;
+        }
+        for (int64_t i = ns - 1; i > 0; --i) {               // order[0] is the root
+            const int32_t v = order[(size_t)i], u = s->link[v];
+            if (u >= 0 && lp[(size_t)v] > lp[(size_t)u]) lp[(size_t)u] = lp[(size_t)v];
+        }
+        std::vector<std::pair<int32_t, int32_t>> tmp;
+        int64_t at = 0;
+        for (int64_t v = 0; v < ns; ++v) {
+            len[v] = s->len[v];
+            link[v] = s->link[v] < 0 ? -1 : s->link[v] + state_base;
+            lastpos[v] = lp[(size_t)v] < 0 ? -1 : lp[(size_t)v] + corpus_base;
+            row_ptr[v] = (int32_t)(at + edge_base);
+            tmp.clear();
+            for (int32_t x = s->head[v]; x != -1; x = s->e_next[x]) tmp.emplace_back(s->e_tok[x], s->e_dst[x]);
+            if (tmp.size() > 1) std::sort(tmp.begin(), tmp.end());
+            for (const auto &pr : tmp) {
+                edge_tok[at] = pr.first;
+                edge_dst[at] = pr.second + state_base;
+                ++at;
+            }
+        }
+        row_ptr[ns] = (int32_t)(at + edge_base);
+        if (nt > 0) std::memcpy(corpus, s->corpus.data(), (size_t)nt * sizeof(int32_t));
+    } catch (const std::bad_alloc &) {
+        return AGENTSAM_ERR_NOMEM;
+    }
+    return AGENTSAM_OK;
+}
+
+void sam_free(sam_t *s) { delete s; }
+
+}  // extern "C"

@@ -1,0 +1,141 @@
+// spec_accept: greedy verification of the drafts.
+//
+// Alg. 4 ("Validate with main LLM; commit matched prefix; on mismatch fall back") and the
+// losslessness claim of Sec. 5.4.1: the committed tokens equal greedy decoding.
+//
+// Two launches on the caller's stream:
+//   1. row_argmax: one workgroup per logits row streams the row once with 16-byte loads
+//      (the kernel is bound by HBM bandwidth: V*sizeof(logit) bytes per row, nothing reused)
+//      and reduces (value, index) pairs with the first-index tie rule through wavefront
+//      shuffles and one LDS exchange.
+//   2. accept_prefix: one lane per session compares the drafts with the row targets.
+#include <hip/hip_bf16.h>
+
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kNoIndex = 0x7fffffff;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct Best {
+    float v;
+    int i;
+};
+
+// candidate b replaces a when it is larger, or equal with a lower index
+__device__ __forceinline__ Best better(Best a, Best b) {
+    const bool take = (b.v > a.v) || (b.v == a.v && b.i < a.i);
+    return take ? b : a;
+}
+
+__device__ __forceinline__ float clean(float x) { return (x != x) ? -INFINITY : x; }   // NaN never wins
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+template <bool BF16>
+__device__ __forceinline__ float load_one(const void *row, int64_t i) {
+    if (BF16) return bf16_bits_to_float(((const uint16_t *)row)[i]);
+    return ((const float *)row)[i];
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void row_argmax_kernel(const void *__restrict__ logits, int64_t V,
+                                                              int32_t *__restrict__ tgt) {
+    constexpr int kElem = BF16 ? 2 : 4;
+    constexpr int kPerVec = 16 / kElem;
+    const int64_t row_id = blockIdx.x;
+    const char *row = (const char *)logits + row_id * V * kElem;
+    const int tid = threadIdx.x;
+
+    // split the row into an unaligned head, a 16-byte-aligned body and a tail
+    const int64_t mis = (int64_t)((uintptr_t)row & 15);
+    int64_t head = mis ? (16 - mis) / kElem : 0;
+    if (head > V) head = V;
+    const int64_t nvec = (V - head) / kPerVec;
+    const int64_t tail0 = head + nvec * kPerVec;
+
+    Best best{-INFINITY, kNoIndex};
+    if (tid < head) {
+        const float x = clean(load_one<BF16>(row, tid));
+        if (x > best.v) best = Best{x, (int)tid};
+    }
+    const u32x4 *body = (const u32x4 *)(row + head * kElem);
+#pragma unroll 4
+    for (int64_t j = tid; j < nvec; j += kThreads) {
+        const u32x4 w = __builtin_nontemporal_load(body + j);
+        const int64_t base = head + j * kPerVec;
+        const uint32_t ws[4] = {w[0], w[1], w[2], w[3]};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (BF16) {
+                const float x0 = clean(bf16_bits_to_float(ws[c] & 0xffffu));
+                const float x1 = clean(__uint_as_float(ws[c] & 0xffff0000u));
+                if (x0 > best.v) best = Best{x0, (int)(base + 2 * c)};
+                if (x1 > best.v) best = Best{x1, (int)(base + 2 * c + 1)};
+            } else {
+                const float x = clean(__uint_as_float(ws[c]));
+                if (x > best.v) best = Best{x, (int)(base + c)};
+            }
+        }
+    }
+    // every thread visits its indices in increasing order (head < body < tail), so the strict
+    // comparison keeps the first maximum it sees
+    for (int64_t i = tail0 + tid; i < V; i += kThreads) {
+        const float x = clean(load_one<BF16>(row, i));
+        if (x > best.v) best = Best{x, (int)i};
+    }
+
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        Best o{__shfl_xor(best.v, off, 64), __shfl_xor(best.i, off, 64)};
+        best = better(best, o);
+    }
+    __shared__ float sv[kThreads / 64];
+    __shared__ int si[kThreads / 64];
+    if ((tid & 63) == 0) { sv[tid >> 6] = best.v; si[tid >> 6] = best.i; }
+    __syncthreads();
+    if (tid == 0) {
+        Best r{sv[0], si[0]};
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) r = better(r, Best{sv[w], si[w]});
+        tgt[row_id] = (r.i == kNoIndex) ? 0 : r.i;       // no finite maximum: index 0
+    }
+}
+
+__global__ void accept_prefix_kernel(const int32_t *__restrict__ tgt, const int32_t *__restrict__ draft,
+                                     const int32_t *__restrict__ n_draft, int B, int k,
+                                     int32_t *__restrict__ accept_len, int32_t *__restrict__ out_tokens) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int R = k + 1;
+    const int nd = min(max(n_draft[b], 0), k);
+    int a = 0;
+    while (a < nd && draft[(int64_t)b * k + a] == tgt[(int64_t)b * R + a]) ++a;
+    accept_len[b] = a;
+    for (int i = 0; i < R; ++i) out_tokens[(int64_t)b * R + i] = (i <= a) ? tgt[(int64_t)b * R + i] : -1;
+}
+
+}  // namespace
+
+extern "C" int spec_accept(const void *logits, int32_t logits_dtype, const int32_t *draft,
+                           const int32_t *n_draft, int32_t B, int32_t k, int64_t V,
+                           int32_t *accept_len, int32_t *out_tokens, int32_t *tgt, void *stream) {
+    if (B < 0 || k < 0 || k > 63 || V < 1 || V > 0x7ffffff0ll) return AGENTSAM_ERR_ARG;
+    if (logits_dtype != AGENTSAM_F32 && logits_dtype != AGENTSAM_BF16) return AGENTSAM_ERR_UNSUPPORTED;
+    if (B == 0) return AGENTSAM_OK;
+    if (!logits || !n_draft || !accept_len || !out_tokens || !tgt || (k > 0 && !draft)) return AGENTSAM_ERR_NULL;
+    const int64_t rows = (int64_t)B * (k + 1);
+    if (rows > 0x7fffffffll) return AGENTSAM_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (logits_dtype == AGENTSAM_BF16)
+        hipLaunchKernelGGL(row_argmax_kernel<true>, dim3((unsigned)rows), dim3(kThreads), 0, st, logits, V, tgt);
+    else
+        hipLaunchKernelGGL(row_argmax_kernel<false>, dim3((unsigned)rows), dim3(kThreads), 0, st, logits, V, tgt);
+    AGENTSAM_LAUNCH_CHECK();
+    hipLaunchKernelGGL(accept_prefix_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), 0, st, tgt, draft,
+                       n_draft, (int)B, (int)k, accept_len, out_tokens);
+    AGENTSAM_LAUNCH_CHECK();
+    return AGENTSAM_OK;
+}

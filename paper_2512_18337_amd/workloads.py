@@ -233,7 +233,7 @@ def recent_windows(cfg: Config, memories: List[np.ndarray]) -> Tuple[np.ndarray,
                     break
             if w is None:
                 w = st.randint(0, cfg.vocab - 1, m).astype(np.int32)
-            else:
+            elif m >= 2:
                 d = st.one_int(1, m - 1)
                 w[m - 1 - d] = st.one_int(0, cfg.vocab - 1)
         else:

@@ -1,0 +1,170 @@
+"""GPU parity of spec_verify_attn against the fp64 oracle, through the C ABI.
+
+Tolerances (max-abs): 1e-5 for fp32 storage, 2e-2 for bf16 storage with fp32 accumulation.
+For bf16 the tests additionally hold the kernel to 3e-3, which is what rounding the
+softmax weights to bf16 (relative 2^-9 per term) allows on N(0,1) values.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_18337_amd as A
+from paper_2512_18337_amd import workloads as W
+from _util import oracle_attention_sample, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+TIGHT = {"f32": 1e-5, "bf16": 3e-3}
+
+
+def _inputs(cfg):
+    lay = W.kv_layout(cfg)
+    q, kc, vc = W.kv_and_queries(cfg, lay, DEV)
+    bt = torch.as_tensor(lay.block_table, device=DEV)
+    seq = torch.as_tensor(lay.seq_lens, device=DEV)
+    return lay, q, kc, vc, bt, seq
+
+
+def _check(cfg, lay, q, kc, vc, out, pairs):
+    scale = 1.0 / np.sqrt(cfg.D)
+    ref = oracle_attention_sample(q, kc, vc, lay.block_table, lay.seq_lens, scale, pairs)
+    o = to_np(out)
+    worst = 0.0
+    for (b, h), r in ref.items():
+        worst = max(worst, float(np.max(np.abs(o[b, :, h] - r))))
+    assert np.isfinite(o).all()
+    assert worst <= TOL[cfg.dtype], worst
+    assert worst <= TIGHT[cfg.dtype], worst
+    return worst
+
+
+def _all_pairs(cfg):
+    return [(b, h) for b in range(cfg.B) for h in range(cfg.Hq)]
+
+
+def test_cfg0_fp32_full():
+    cfg = W.baseline_config(0)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
+def test_fp32_ragged_multi_chunk_and_d128():
+    cfg = W.scaled(W.baseline_config(0), B=3, Hq=4, Hkv=2, D=128, page=16, k=6, kv_mode="ragged",
+                   kv_len=(7, 900), permute_pages=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
+BF16_SMALL = [
+    # several tiles per wavefront, ragged tails, every packed-row tile count, both head dims
+    dict(B=3, Hq=8, Hkv=2, D=128, k=8, kv_mode="ragged", kv_len=(9, 3000), permute_pages=True),     # 36 rows
+    dict(B=2, Hq=4, Hkv=4, D=128, k=3, kv_mode="ragged", kv_len=(4, 700), permute_pages=True),      # 4 rows
+    dict(B=2, Hq=8, Hkv=4, D=128, k=8, kv_mode="fixed", kv_len=(1024, 1024)),                       # 18 rows
+    dict(B=2, Hq=16, Hkv=2, D=128, k=16, kv_mode="ragged", kv_len=(17, 2500), permute_pages=True),  # 136 rows
+    dict(B=2, Hq=10, Hkv=2, D=128, k=8, kv_mode="shared_prefix", kv_len=(40, 500), prefix_len=1024),  # 45 rows
+    dict(B=2, Hq=8, Hkv=2, D=64, k=8, kv_mode="ragged", kv_len=(9, 2000), permute_pages=True, page=32),
+]
+
+
+@pytest.mark.parametrize("vmode", [0, 1])
+@pytest.mark.parametrize("case", range(len(BF16_SMALL)))
+def test_bf16_small_all_heads(case, vmode):
+    cfg = W.scaled(W.baseline_config(1), **BF16_SMALL[case])
+    print(f"attn bf16 case {case} vmode {vmode}: {BF16_SMALL[case]}", flush=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    A.agentsam_set_option("attn_v_mode", vmode)
+    try:
+        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+        torch.cuda.synchronize()
+    finally:
+        A.agentsam_set_option("attn_v_mode", 0)
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
+def test_bf16_minimum_and_boundary_lengths():
+    """seq_len == R (every row sees only the new positions), lengths around tile / page / chunk edges."""
+    base = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=2, D=128, k=8)
+    A.agentsam_set_option("attn_kv_chunk", 128)
+    try:
+        for S in (9, 10, 31, 32, 33, 64, 65, 127, 128, 129, 130, 136, 137, 255, 257, 384 + 5):
+            cfg = W.scaled(base, kv_len=(S, S), seed=1000 + S)
+            lay, q, kc, vc, bt, seq = _inputs(cfg)
+            out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+            torch.cuda.synchronize()
+            _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+    finally:
+        A.agentsam_set_option("attn_kv_chunk", 0)
+
+
+def test_split_and_page_permutation_invariance():
+    cfg = W.scaled(W.baseline_config(1), B=2, Hq=8, Hkv=2, D=128, k=8, kv_mode="ragged", kv_len=(1500, 4000))
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    scale = 1.0 / np.sqrt(cfg.D)
+    outs = []
+    for chunk in (0, 128, 512, 1024, 4096):
+        A.agentsam_set_option("attn_kv_chunk", chunk)
+        try:
+            outs.append(to_np(A.spec_verify_attn(q, kc, vc, bt, seq, scale)))
+        finally:
+            A.agentsam_set_option("attn_kv_chunk", 0)
+    for o in outs[1:]:
+        assert np.max(np.abs(o - outs[0])) < 2e-4        # only the fp32 summation order changes
+    # move the pages around physically (same logical content): results must not change at all
+    perm = torch.randperm(lay.num_pages, device=DEV)
+    inv = torch.empty_like(perm); inv[perm] = torch.arange(lay.num_pages, device=DEV)
+    kc2, vc2 = kc[perm].contiguous(), vc[perm].contiguous()
+    bt2 = torch.where(bt >= 0, inv[bt.clamp(min=0).long()].int(), bt)
+    o2 = to_np(A.spec_verify_attn(q, kc2, vc2, bt2, seq, scale))
+    assert np.array_equal(o2, outs[0])
+
+
+def test_bad_page_id_reads_zeros_and_bf16_output():
+    cfg = W.scaled(W.baseline_config(1), B=2, Hq=8, Hkv=2, D=128, k=8, kv_len=(640, 640))
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    scale = 1.0 / np.sqrt(cfg.D)
+    bt_bad = bt.clone(); bt_bad[0, 3] = lay.num_pages + 7; bt_bad[1, 2] = -5
+    out = A.spec_verify_attn(q, kc, vc, bt_bad, seq, scale)
+    # the same thing with real pages of zeros
+    kc2 = torch.cat([kc, torch.zeros_like(kc[:1])]); vc2 = torch.cat([vc, torch.zeros_like(vc[:1])])
+    bt_z = bt.clone(); bt_z[0, 3] = lay.num_pages; bt_z[1, 2] = lay.num_pages
+    ref = A.spec_verify_attn(q, kc2, vc2, bt_z, seq, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+    ob = A.spec_verify_attn(q, kc, vc, bt, seq, scale, out_dtype=torch.bfloat16)
+    of = A.spec_verify_attn(q, kc, vc, bt, seq, scale)
+    torch.cuda.synchronize()
+    assert ob.dtype == torch.bfloat16 and torch.equal(ob, of.to(torch.bfloat16))
+
+
+def test_error_returns_on_device_arguments():
+    cfg = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=2, D=128, k=8, kv_len=(20000, 20000))
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    tiny = torch.empty(4, device=DEV)
+    from paper_2512_18337_amd import binding
+    rc = binding.lib().spec_verify_attn(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), bt.data_ptr(), bt.shape[1],
+                                        seq.data_ptr(), 1, 9, 8, 2, 128, 64, lay.num_pages, 0.1, 1, 0,
+                                        q.data_ptr(), tiny.data_ptr(), 16, None)
+    assert rc == -4
+
+
+@pytest.mark.parametrize("i", [1, 2, 3, 4])
+def test_full_size_sampled_heads(i):
+    """Baseline shapes in the launch configuration the benchmark times; the oracle checks a seeded
+    sample of (session, head) pairs, every row of each."""
+    cfg = W.baseline_config(i)
+    print(f"attn full-size {cfg.name}", flush=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(cfg.seed)
+    order = np.argsort(lay.seq_lens)
+    bs = {int(order[0]), int(order[-1]), int(rng.integers(0, cfg.B))}      # shortest, longest, one more
+    pairs = [(b, int(h)) for b in sorted(bs) for h in rng.choice(cfg.Hq, 2, replace=False)]
+    worst = _check(cfg, lay, q, kc, vc, out, pairs)
+    print(f"  max-abs error {worst:.3e} on {pairs}", flush=True)
+    assert torch.isfinite(out).all()
