@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     const int kvh = blockIdx.y / p.n_rg;
     const int rg = blockIdx.y % p.n_rg;
     const int b = blockIdx.z;
-    const int S = p.seq[b];
+    const int S = min(p.seq[b], p.max_pages * p.P);      // never index past the block table
     const int c0 = chunk * p.chunk;
     if (c0 >= S) return;                                     // uniform over the workgroup
     const int c1 = min(S, c0 + p.chunk);
@@ -266,9 +266,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
         for (int dt = 0; dt < D / 16; ++dt) {
             bf16x8 vf;
             if (VMODE == 1) {
-                // LDS transpose read: 4 lanes each fetch 4 consecutive d of one position and get back
-                // 4 consecutive positions of one d
-                const int bq = n >> 2, jq = n & 3;
+                // LDS transpose read (per 16 lanes): lane r supplies the 8-byte chunk (position r/4,
+                // d-chunk r%4); lane i receives element i%4 of the chunks of lanes i/4, 4+i/4, 8+i/4,
+                // 12+i/4, i.e. d = 16*dt + i at 4 consecutive positions
+                const int bq = n & 3, jq = n >> 2;
                 const char *a0 = Vs + (4 * g + jq) * C::kVStr + (dt * 16 + 4 * bq) * 2;
                 const char *a1 = a0 + 16 * C::kVStr;
                 s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnParams p, int heads_outer, int G_eff) {
     const int ho = blockIdx.x, b = blockIdx.y;
-    const int S = p.seq[b];
+    const int S = min(p.seq[b], p.max_pages * p.P);      // never index past the block table
     const int nchunks_b = (S + p.chunk - 1) / p.chunk;
     if (nchunks_b <= 1) return;
     const int rows = G_eff * p.R;
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p) {
     __shared__ float row_m[kF32MaxR], row_l[kF32MaxR];
 
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int S = p.seq[b];
+    const int S = min(p.seq[b], p.max_pages * p.P);      // never index past the block table
     const int c0 = chunk * p.chunk;
     if (c0 >= S) return;
     const int c1 = min(S, c0 + p.chunk);
