@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of one AgentSAM speculative step on one MI355X.
+
+A step = sam_draft + spec_verify_attn + spec_accept back to back on one stream over one batch
+of synthetic sessions (inputs resident in HBM before the timed region).  The default workload
+is the configuration the headline metric is quoted on: B=64 sessions, 32k-token KV per session,
+k=8 drafts (baseline workload 2).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+
+# HBM bytes of one spec_verify_attn launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE
+# runs, scaled by a copy kernel of known size); see profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="baseline workload index (default: the headline one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-only", action="store_true", help="time only spec_verify_attn (for profiling)")
+    ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
+                    help="override a workload field (experiments only), e.g. --set permute_pages=False")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h, budget_s=20.0):
+    """The CPU oracle as it stands, timed on this machine's host cores on a bounded sample of the step."""
+    import torch
+    from oracle import accept_oracle, attention_oracle_head, draft_oracle_batch
+    from oracle.attention import gather_kv
+    cpu0, wall0 = time.process_time(), time.perf_counter()
+    # draft lookup: every session
+    T = np.concatenate(mems)
+    if cfg.sam_mode == "per_session":
+        sizes = np.array([len(m) for m in mems], dtype=np.int64)
+        begin = np.concatenate([[0], np.cumsum(sizes)[:-1]]); end = begin + sizes
+    else:
+        begin = np.zeros(cfg.B, dtype=np.int64); end = np.full(cfg.B, len(T), dtype=np.int64)
+    t0 = time.perf_counter()
+    draft_oracle_batch(T, begin, end, recent, rlen, cfg.k, cfg.sep)
+    t_draft = time.perf_counter() - t0
+    # accept: every row
+    lg = logits.float().cpu().numpy()
+    t0 = time.perf_counter()
+    accept_oracle(lg, draft_h, nd_h)
+    t_accept = time.perf_counter() - t0
+    # attention: seeded sample of (session, head) pairs, every row of each; extrapolated linearly
+    rng = np.random.default_rng(cfg.seed)
+    scale = 1.0 / np.sqrt(cfg.D)
+    P = cfg.page
+    done, t_attn, pos_done = 0, 0.0, 0
+    total_pos = int(lay.seq_lens.astype(np.int64).sum()) * cfg.Hq
+    while t_attn < budget_s and done < cfg.B * cfg.Hq:
+        b = int(rng.integers(0, cfg.B)); h = int(rng.integers(0, cfg.Hq))
+        S = int(lay.seq_lens[b]); npg = (S + P - 1) // P
+        pages = torch.as_tensor(lay.block_table[b, :npg].astype(np.int64), device=kc.device)
+        g = h // cfg.G
+        Kp = kc[pages, g].float().cpu().numpy()[:, None]          # [npg,1,P,D] page-shaped host copy
+        Vp = vc[pages, g].float().cpu().numpy()[:, None]
+        qh = q[b, :, h].float().cpu().numpy()
+        ident = np.arange(npg)
+        t0 = time.perf_counter()
+        K = gather_kv(Kp, ident, S, 0); V = gather_kv(Vp, ident, S, 0)
+        attention_oracle_head(qh, K, V, scale)
+        t_attn += time.perf_counter() - t0
+        done += 1; pos_done += S
+    t_attn_full = t_attn * total_pos / max(1, pos_done)
+    cpu1, wall1 = time.process_time(), time.perf_counter()
+    t_step = t_draft + t_attn_full + t_accept
+    cores = max(1, int(round((cpu1 - cpu0) / max(1e-9, wall1 - wall0))))
+    return {
+        "value": cfg.B * cfg.k / t_step, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+        "sample": (f"draft oracle on all {cfg.B} sessions ({t_draft:.3f} s) + accept oracle on all "
+                   f"{cfg.B * cfg.R} rows ({t_accept:.3f} s) + fp64 attention oracle on {done} seeded "
+                   f"(session, head) pairs of {cfg.B * cfg.Hq} ({t_attn:.1f} s, extrapolated linearly by "
+                   f"KV positions to {t_attn_full:.1f} s)"),
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is design-only.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2512_18337_amd as A
+    from paper_2512_18337_amd import workloads as W
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = W.baseline_config(args.config)
+    if args.set:
+        import ast
+        cfg = W.scaled(cfg, name=cfg.name + "+" + ",".join(args.set),
+                       **{kv.split("=")[0]: ast.literal_eval(kv.split("=", 1)[1]) for kv in args.set})
+    if args.kv_chunk:
+        A.agentsam_set_option("attn_kv_chunk", args.kv_chunk)
+
+    # ---- inputs (all resident in HBM before timing)
+    nmem = cfg.B if cfg.sam_mode == "per_session" else 1
+    mems = [W.token_memory(cfg, i) for i in range(nmem)]
+    t0 = time.perf_counter()
+    sams = [A.sam_build(m, cfg.sep) for m in mems]
+    t_build = time.perf_counter() - t0
+    flat = A.sam_flatten(sams)
+    fd = flat.to(dev)
+    idx = np.arange(cfg.B) if nmem > 1 else np.zeros(cfg.B, dtype=np.int64)
+    recent, rlen = W.recent_windows(cfg, mems)
+    root_d = torch.as_tensor(flat.roots[idx], device=dev)
+    cend_d = torch.as_tensor(flat.corpus_end[idx], device=dev)
+    recent_d = torch.as_tensor(recent, device=dev)
+    rlen_d = torch.as_tensor(rlen, device=dev)
+    lay = W.kv_layout(cfg)
+    q, kc, vc = W.kv_and_queries(cfg, lay, dev)
+    bt = torch.as_tensor(lay.block_table, device=dev)
+    seq = torch.as_tensor(lay.seq_lens, device=dev)
+    scale = 1.0 / float(np.sqrt(cfg.D))
+    ws_bytes = A.spec_verify_attn_workspace(cfg.B, cfg.R, cfg.Hq, cfg.Hkv, cfg.D, cfg.page, bt.shape[1],
+                                            A.BF16 if cfg.dtype == "bf16" else A.F32)
+    ws = torch.empty(max(ws_bytes, 16) // 4 + 1, dtype=torch.float32, device=dev)
+    out = torch.empty((cfg.B, cfg.R, cfg.Hq, cfg.D), dtype=torch.float32, device=dev)
+
+    # the logits stand in for the LM head: built once from the library's own drafts
+    draft, n_draft, _, _ = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
+    torch.cuda.synchronize()
+    draft_h, nd_h = draft.cpu().numpy(), n_draft.cpu().numpy()
+    logits = W.verify_logits(cfg, draft_h, nd_h, dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(events=None):
+        if not args.attn_only:
+            if events: events[0].record()
+            d, nd, ml, me = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
+        if events: events[1].record()
+        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)
+        if events: events[2].record()
+        if not args.attn_only:
+            res = A.spec_accept(logits, d, nd)
+            if events: events[3].record()
+            return res
+        return None
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        res = step(evs[i])
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    ms_step = t_total / args.steps * 1e3
+
+    t_attn = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))             # ms, whole call
+    if args.attn_only:
+        t_draft = t_accept = 0.0
+        accept_len = np.zeros(cfg.B, dtype=np.int32)
+    else:
+        t_draft = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+        t_accept = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+        accept_len = res[0].cpu().numpy()
+
+    kv_elem = 2 if cfg.dtype == "bf16" else 4
+    alg_bytes = float(lay.seq_lens.astype(np.int64).sum()) * cfg.Hkv * 2 * cfg.D * kv_elem
+    achieved = alg_bytes / (t_attn * 1e-3) / 1e9
+    result = {
+        "metric": "verified tokens/s/GPU (B=64, 32k ctx, k=8); verify-attn HBM GB/s % of peak",
+        "value": cfg.B * cfg.k / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "head_dim": cfg.D,
+                   "kv_len": [int(lay.seq_lens.min()), int(lay.seq_lens.max())], "page": cfg.page, "k": cfg.k,
+                   "sam_tokens": int(sum(len(m) for m in mems)), "vocab": cfg.vocab,
+                   "step": "sam_draft + spec_verify_attn + spec_accept", "attn_only": bool(args.attn_only)},
+        "roofline": {"bound": "hbm", "kernel": "spec_verify_attn", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "algorithmic_bytes": alg_bytes,
+                     "launch_ms": t_attn},
+        "detail": {"t_draft_us": t_draft * 1e3, "t_attn_us": t_attn * 1e3, "t_accept_us": t_accept * 1e3,
+                   "sessions_per_s_sam_draft": (cfg.B / (t_draft * 1e-3)) if t_draft else None,
+                   "accepted_tokens_per_s": float((accept_len + 1).sum()) / (ms_step * 1e-3),
+                   "synthetic_OTE": float((accept_len + 1).mean()),
+                   "synthetic_SHR": (float(accept_len[nd_h > 0].sum()) / float(cfg.k * max(1, (nd_h > 0).sum()))),
+                   "accept_hbm_GBs": (logits.numel() * logits.element_size() / (t_accept * 1e-3) / 1e9)
+                   if t_accept else None,
+                   "sam_build_tokens_per_s": sum(len(m) for m in mems) / t_build,
+                   "attn_workspace_bytes": ws_bytes},
+    }
+    if not args.no_cpu_baseline and not args.attn_only:
+        result["cpu_baseline"] = cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -6,7 +6,7 @@
 
 namespace agentsam {
 static std::atomic<int64_t> g_attn_kv_chunk{0};
-static std::atomic<int64_t> g_attn_v_mode{0};
+static std::atomic<int64_t> g_attn_v_mode{1};
 int64_t option_attn_kv_chunk() { return g_attn_kv_chunk.load(std::memory_order_relaxed); }
 int64_t option_attn_v_mode() { return g_attn_v_mode.load(std::memory_order_relaxed); }
 }  // namespace agentsam

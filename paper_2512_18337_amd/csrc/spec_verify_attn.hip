@@ -35,12 +35,14 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;          // finite stand-in for -inf in running maxima
 constexpr int kTile = 32;                    // KV positions per wavefront step
 constexpr int kWaves = 4;
-constexpr int kRowsPerGroup = 48;            // 3 MFMA row tiles of 16 per wavefront
+constexpr int kRowsPerGroup = 48;            // packed rows one wavefront can hold (3 MFMA row tiles of 16)
 constexpr int kF32Chunk = 256;               // KV positions per workgroup of the fp32 kernel
 constexpr int kF32MaxR = 32;
 
@@ -50,12 +52,12 @@ struct AttnParams {
     void *out;
     float *ws;
     int B, R, Hq, Hkv, G, P, max_pages;
+    int log2P;               // log2(P) when P is a power of two, else -1
     int64_t num_pages;
     float scale_log2;        // scale * log2(e)
     int chunk;               // KV positions per workgroup
     int nchunks_max;         // grid extent over chunks
     int rows;                // G*R packed rows per kv head
-    int n_rg;                // row groups of kRowsPerGroup rows
     int rows_pad;            // rows per workspace record
     int out_bf16;
 };
@@ -74,18 +76,17 @@ __device__ __forceinline__ void store_out(void *out, int64_t idx, float4 v, int 
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA kernel
+// bf16 MFMA kernels
 // ------------------------------------------------------------------------------------------
 template <int D>
 struct Bf16Cfg {
     static constexpr int kKStr = D * 2 + 16;                 // LDS row strides in bytes (padded against
     static constexpr int kVStr = D * 2 + 32;                 // bank conflicts of the two read patterns)
-    static constexpr int kWaveBytes = kTile * (kKStr + kVStr);
+    static constexpr int kTileBytes = kTile * (kKStr + kVStr);
     static constexpr int kOStr = D + 4;                      // floats
-    static constexpr int kStageBytes = kWaves * kWaveBytes;
-    static constexpr int kMergeBytes = kRowsPerGroup * kOStr * 4;
-    static constexpr int kSmemBytes = (kStageBytes > kMergeBytes ? kStageBytes : kMergeBytes);
     static constexpr int kLoads = D / 16;                    // 16-byte loads per lane per tile, for K and for V
+    static constexpr int kLanesPerRow = D / 8;
+    static constexpr int kRowsPerLoad = 64 / kLanesPerRow;
 };
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -95,18 +96,268 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int D, int MT, int VMODE>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
+__device__ __forceinline__ uint4 ld_stream(const void *ptr) {
+    // K/V are read exactly once per launch: keep them from displacing reusable lines
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)ptr);
+    return uint4{v[0], v[1], v[2], v[3]};
+}
+
+// Per-wavefront state: the packed query rows [row0, row_end) of one kv head, their running softmax
+// statistics and the transposed output accumulators.
+template <int D, int MT>
+struct WaveState {
+    bf16x8 qf[MT][D / 32];       // B operand of S^T = K.Q^T: column n = packed row, 8 consecutive d per lane
+    int irow[MT];                // query row (0..R-1) of this lane's column, per row tile
+    f32x4 oacc[D / 16][MT];      // O^T[d = 16*dt + 4g + r][row = 16*rt + n]
+    float m_run[MT];             // reference maximum (base-2 domain), identical in the 4 lanes of a column
+    float l_part[MT];            // this lane's share of the row sum
+};
+
+template <int D, int MT>
+__device__ __forceinline__ void init_state(WaveState<D, MT> &w, const AttnParams &p, int b, int kvh,
+                                           int row0, int row_end, int n, int g) {
+    const __hip_bfloat16 *qg = (const __hip_bfloat16 *)p.q;
+    const int R = p.R;
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt) {
+        const int pr = row0 + rt * 16 + n;
+        const bool live = pr < row_end;
+        const int hh = live ? pr / R : 0;
+        const int i = live ? pr % R : R - 1;
+        w.irow[rt] = i;
+        const __hip_bfloat16 *src = qg + (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D;
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) {
+            s16x8 raw = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (live) raw = *(const s16x8 *)(src + ks * 32 + g * 8);
+            w.qf[rt][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
+        w.m_run[rt] = kNegBig;
+        w.l_part[rt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) w.oacc[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+// max over the 4 lanes {n, n+16, n+32, n+48} that hold one packed row, result in all 4
+__device__ __forceinline__ float row_max4(float x) {
+    // v_permlane32_swap exchanges the upper half of the first operand with the lower half of the
+    // second; with both operands equal the two results are x[l%32] and x[32 + l%32] in every lane.
+    // v_permlane16_swap does the same for odd/even rows of 16 lanes.
+    const unsigned xi = __float_as_uint(x);
+    const u32x2 a = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    const float m = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const unsigned mi = __float_as_uint(m);
+    const u32x2 c = __builtin_amdgcn_permlane16_swap(mi, mi, false, false);
+    return fmaxf(__uint_as_float(c[0]), __uint_as_float(c[1]));
+}
+
+// S^T = K . Q^T for one 32-position tile: two 16-position tiles x MT row tiles
+template <int D, int MT>
+__device__ __forceinline__ void s_mfma(const WaveState<D, MT> &w, const char *Ks, f32x4 (&sacc)[2][MT], int n, int g) {
     using C = Bf16Cfg<D>;
-    __shared__ __align__(16) char smem[C::kSmemBytes];
+#pragma unroll
+    for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+        for (int rt = 0; rt < MT; ++rt) sacc[pt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) {
+        bf16x8 kf[2];
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt)
+            kf[pt] = *(const bf16x8 *)(Ks + (pt * 16 + n) * C::kKStr + (ks * 32 + g * 8) * 2);
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+            for (int rt = 0; rt < MT; ++rt)
+                sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
+    }
+}
+
+// Online softmax, part 1: bring the scores into the base-2 domain (masked ones to -inf) and find the
+// row maxima.  Returns whether some row's maximum exceeds its reference by more than kSlack.
+// The reference only moves in that case: any reference gives the same result after normalisation,
+// weights stay below 2^kSlack, and the accumulators are rescaled a handful of times per wavefront
+// instead of once per tile.
+template <int D, int MT, bool MASK>
+__device__ __forceinline__ bool softmax_max(const WaveState<D, MT> &w, f32x4 (&sacc)[2][MT], float (&mx)[MT],
+                                            int pos0, int S, int R, float c, int g) {
+    constexpr float kSlack = 8.0f;
+    bool move = false;
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt) {
+        if (MASK) {
+            const int limit = S - R + w.irow[rt];            // last visible position of this row
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int pos = pos0 + pt * 16 + 4 * g + r;
+                    sacc[pt][rt][r] = (pos <= limit) ? sacc[pt][rt][r] * c : -INFINITY;
+                }
+        }
+        float m = fmaxf(fmaxf(sacc[0][rt][0], sacc[0][rt][1]), fmaxf(sacc[0][rt][2], sacc[0][rt][3]));
+        m = fmaxf(m, fmaxf(fmaxf(sacc[1][rt][0], sacc[1][rt][1]), fmaxf(sacc[1][rt][2], sacc[1][rt][3])));
+        m = row_max4(m);
+        mx[rt] = MASK ? m : m * c;                           // c > 0
+        move = move || (mx[rt] > w.m_run[rt] + kSlack);
+    }
+    return __builtin_amdgcn_ballot_w64(move) != 0;           // uniform over the wavefront, rarely true
+}
+
+// Move the reference maxima to max(old, mx) and rescale sums and accumulators accordingly.
+template <int D, int MT>
+__device__ __forceinline__ void rescale(WaveState<D, MT> &w, const float (&mx)[MT]) {
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt) {
+        const float m_new = fmaxf(w.m_run[rt], mx[rt]);
+        const float alpha = __builtin_amdgcn_exp2f(w.m_run[rt] - m_new);
+        w.m_run[rt] = m_new;
+        w.l_part[rt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) w.oacc[dt][rt] *= alpha;
+    }
+}
+
+// Online softmax, part 2: weights 2^(s*c - m), their row sums, and the bf16 B operand of the
+// second contraction (k-slot 8g+j <-> position j<4 ? 4g+j : 16+4g+j-4).
+template <int D, int MT, bool MASK>
+__device__ __forceinline__ void softmax_exp(WaveState<D, MT> &w, const f32x4 (&sacc)[2][MT], float c,
+                                            bf16x8 (&pf)[MT]) {
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt) {
+        const float mref = w.m_run[rt];
+        float psum = 0.f;
+        bf16x8 pk;
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float e = MASK ? __builtin_amdgcn_exp2f(sacc[pt][rt][r] - mref)   // -inf -> 0
+                                     : __builtin_amdgcn_exp2f(fmaf(sacc[pt][rt][r], c, -mref));
+                psum += e;
+                pk[pt * 4 + r] = (__bf16)e;
+            }
+        w.l_part[rt] += psum;
+        pf[rt] = pk;
+    }
+}
+
+// O^T += V^T . P^T for one tile
+template <int D, int MT, int VMODE>
+__device__ __forceinline__ void pv_mfma(WaveState<D, MT> &w, const char *Vs, const bf16x8 (&pf)[MT], int n, int g) {
+    using C = Bf16Cfg<D>;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+        bf16x8 vf;
+        if (VMODE == 1) {
+            // LDS transpose read (per 16 lanes): lane r supplies the 8-byte chunk (position r/4,
+            // d-chunk r%4); lane i receives element i%4 of the chunks of lanes i/4, 4+i/4, 8+i/4,
+            // 12+i/4, i.e. d = 16*dt + i at 4 consecutive positions
+            const int bq = n & 3, jq = n >> 2;
+            const char *a0 = Vs + (4 * g + jq) * C::kVStr + (dt * 16 + 4 * bq) * 2;
+            const char *a1 = a0 + 16 * C::kVStr;
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a1);
+            s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            vf = __builtin_bit_cast(bf16x8, cat);
+        } else {
+            s16x8 cat;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int pos = (j < 4) ? (4 * g + j) : (16 + 4 * g + j - 4);
+                cat[j] = *(const short *)(Vs + pos * C::kVStr + (dt * 16 + n) * 2);
+            }
+            vf = __builtin_bit_cast(bf16x8, cat);
+        }
+#pragma unroll
+        for (int rt = 0; rt < MT; ++rt)
+            w.oacc[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], w.oacc[dt][rt], 0, 0, 0);
+    }
+}
+
+// One 32-position tile (K at Ks, V at Vs in LDS) against the wavefront's rows, start to finish.
+template <int D, int MT, int VMODE>
+__device__ __forceinline__ void compute_tile(WaveState<D, MT> &w, const char *Ks, const char *Vs, int pos0,
+                                             int S, int R, float c /* scale*log2e */, int n, int g) {
+    f32x4 sacc[2][MT];
+    bf16x8 pf[MT];
+    s_mfma<D, MT>(w, Ks, sacc, n, g);
+    float mx[MT];
+    const bool mask = pos0 + kTile > S - R;                  // tile touches the new rows or the ragged end
+    const bool move = mask ? softmax_max<D, MT, true>(w, sacc, mx, pos0, S, R, c, g)
+                           : softmax_max<D, MT, false>(w, sacc, mx, pos0, S, R, c, g);
+    if (move) rescale<D, MT>(w, mx);
+    if (mask) softmax_exp<D, MT, true>(w, sacc, c, pf);
+    else softmax_exp<D, MT, false>(w, sacc, c, pf);
+    pv_mfma<D, MT, VMODE>(w, Vs, pf, n, g);
+}
+
+// The page ids of one chunk, fetched once at kernel start (lane i of register r holds the id of the
+// chunk's page 64*r + i) and handed out with v_readlane: the tile loop never waits on a block-table
+// load, and no vector load of its own sits between the streaming loads whose completion it counts.
+constexpr int kPageRegs = 4;                                 // up to 256 pages per chunk
+struct ChunkPages {
+    int r0, r1, r2, r3;          // named members, not an array: an indexable private array would be
+    int first_page;              // demoted to LDS by the compiler
+};
+
+__device__ __forceinline__ ChunkPages load_chunk_pages(const AttnParams &p, int b, int c0, int c1, int lane) {
+    ChunkPages cp;
+    cp.first_page = p.log2P >= 0 ? (c0 >> p.log2P) : (c0 / p.P);
+    const int last_page = p.log2P >= 0 ? ((c1 - 1) >> p.log2P) : ((c1 - 1) / p.P);
+    const int npages = last_page - cp.first_page + 1;
+    const int32_t *row = p.bt + (int64_t)b * p.max_pages + cp.first_page;
+    cp.r0 = (lane < npages) ? row[lane] : -1;
+    cp.r1 = (64 + lane < npages) ? row[64 + lane] : -1;
+    cp.r2 = (128 + lane < npages) ? row[128 + lane] : -1;
+    cp.r3 = (192 + lane < npages) ? row[192 + lane] : -1;
+    return cp;
+}
+
+// Start of a tile's first row in the K and V caches, and whether its page id is usable.
+template <int D>
+struct TileSrc {
+    const __hip_bfloat16 *kbase, *vbase;
+    int pos0;
+    bool page_ok;
+};
+
+template <int D>
+__device__ __forceinline__ TileSrc<D> tile_src(const AttnParams &p, const ChunkPages &cp, int kvh, int pos0) {
+    TileSrc<D> t;
+    const int pidx = p.log2P >= 0 ? (pos0 >> p.log2P) : (pos0 / p.P);
+    const int slot = pos0 - pidx * p.P;
+    const int lp = pidx - cp.first_page;                     // uniform over the wavefront
+    const int sel = lp >> 6;
+    const int v = sel == 0 ? cp.r0 : sel == 1 ? cp.r1 : sel == 2 ? cp.r2 : cp.r3;
+    const int page = __builtin_amdgcn_readlane(v, lp & 63);
+    t.page_ok = page >= 0 && (int64_t)page < p.num_pages;
+    const int64_t base = (((int64_t)(t.page_ok ? page : 0) * p.Hkv + kvh) * p.P + slot) * D;
+    t.kbase = (const __hip_bfloat16 *)p.kc + base;
+    t.vbase = (const __hip_bfloat16 *)p.vc + base;
+    t.pos0 = pos0;
+    return t;
+}
+
+// -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the chunk
+template <int D, int MT, int VMODE>
+__global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams p) {
+    using C = Bf16Cfg<D>;
+    constexpr int kStage = kWaves * C::kTileBytes;
+    constexpr int kMerge = kRowsPerGroup * C::kOStr * 4;
+    __shared__ __align__(16) char smem[kStage > kMerge ? kStage : kMerge];
     __shared__ float red_m[kWaves * kRowsPerGroup];
     __shared__ float red_l[kWaves * kRowsPerGroup];
 
-    const int chunk = blockIdx.x;
-    const int kvh = blockIdx.y / p.n_rg;
-    const int rg = blockIdx.y % p.n_rg;
-    const int b = blockIdx.z;
-    const int S = min(p.seq[b], p.max_pages * p.P);      // never index past the block table
+    // 1-D grid, kv head fastest and chunk slowest.  Workgroups are handed to the 8 XCDs round-robin,
+    // so with 8 kv heads every XCD streams one kv head of every session: the load is balanced
+    // whatever the length distribution, and sessions that share the pages of a (kv head, chunk)
+    // (a common prefix) run back to back on the same XCD and meet in its L2.
+    const int kvh = blockIdx.x % p.Hkv;
+    const int b = (blockIdx.x / p.Hkv) % p.B;
+    const int chunk = blockIdx.x / (p.B * p.Hkv);
+    const int S = min(p.seq[b], p.max_pages * p.P);          // never index past the block table
     const int c0 = chunk * p.chunk;
     if (c0 >= S) return;                                     // uniform over the workgroup
     const int c1 = min(S, c0 + p.chunk);
@@ -114,189 +365,66 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     const int nchunks_b = (S + p.chunk - 1) / p.chunk;
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6;
-    const int lane = tid & 63;
-    const int n = lane & 15;                                 // MFMA column / A-row index
-    const int g = lane >> 4;                                 // MFMA k-group
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
+    const int n = lane & 15, g = lane >> 4;
     const int R = p.R;
 
-    char *Ks = smem + wave * C::kWaveBytes;
+    char *Ks = smem + wave * C::kTileBytes;
     char *Vs = Ks + kTile * C::kKStr;
 
-    const __hip_bfloat16 *qg = (const __hip_bfloat16 *)p.q;
-    const __hip_bfloat16 *kg = (const __hip_bfloat16 *)p.kc;
-    const __hip_bfloat16 *vg = (const __hip_bfloat16 *)p.vc;
+    WaveState<D, MT> w;
+    init_state<D, MT>(w, p, b, kvh, 0, p.rows, n, g);
+    const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
 
-    // ---- Q fragments (B operand of S^T = K.Q^T): column n = packed row, 8 consecutive d per lane
-    bf16x8 qf[MT][D / 32];
-    int irow[MT];                                            // query row index (0..R-1) of this lane's column
-#pragma unroll
-    for (int rt = 0; rt < MT; ++rt) {
-        const int pr = rg * kRowsPerGroup + rt * 16 + n;
-        const bool live = pr < p.rows;
-        const int hh = live ? pr / R : 0;
-        const int i = live ? pr % R : R - 1;
-        irow[rt] = i;
-        const __hip_bfloat16 *src = qg + (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D;
-#pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) {
-            s16x8 raw = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (live) raw = *(const s16x8 *)(src + ks * 32 + g * 8);
-            qf[rt][ks] = __builtin_bit_cast(bf16x8, raw);
-        }
-    }
+    // tile loads: lane -> (row, 16-byte column); one instruction reads 1 KB contiguous.  Two tiles
+    // are kept in flight in registers while a third is being computed from LDS.
+    const int ld_row = lane / C::kLanesPerRow, ld_col = lane % C::kLanesPerRow;
+    uint4 kreg[2][C::kLoads], vreg[2][C::kLoads];
 
-    f32x4 oacc[D / 16][MT];
-#pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt)
-#pragma unroll
-        for (int rt = 0; rt < MT; ++rt) oacc[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run[MT], l_part[MT];
-#pragma unroll
-    for (int rt = 0; rt < MT; ++rt) { m_run[rt] = kNegBig; l_part[rt] = 0.f; }
-
-    // ---- tile loads: lane -> (row, 16-byte column) so that one instruction reads 1 KB contiguous
-    constexpr int kLanesPerRow = D / 8;
-    constexpr int kRowsPerLoad = 64 / kLanesPerRow;
-    const int ld_row = lane / kLanesPerRow;
-    const int ld_col = lane % kLanesPerRow;
-    uint4 kreg[C::kLoads], vreg[C::kLoads];
-
-    auto issue_loads = [&](int t) {
-        const int pos0 = c0 + t * kTile;
-        const int page = p.bt[(int64_t)b * p.max_pages + pos0 / p.P];
-        const bool page_ok = (unsigned)page < (unsigned long long)p.num_pages && page >= 0;
-        const int64_t base = (((int64_t)(page_ok ? page : 0) * p.Hkv + kvh) * p.P + (pos0 % p.P)) * D;
+    auto issue_loads = [&](int t, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
+        const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0 + t * kTile);
 #pragma unroll
         for (int i = 0; i < C::kLoads; ++i) {
-            const int row = i * kRowsPerLoad + ld_row;
-            const bool ok = page_ok && (pos0 + row < S);
-            const int64_t off = base + (int64_t)row * D + ld_col * 8;
-            kreg[i] = ok ? *(const uint4 *)(kg + off) : uint4{0u, 0u, 0u, 0u};
-            vreg[i] = ok ? *(const uint4 *)(vg + off) : uint4{0u, 0u, 0u, 0u};
+            const int row = i * C::kRowsPerLoad + ld_row;
+            const bool ok = src.page_ok && (src.pos0 + row < S);
+            const int off = row * D + ld_col * 8;
+            kr[i] = ok ? ld_stream(src.kbase + off) : uint4{0u, 0u, 0u, 0u};
+            vr[i] = ok ? ld_stream(src.vbase + off) : uint4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto stage = [&](const uint4 (&kr)[C::kLoads], const uint4 (&vr)[C::kLoads]) {
+#pragma unroll
+        for (int i = 0; i < C::kLoads; ++i) {
+            const int row = i * C::kRowsPerLoad + ld_row;
+            *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[i];
+            *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[i];
         }
     };
 
     int t = wave;
-    if (t < ntiles) issue_loads(t);
-    for (; t < ntiles; t += kWaves) {
-        // hand the prefetched tile to LDS
-#pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) {
-            const int row = i * kRowsPerLoad + ld_row;
-            *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kreg[i];
-            *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vreg[i];
-        }
+    if (t < ntiles) issue_loads(t, kreg[0], vreg[0]);
+    if (t + kWaves < ntiles) issue_loads(t + kWaves, kreg[1], vreg[1]);
+    while (t < ntiles) {
+        stage(kreg[0], vreg[0]);
         wave_lds_fence();
-        if (t + kWaves < ntiles) issue_loads(t + kWaves);
-
-        const int pos0 = c0 + t * kTile;
-
-        // ---- S^T = K . Q^T : two 16-position tiles x MT row tiles
-        f32x4 sacc[2][MT];
-#pragma unroll
-        for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-            for (int rt = 0; rt < MT; ++rt) sacc[pt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) {
-            bf16x8 kf[2];
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
-                kf[pt] = *(const bf16x8 *)(Ks + (pt * 16 + n) * C::kKStr + (ks * 32 + g * 8) * 2);
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                for (int rt = 0; rt < MT; ++rt)
-                    sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], qf[rt][ks], sacc[pt][rt], 0, 0, 0);
-        }
-
-        // ---- online softmax; lane holds, for column n of each row tile, positions pt*16 + 4g + r
-        const bool need_mask = pos0 + kTile > S - R;         // tile touches the new rows or the ragged end
-        bf16x8 pf[MT];
-#pragma unroll
-        for (int rt = 0; rt < MT; ++rt) {
-            float sv[8];
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) sv[pt * 4 + r] = sacc[pt][rt][r] * p.scale_log2;
-            bool allowed[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) allowed[j] = true;
-            if (need_mask) {
-                const int limit = S - R + irow[rt];          // last visible position of this row
-#pragma unroll
-                for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int pos = pos0 + pt * 16 + 4 * g + r;
-                        allowed[pt * 4 + r] = pos <= limit;
-                        if (!allowed[pt * 4 + r]) sv[pt * 4 + r] = kNegBig;
-                    }
-            }
-            float mx = sv[0];
-#pragma unroll
-            for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[rt], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
-            m_run[rt] = m_new;
-            float ps[8];
-            float psum = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                float e = __builtin_amdgcn_exp2f(sv[j] - m_new);
-                if (need_mask && !allowed[j]) e = 0.f;
-                ps[j] = e;
-                psum += e;
-            }
-            l_part[rt] = l_part[rt] * alpha + psum;
-            bf16x8 pk;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) pk[j] = (__bf16)ps[j];
-            pf[rt] = pk;
-#pragma unroll
-            for (int dt = 0; dt < D / 16; ++dt) oacc[dt][rt] *= alpha;
-        }
-
-        // ---- O^T += V^T . P^T ; k-slot 8g+j <-> position (j<4 ? 4g+j : 16+4g+j-4)
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-            bf16x8 vf;
-            if (VMODE == 1) {
-                // LDS transpose read (per 16 lanes): lane r supplies the 8-byte chunk (position r/4,
-                // d-chunk r%4); lane i receives element i%4 of the chunks of lanes i/4, 4+i/4, 8+i/4,
-                // 12+i/4, i.e. d = 16*dt + i at 4 consecutive positions
-                const int bq = n & 3, jq = n >> 2;
-                const char *a0 = Vs + (4 * g + jq) * C::kVStr + (dt * 16 + 4 * bq) * 2;
-                const char *a1 = a0 + 16 * C::kVStr;
-                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
-                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a1);
-                s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                vf = __builtin_bit_cast(bf16x8, cat);
-            } else {
-                s16x8 cat;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int pos = (j < 4) ? (4 * g + j) : (16 + 4 * g + j - 4);
-                    cat[j] = *(const short *)(Vs + pos * C::kVStr + (dt * 16 + n) * 2);
-                }
-                vf = __builtin_bit_cast(bf16x8, cat);
-            }
-#pragma unroll
-            for (int rt = 0; rt < MT; ++rt)
-                oacc[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], oacc[dt][rt], 0, 0, 0);
-        }
+        if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[0], vreg[0]);
+        compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
         wave_lds_fence();
+        t += kWaves;
+        if (t >= ntiles) break;
+        stage(kreg[1], vreg[1]);
+        wave_lds_fence();
+        if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[1], vreg[1]);
+        compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
+        wave_lds_fence();
+        t += kWaves;
     }
 
     // ---- merge the 4 wavefronts through LDS
     float l_tot[MT];
 #pragma unroll
     for (int rt = 0; rt < MT; ++rt) {
-        float l = l_part[rt];
+        float l = w.l_part[rt];
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
         l_tot[rt] = l;
@@ -305,7 +433,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     if (g == 0) {
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt) {
-            red_m[wave * kRowsPerGroup + rt * 16 + n] = m_run[rt];
+            red_m[wave * kRowsPerGroup + rt * 16 + n] = w.m_run[rt];
             red_l[wave * kRowsPerGroup + rt * 16 + n] = l_tot[rt];
         }
     }
@@ -316,45 +444,44 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
         const int row = rt * 16 + n;
         float M = red_m[row];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, red_m[w * kRowsPerGroup + row]);
+        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, red_m[ww * kRowsPerGroup + row]);
         float L = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w)
-            L += red_l[w * kRowsPerGroup + row] * __builtin_amdgcn_exp2f(red_m[w * kRowsPerGroup + row] - M);
+        for (int ww = 0; ww < kWaves; ++ww)
+            L += red_l[ww * kRowsPerGroup + row] * __builtin_amdgcn_exp2f(red_m[ww * kRowsPerGroup + row] - M);
         M_all[rt] = M;
         L_all[rt] = L;
-        my_scale[rt] = __builtin_amdgcn_exp2f(m_run[rt] - M);
+        my_scale[rt] = __builtin_amdgcn_exp2f(w.m_run[rt] - M);
     }
     float *Osum = (float *)smem;
-    for (int w = 0; w < kWaves; ++w) {
-        if (wave == w) {
+    for (int ww = 0; ww < kWaves; ++ww) {
+        if (wave == ww) {
 #pragma unroll
             for (int rt = 0; rt < MT; ++rt)
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) {
                     float4 *dst = (float4 *)(Osum + (rt * 16 + n) * C::kOStr + dt * 16 + 4 * g);
-                    const f32x4 a = oacc[dt][rt] * my_scale[rt];
+                    const f32x4 a = w.oacc[dt][rt] * my_scale[rt];
                     float4 v{a[0], a[1], a[2], a[3]};
-                    if (w > 0) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+                    if (ww > 0) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
                     *dst = v;
                 }
         }
         __syncthreads();
     }
-    // red_m/red_l of wavefront 0 now carry the merged maximum and sum (every wavefront computed the
-    // same values; reads of the per-wavefront entries finished before the barriers above)
+    // every wavefront computed the same merged maximum and sum; the per-wavefront entries were last
+    // read before the barriers above, so wavefront 0 may now overwrite its own with the merged values
     if (wave == 0 && g == 0) {
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt) { red_m[rt * 16 + n] = M_all[rt]; red_l[rt * 16 + n] = L_all[rt]; }
     }
     __syncthreads();
 
-    const int rows_here = min(MT * 16, p.rows - rg * kRowsPerGroup);
+    const int rows_here = p.rows;
     if (nchunks_b == 1) {
         for (int idx = tid; idx < rows_here * (D / 4); idx += 256) {
             const int row = idx / (D / 4), c4 = idx % (D / 4);
-            const int pr = rg * kRowsPerGroup + row;
-            const int hh = pr / R, i = pr % R;
+            const int hh = row / R, i = row % R;
             const float inv = 1.0f / red_l[row];
             float4 v = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
             v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
@@ -368,12 +495,323 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
         float *wl = wm + p.rows_pad;
         for (int idx = tid; idx < rows_here * (D / 4); idx += 256) {
             const int row = idx / (D / 4), c4 = idx % (D / 4);
-            const int pr = rg * kRowsPerGroup + row;
-            *(float4 *)(wo + (int64_t)pr * D + c4 * 4) = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
+            *(float4 *)(wo + (int64_t)row * D + c4 * 4) = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
         }
-        if (tid < rows_here) {
-            wm[rg * kRowsPerGroup + tid] = red_m[tid];
-            wl[rg * kRowsPerGroup + tid] = red_l[tid];
+        if (tid < rows_here) { wm[tid] = red_m[tid]; wl[tid] = red_l[tid]; }
+    }
+}
+
+// -------- wide kernel: 49..192 packed rows; the 4 wavefronts take different rows of the SAME tile.
+//
+// With this many rows per K/V byte the MFMA and softmax arithmetic are no longer negligible next to
+// the memory stream, and there are no registers to spare for staging, so:
+//   - tiles go from global memory straight into a ring of NS LDS slots (global_load_lds_dwordx4:
+//     lane i's 16 bytes land at slot base + 16*i), each wavefront fetching a quarter of every tile;
+//     NS-2 tiles are in flight while two are being consumed;
+//   - rows are stored unpadded (256 B for D=128), so the 16-byte chunks of a row are XOR-swizzled
+//     with the row index on the way in (the lane picks which global chunk it fetches) to keep the
+//     column-wise fragment reads off a single bank;
+//   - the loop is software-pipelined inside a wavefront: the S^T contraction of tile t+1 is issued
+//     before the softmax of tile t, so the matrix pipe works while the vector ALU exponentiates.
+// LDS-DMA completion is tracked by hand with s_waitcnt vmcnt(N) (N = loads of the newer tiles that
+// may still be in flight); one workgroup barrier per tile publishes the tile to the other wavefronts.
+template <int D>
+struct WideCfg {
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kKT = kTile * kRowBytes;            // bytes of the K (or V) part of a tile
+    static constexpr int kSlot = 2 * kKT;
+    static constexpr int kCPR = D / 8;                       // 16-byte chunks per row
+    static constexpr int kRPI = 64 / kCPR;                   // rows per 1 KB load instruction
+    static constexpr int kInstr = kTile / kRPI;              // load instructions per K (or V) tile
+    static constexpr int kQ = kInstr / kWaves;               // ... per wavefront
+};
+
+// 16 bytes per lane from global memory straight into LDS: lane i's data lands at lds_base + 16*i.
+// Written as inline assembly on purpose: the compiler then neither reorders it (memory clobber) nor
+// adds its own conservative "wait for every outstanding LDS-DMA" in front of later LDS reads, which
+// would drain the ring on every tile; completion is tracked by wait_vmcnt() in the caller.  An
+// unknown VMEM instruction can only make the compiler's own vmcnt waits stricter, never weaker.
+__device__ __forceinline__ void lds_dma16(const void *gbase /* uniform */, unsigned voff, void *lds_base /* uniform */) {
+    const unsigned m = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) char *)lds_base);
+    unsigned saved;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\t"
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, %3\n\t"
+        "s_mov_b32 m0, %0"
+        : "=&s"(saved)
+        : "s"(m), "v"(voff), "s"(gbase)
+        : "memory");
+}
+
+__device__ __forceinline__ void wait_vmcnt(int n) {
+    // s_waitcnt with only the vmcnt field active (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
+    switch (n) {
+        case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+        case 2: __builtin_amdgcn_s_waitcnt(0x0f72); break;
+        case 4: __builtin_amdgcn_s_waitcnt(0x0f74); break;
+        case 6: __builtin_amdgcn_s_waitcnt(0x0f76); break;
+        case 8: __builtin_amdgcn_s_waitcnt(0x0f78); break;
+        case 10: __builtin_amdgcn_s_waitcnt(0x0f7a); break;
+        case 12: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
+        case 16: __builtin_amdgcn_s_waitcnt(0x4f70); break;
+        case 20: __builtin_amdgcn_s_waitcnt(0x4f74); break;
+        case 24: __builtin_amdgcn_s_waitcnt(0x4f78); break;
+        default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+    }
+}
+
+template <int D, int MT, int NS, bool PIPE>
+__global__ __launch_bounds__(256, PIPE ? 1 : 2) void attn_bf16_wide_kernel(const AttnParams p) {
+    using W = WideCfg<D>;
+    __shared__ __align__(16) char smem[NS * W::kSlot];
+
+    const int kvh = blockIdx.x % p.Hkv;
+    const int b = (blockIdx.x / p.Hkv) % p.B;
+    const int chunk = blockIdx.x / (p.B * p.Hkv);
+    const int S = min(p.seq[b], p.max_pages * p.P);
+    const int c0 = chunk * p.chunk;
+    if (c0 >= S) return;
+    const int c1 = min(S, c0 + p.chunk);
+    const int ntiles = (c1 - c0 + kTile - 1) / kTile;
+    const int nchunks_b = (S + p.chunk - 1) / p.chunk;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
+    const int n = lane & 15, g = lane >> 4;
+    const int R = p.R;
+    const float c = p.scale_log2;
+
+    const int rpw = (p.rows + kWaves - 1) / kWaves;          // packed rows per wavefront (<= 16*MT)
+    const int row0 = wave * rpw;
+    const int row_end = min(p.rows, row0 + rpw);
+    WaveState<D, MT> w;
+    init_state<D, MT>(w, p, b, kvh, row0, row_end, n, g);
+    const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
+
+    // ---- per-lane constants of the tile loop (computed once; the loop only adds uniform bases)
+    // my 16-byte pieces of a tile: piece i is row ld_row[i], and I fetch the global chunk that belongs
+    // in my LDS chunk under the XOR swizzle
+    const int lrow = lane / W::kCPR, lslot = lane % W::kCPR;
+    int ld_row[W::kQ];
+    unsigned ld_goff[W::kQ];                                 // byte offset inside the tile in global memory
+#pragma unroll
+    for (int i = 0; i < W::kQ; ++i) {
+        ld_row[i] = (wave * W::kQ + i) * W::kRPI + lrow;
+        ld_goff[i] = (unsigned)(ld_row[i] * D + (lslot ^ (ld_row[i] & (W::kCPR - 1))) * 8) * 2u;
+    }
+    // fragment reads: K rows n and n+16 (the swizzle only sees row & 15), V rows 4g+jq and +16
+    int koff[D / 32], voff[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) koff[ks] = n * W::kRowBytes + (((ks * 4 + g) ^ (n & (W::kCPR - 1))) * 16);
+    {
+        const int bq = n & 3, jq = n >> 2, vrow = 4 * g + jq;    // transpose-read lane roles, see pv_mfma
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt)
+            voff[dt] = W::kKT + vrow * W::kRowBytes + (((dt * 2 + (bq >> 1)) ^ (vrow & (W::kCPR - 1))) * 16) + (bq & 1) * 8;
+    }
+    const int64_t page_bytes = (int64_t)p.Hkv * p.P * D * 2;
+    const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
+    bool irregular = false;      // a load of this wavefront was (partly) replaced by zero fill
+
+    auto issue = [&](int t) {
+        const int pos0 = c0 + t * kTile;
+        const int pidx = p.log2P >= 0 ? (pos0 >> p.log2P) : (pos0 / p.P);
+        const int lp = pidx - cp.first_page;
+        const int sel = lp >> 6;
+        const int page = __builtin_amdgcn_readlane(sel == 0 ? cp.r0 : sel == 1 ? cp.r1 : sel == 2 ? cp.r2 : cp.r3, lp & 63);
+        const bool page_ok = page >= 0 && (int64_t)page < p.num_pages;
+        const int64_t base = (int64_t)(page_ok ? page : 0) * page_bytes + head_bytes + (int64_t)(pos0 - pidx * p.P) * (D * 2);
+        const char *kb = (const char *)p.kc + base;
+        const char *vb = (const char *)p.vc + base;
+        char *slot = smem + (t % NS) * W::kSlot + wave * (W::kQ * 1024);
+        const int rows_left = S - pos0;                      // rows >= rows_left lie past the sequence
+#pragma unroll
+        for (int i = 0; i < W::kQ; ++i) {
+            const bool ok = page_ok && ld_row[i] < rows_left;
+            char *lk = slot + i * 1024;
+            if (ok) {
+                lds_dma16(kb, ld_goff[i], lk);
+                lds_dma16(vb, ld_goff[i], lk + W::kKT);
+            } else {
+                // past the end of the sequence (or a bad page id): the slot must not keep stale bits,
+                // since 0 * NaN would poison the row sums
+                *(uint4 *)(lk + lane * 16) = uint4{0u, 0u, 0u, 0u};
+                *(uint4 *)(lk + W::kKT + lane * 16) = uint4{0u, 0u, 0u, 0u};
+            }
+        }
+        if (!page_ok || rows_left < kTile) irregular = true; // uniform
+    };
+    constexpr int kPerTile = 2 * W::kQ;                      // load instructions per wavefront per tile
+
+    // S^T of the tile at `tile` (LDS address), fragments at the precomputed lane offsets
+    auto s_mfma_t = [&](const char *tile, f32x4 (&sacc)[2][MT]) {
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+            for (int rt = 0; rt < MT; ++rt) sacc[pt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) {
+            bf16x8 kf[2];
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt) kf[pt] = *(const bf16x8 *)(tile + koff[ks] + pt * 16 * W::kRowBytes);
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int rt = 0; rt < MT; ++rt)
+                    sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
+        }
+    };
+    // O^T += V^T . P^T with the V part of the tile at `tile`
+    auto pv_mfma_t = [&](const char *tile, const bf16x8 (&pf)[MT]) {
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+            const char *a0 = tile + voff[dt];
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)(a0 + 16 * W::kRowBytes));
+            s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, cat);
+#pragma unroll
+            for (int rt = 0; rt < MT; ++rt)
+                w.oacc[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], w.oacc[dt][rt], 0, 0, 0);
+        }
+    };
+
+    // The reference maximum of a row is FIXED at the maximum of the first tile in which the row sees
+    // anything, so the steady-state tile is branch-free: weights 2^(s*c - ref), no running maximum, no
+    // rescaling of the accumulators (any reference gives the same result after normalisation).  Should
+    // a later score exceed the reference by so much that a weight overflows - the sums then turn
+    // non-finite or absurdly large - the chunk is redone: one pass that only raises the references to
+    // the exact row maxima, then a final pass.  attempt: 0 optimistic, 1 exact maxima, 2 final.
+    for (int attempt = 0;; ++attempt) {
+        const bool raise_always = attempt == 1;
+        irregular = false;
+
+        if (PIPE) {
+            // step 0 applies (zero) weights to the V part of ring slot NS-1: give it defined, finite contents
+            for (int i = tid; i < W::kKT / 16; i += 256)
+                *(uint4 *)(smem + (NS - 1) * W::kSlot + W::kKT + i * 16) = uint4{0u, 0u, 0u, 0u};
+
+            // prologue: tiles 0 .. NS-3 in flight; tile 0 must have landed before the first contraction
+            for (int t = 0; t < NS - 2; ++t)
+                if (t < ntiles) issue(t);
+            if (irregular || ntiles < NS - 2) wait_vmcnt(0); else wait_vmcnt(kPerTile * (NS - 3));
+            __syncthreads();
+            f32x4 s_a[2][MT], s_b[2][MT];
+            bf16x8 pf_prev[MT];                                  // weights of the previous tile, not yet applied to V
+    #pragma unroll
+            for (int rt = 0; rt < MT; ++rt) pf_prev[rt] = __builtin_bit_cast(bf16x8, s16x8{0, 0, 0, 0, 0, 0, 0, 0});
+            s_mfma_t(smem, s_a);
+
+            // Step t: the contraction S^T of tile t+1, the contraction P.V of tile t-1 and the softmax of
+            // tile t are mutually independent and sit in one straight-line block, so the 48 MFMAs and the
+            // vector-ALU work of a step can interleave.
+            auto step = [&](int t, f32x4 (&s_cur)[2][MT], f32x4 (&s_next)[2][MT]) {
+                // my quarter of tile t+1 has landed once at most the loads of tiles t+2 .. t+NS-3 are pending
+                if (irregular || t + NS - 3 >= ntiles) wait_vmcnt(0); else wait_vmcnt(kPerTile * (NS - 4));
+                __syncthreads();                                 // tile t+1 visible; everyone is done with tile t-2
+                if (t + NS - 2 < ntiles) issue(t + NS - 2);      // into the slot tile t-2 occupied
+                const int pos0 = c0 + t * kTile;
+                const bool mask = pos0 + kTile > S - R;          // touches the new rows or the ragged end
+                float c_eff = c;
+                if (t == 0 || mask || raise_always) {            // rare: maxima, reference, masking
+                    float mx[MT];
+                    if (mask) softmax_max<D, MT, true>(w, s_cur, mx, pos0, S, R, c, g);
+                    else softmax_max<D, MT, false>(w, s_cur, mx, pos0, S, R, c, g);
+    #pragma unroll
+                    for (int rt = 0; rt < MT; ++rt)              // mx = -inf (nothing visible) leaves it unset
+                        if (raise_always || w.m_run[rt] == kNegBig) w.m_run[rt] = fmaxf(w.m_run[rt], mx[rt]);
+                    if (mask) c_eff = 1.0f;                      // the masked form has scaled the scores in place
+                }
+                s_mfma_t(smem + ((t + 1) % NS) * W::kSlot, s_next);      // unused after the chunk's last tile
+                pv_mfma_t(smem + ((t + NS - 1) % NS) * W::kSlot, pf_prev);
+                softmax_exp<D, MT, false>(w, s_cur, c_eff, pf_prev);     // fma(-inf, 1, -ref) = -inf -> weight 0
+            };
+            for (int t = 0; t < ntiles; t += 2) {
+                step(t, s_a, s_b);
+                if (t + 1 < ntiles) step(t + 1, s_b, s_a);
+            }
+            pv_mfma_t(smem + ((ntiles - 1) % NS) * W::kSlot, pf_prev);
+        } else {
+            // two workgroups per compute unit: the other workgroup's wavefront on the same SIMD fills
+            // the gaps, so the loop stays simple (S^T, softmax, P.V of one tile per step)
+            for (int t = 0; t < NS - 1; ++t)
+                if (t < ntiles) issue(t);
+            for (int t = 0; t < ntiles; ++t) {
+                // my quarter of tile t has landed once at most the loads of tiles t+1 .. t+NS-2 are pending
+                if (irregular || t + NS - 2 >= ntiles) wait_vmcnt(0); else wait_vmcnt(kPerTile * (NS - 2));
+                __syncthreads();                             // tile t visible; everyone is done with tile t-1
+                if (t + NS - 1 < ntiles) issue(t + NS - 1);  // into the slot tile t-1 occupied
+                const int pos0 = c0 + t * kTile;
+                const bool mask = pos0 + kTile > S - R;
+                const char *tile = smem + (t % NS) * W::kSlot;
+                f32x4 sacc[2][MT];
+                bf16x8 pf[MT];
+                s_mfma_t(tile, sacc);
+                float c_eff = c;
+                if (t == 0 || mask || raise_always) {
+                    float mx[MT];
+                    if (mask) softmax_max<D, MT, true>(w, sacc, mx, pos0, S, R, c, g);
+                    else softmax_max<D, MT, false>(w, sacc, mx, pos0, S, R, c, g);
+#pragma unroll
+                    for (int rt = 0; rt < MT; ++rt)
+                        if (raise_always || w.m_run[rt] == kNegBig) w.m_run[rt] = fmaxf(w.m_run[rt], mx[rt]);
+                    if (mask) c_eff = 1.0f;
+                }
+                softmax_exp<D, MT, false>(w, sacc, c_eff, pf);
+                pv_mfma_t(tile, pf);
+            }
+        }
+
+        bool bad = false;
+#pragma unroll
+        for (int rt = 0; rt < MT; ++rt) bad = bad || !(w.l_part[rt] < 1.0e30f);    // also catches NaN
+        // the barrier also keeps a fast wavefront from refilling ring slots others still read
+        const bool redo = __syncthreads_or(bad) != 0;
+        if (attempt == 2 || (attempt == 0 && !redo)) break;
+#pragma unroll
+        for (int rt = 0; rt < MT; ++rt) {
+            if (attempt == 0) w.m_run[rt] = kNegBig;         // attempt 1 finds the exact maxima from scratch
+            w.l_part[rt] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < D / 16; ++dt) w.oacc[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    // ---- every wavefront owns its rows outright: normalise (or leave a partial) straight from registers
+    float *wo = nullptr, *wm = nullptr, *wl = nullptr;
+    if (nchunks_b > 1) {
+        const int64_t rec = ((int64_t)b * p.Hkv + kvh) * p.nchunks_max + chunk;
+        wo = p.ws + rec * ws_record_floats(p.rows_pad, D);
+        wm = wo + (int64_t)p.rows_pad * D;
+        wl = wm + p.rows_pad;
+    }
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt) {
+        float l = w.l_part[rt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const int pr = row0 + rt * 16 + n;
+        if (pr < row_end) {
+            if (nchunks_b == 1) {
+                const int hh = pr / R, i = pr % R;
+                const float inv = 1.0f / l;
+                const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D;
+#pragma unroll
+                for (int dt = 0; dt < D / 16; ++dt) {
+                    const f32x4 a = w.oacc[dt][rt] * inv;
+                    store_out(p.out, o + dt * 16 + 4 * g, float4{a[0], a[1], a[2], a[3]}, p.out_bf16);
+                }
+            } else {
+#pragma unroll
+                for (int dt = 0; dt < D / 16; ++dt) {
+                    const f32x4 a = w.oacc[dt][rt];
+                    *(float4 *)(wo + (int64_t)pr * D + dt * 16 + 4 * g) = float4{a[0], a[1], a[2], a[3]};
+                }
+                if (g == 0) { wm[pr] = w.m_run[rt]; wl[pr] = l; }
+            }
         }
     }
 }
@@ -465,7 +903,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p) {
     __syncthreads();
 
     // pass 2: per-row maximum and weights, one wavefront per row
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
     for (int i = wave; i < R; i += 4) {
         float mx = -INFINITY;
         for (int t = lane; t < npos; t += 64) mx = fmaxf(mx, sc[i][t]);
@@ -517,7 +955,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p) {
 // host side
 // ------------------------------------------------------------------------------------------
 struct Plan {
-    int chunk, nchunks_max, n_rg, rows_pad, heads_outer;
+    int chunk, nchunks_max, rows_pad, heads_outer;
+    bool wide;
     size_t ws_bytes;
 };
 
@@ -530,28 +969,35 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
     if (smax > 0x7fffff00ll) return AGENTSAM_ERR_ARG;
     const int G = Hq / Hkv;
     const int64_t opt = agentsam::option_attn_kv_chunk();
+    pl->wide = false;
     if (dtype == AGENTSAM_F32) {
         if (R > kF32MaxR) return AGENTSAM_ERR_UNSUPPORTED;
         pl->chunk = kF32Chunk;                               // fixed: the score tile lives in LDS
-        pl->n_rg = 1;
         pl->rows_pad = R;
         pl->heads_outer = Hq;
     } else {
         if (page_size % kTile != 0) return AGENTSAM_ERR_UNSUPPORTED;
         const int rows = G * R;
-        if (rows > 4 * kRowsPerGroup) return AGENTSAM_ERR_UNSUPPORTED;
-        pl->n_rg = (rows + kRowsPerGroup - 1) / kRowsPerGroup;
-        pl->rows_pad = pl->n_rg * kRowsPerGroup;
+        if (rows > kWaves * kRowsPerGroup) return AGENTSAM_ERR_UNSUPPORTED;
+        pl->wide = rows > kRowsPerGroup;
+        pl->rows_pad = (rows + 3) & ~3;                      // keeps every record 16-byte aligned
         pl->heads_outer = Hkv;
         int64_t chunk = opt;
         if (chunk == 0) {
             // aim at ~2048 workgroups (8 per compute unit) when the sequences are long enough
-            const int64_t pairs = (int64_t)B * Hkv * pl->n_rg;
+            const int64_t pairs = (int64_t)B * Hkv;
             chunk = smax * (pairs > 0 ? pairs : 1) / 2048;
             chunk = (chunk + 127) / 128 * 128;
             if (chunk < 1024) chunk = 1024;
             if (chunk > 8192) chunk = 8192;
         }
+        // chunks start on page boundaries and span at most 64*kPageRegs pages
+        int64_t unit = 128;
+        while (unit % page_size != 0) unit += 128;           // lcm(128, page_size)
+        chunk = (chunk + unit - 1) / unit * unit;
+        const int64_t cap = (int64_t)64 * kPageRegs * page_size / unit * unit;
+        if (cap < unit) return AGENTSAM_ERR_UNSUPPORTED;
+        if (chunk > cap) chunk = cap;
         pl->chunk = (int)chunk;
     }
     pl->nchunks_max = (int)((smax + pl->chunk - 1) / pl->chunk);
@@ -561,15 +1007,21 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
 }
 
 template <int D, int VMODE>
-void launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st) {
-    const int rows_last = p.rows - (p.n_rg - 1) * kRowsPerGroup;   // all groups but the last are full
-    // one instantiation per row-tile count of the (possibly partial) last group would need two
-    // launches; a partially filled group simply carries dead rows instead
-    (void)rows_last;
-    const int mt = (p.n_rg > 1) ? 3 : (p.rows + 15) / 16;
-    if (mt == 1) hipLaunchKernelGGL((attn_bf16_kernel<D, 1, VMODE>), grid, dim3(256), 0, st, p);
-    else if (mt == 2) hipLaunchKernelGGL((attn_bf16_kernel<D, 2, VMODE>), grid, dim3(256), 0, st, p);
-    else hipLaunchKernelGGL((attn_bf16_kernel<D, 3, VMODE>), grid, dim3(256), 0, st, p);
+void launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st) {
+    if (wide) {
+        const int rpw = (p.rows + kWaves - 1) / kWaves;
+        const int mt = (rpw + 15) / 16;
+        // two workgroups per compute unit, each with a ring of 4 tile slots
+        constexpr int NS = 4;
+        if (mt == 1) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS, false>), grid, dim3(256), 0, st, p);
+        else if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS, false>), grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 3, NS, false>), grid, dim3(256), 0, st, p);
+        return;
+    }
+    const int mt = (p.rows + 15) / 16;
+    if (mt == 1) hipLaunchKernelGGL((attn_bf16_narrow_kernel<D, 1, VMODE>), grid, dim3(256), 0, st, p);
+    else if (mt == 2) hipLaunchKernelGGL((attn_bf16_narrow_kernel<D, 2, VMODE>), grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((attn_bf16_narrow_kernel<D, 3, VMODE>), grid, dim3(256), 0, st, p);
 }
 
 }  // namespace
@@ -598,16 +1050,19 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     if (!q || !k_cache || !v_cache || !block_table || !seq_lens || !out) return AGENTSAM_ERR_NULL;
     if (pl.ws_bytes > 0 && !workspace) return AGENTSAM_ERR_NULL;
     if (workspace_bytes < pl.ws_bytes) return AGENTSAM_ERR_WORKSPACE;
-    if ((int64_t)B * pl.heads_outer * pl.n_rg > 65535ll * 65535ll) return AGENTSAM_ERR_ARG;
+    if (B > 65535 || pl.heads_outer > 65535) return AGENTSAM_ERR_ARG;
 
     AttnParams p;
     p.q = q; p.kc = k_cache; p.vc = v_cache; p.bt = block_table; p.seq = seq_lens; p.out = out;
     p.ws = (float *)workspace;
     p.B = B; p.R = R; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv; p.P = page_size; p.max_pages = max_pages;
     p.num_pages = num_pages;
+    p.log2P = -1;
+    for (int sft = 0; sft < 31; ++sft)
+        if ((1 << sft) == page_size) p.log2P = sft;
     p.scale_log2 = scale * kLog2e;
     p.chunk = pl.chunk; p.nchunks_max = pl.nchunks_max;
-    p.rows = p.G * R; p.n_rg = pl.n_rg; p.rows_pad = pl.rows_pad;
+    p.rows = p.G * R; p.rows_pad = pl.rows_pad;
     p.out_bf16 = (out_dtype == AGENTSAM_BF16);
     hipStream_t st = (hipStream_t)stream;
 
@@ -625,10 +1080,11 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
         return AGENTSAM_OK;
     }
 
-    dim3 grid((unsigned)pl.nchunks_max, (unsigned)(Hkv * pl.n_rg), (unsigned)B);
+    if ((int64_t)pl.nchunks_max * Hkv * B > 0x7fffffffll) return AGENTSAM_ERR_ARG;
+    dim3 grid((unsigned)((int64_t)pl.nchunks_max * Hkv * B));
     const bool tr = agentsam::option_attn_v_mode() == 1;
-    if (D == 64) { if (tr) launch_bf16<64, 1>(p, grid, st); else launch_bf16<64, 0>(p, grid, st); }
-    else { if (tr) launch_bf16<128, 1>(p, grid, st); else launch_bf16<128, 0>(p, grid, st); }
+    if (D == 64) { if (tr) launch_bf16<64, 1>(p, pl.wide, grid, st); else launch_bf16<64, 0>(p, pl.wide, grid, st); }
+    else { if (tr) launch_bf16<128, 1>(p, pl.wide, grid, st); else launch_bf16<128, 0>(p, pl.wide, grid, st); }
     AGENTSAM_LAUNCH_CHECK();
     if (pl.nchunks_max > 1) {
         dim3 mg((unsigned)Hkv, (unsigned)B);

@@ -103,6 +103,25 @@ def test_bf16_minimum_and_boundary_lengths():
         A.agentsam_set_option("attn_kv_chunk", 0)
 
 
+@pytest.mark.parametrize("k,Hq", [(8, 8), (16, 16)])
+def test_scores_far_above_the_first_tile(k, Hq):
+    """Late keys whose scores exceed everything seen before by hundreds of log2 units (a fixed softmax
+    reference would overflow): both the 36-row and the 136-row kernels must still match the oracle."""
+    cfg = W.scaled(W.baseline_config(1), B=2, Hq=Hq, Hkv=2, D=128, k=k, kv_mode="ragged", kv_len=(700, 2100),
+                   permute_pages=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    kc = kc * 0.05                                              # quiet keys ...
+    for b in range(cfg.B):
+        S = int(lay.seq_lens[b])
+        for pos, row, h in ((S // 2, 0, 0), (S // 2 + 37, cfg.R - 1, Hq - 1), (S - cfg.R - 3, 1, Hq // 2)):
+            page, slot = int(lay.block_table[b, pos // cfg.page]), pos % cfg.page
+            kc[page, h // cfg.G, slot] = (q[b, row, h].float() * 16.0).to(kc.dtype)   # ... and a few loud ones
+    kc = kc.contiguous()
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
 def test_split_and_page_permutation_invariance():
     cfg = W.scaled(W.baseline_config(1), B=2, Hq=8, Hkv=2, D=128, k=8, kv_mode="ragged", kv_len=(1500, 4000))
     lay, q, kc, vc, bt, seq = _inputs(cfg)
