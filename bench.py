@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 
 # HBM bytes of one spec_verify_attn launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE
 # runs, scaled by a copy kernel of known size); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg2-b64-32k": 8.68e9}      # profiles/spec_verify_attn_cfg2_hbm_traffic.txt
 
 
 def parse():
@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only spec_verify_attn (for profiling)")
     ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy (5 times): a kernel of known HBM traffic "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with")
     ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
                     help="override a workload field (experiments only), e.g. --set permute_pages=False")
     return ap.parse_args()
@@ -109,6 +112,15 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4,
+                          "launches": 5}))
+        return
     cfg = W.baseline_config(args.config)
     if args.set:
         import ast

@@ -293,26 +293,34 @@ __device__ __forceinline__ void compute_tile(WaveState<D, MT> &w, const char *Ks
     pv_mfma<D, MT, VMODE>(w, Vs, pf, n, g);
 }
 
-// The page ids of one chunk, fetched once at kernel start (lane i of register r holds the id of the
-// chunk's page 64*r + i) and handed out with v_readlane: the tile loop never waits on a block-table
-// load, and no vector load of its own sits between the streaming loads whose completion it counts.
-constexpr int kPageRegs = 4;                                 // up to 256 pages per chunk
+// The page id of every 32-position tile of a chunk, fetched once at kernel start (lane i of register
+// r holds the id for tile 64*r + i) and handed out with v_readlane: the tile loop never waits on a
+// block-table load, and no vector load of its own sits between the streaming loads whose completion
+// it counts.  A chunk therefore spans at most 256 tiles (8192 positions).
+constexpr int kMaxChunk = 256 * kTile;
 struct ChunkPages {
     int r0, r1, r2, r3;          // named members, not an array: an indexable private array would be
-    int first_page;              // demoted to LDS by the compiler
-};
+};                               // demoted to LDS by the compiler
 
 __device__ __forceinline__ ChunkPages load_chunk_pages(const AttnParams &p, int b, int c0, int c1, int lane) {
     ChunkPages cp;
-    cp.first_page = p.log2P >= 0 ? (c0 >> p.log2P) : (c0 / p.P);
-    const int last_page = p.log2P >= 0 ? ((c1 - 1) >> p.log2P) : ((c1 - 1) / p.P);
-    const int npages = last_page - cp.first_page + 1;
-    const int32_t *row = p.bt + (int64_t)b * p.max_pages + cp.first_page;
-    cp.r0 = (lane < npages) ? row[lane] : -1;
-    cp.r1 = (64 + lane < npages) ? row[64 + lane] : -1;
-    cp.r2 = (128 + lane < npages) ? row[128 + lane] : -1;
-    cp.r3 = (192 + lane < npages) ? row[192 + lane] : -1;
+    const int32_t *row = p.bt + (int64_t)b * p.max_pages;
+    auto page_of_tile = [&](int tile) {
+        const int pos = c0 + tile * kTile;
+        if (pos >= c1) return -1;
+        return row[p.log2P >= 0 ? (pos >> p.log2P) : (pos / p.P)];
+    };
+    cp.r0 = page_of_tile(lane);
+    cp.r1 = page_of_tile(64 + lane);
+    cp.r2 = page_of_tile(128 + lane);
+    cp.r3 = page_of_tile(192 + lane);
     return cp;
+}
+
+__device__ __forceinline__ int tile_page(const ChunkPages &cp, int t /* uniform */) {
+    const int sel = t >> 6;
+    const int v = sel == 0 ? cp.r0 : sel == 1 ? cp.r1 : sel == 2 ? cp.r2 : cp.r3;
+    return __builtin_amdgcn_readlane(v, t & 63);
 }
 
 // Start of a tile's first row in the K and V caches, and whether its page id is usable.
@@ -324,20 +332,17 @@ struct TileSrc {
 };
 
 template <int D>
-__device__ __forceinline__ TileSrc<D> tile_src(const AttnParams &p, const ChunkPages &cp, int kvh, int pos0) {
-    TileSrc<D> t;
-    const int pidx = p.log2P >= 0 ? (pos0 >> p.log2P) : (pos0 / p.P);
-    const int slot = pos0 - pidx * p.P;
-    const int lp = pidx - cp.first_page;                     // uniform over the wavefront
-    const int sel = lp >> 6;
-    const int v = sel == 0 ? cp.r0 : sel == 1 ? cp.r1 : sel == 2 ? cp.r2 : cp.r3;
-    const int page = __builtin_amdgcn_readlane(v, lp & 63);
-    t.page_ok = page >= 0 && (int64_t)page < p.num_pages;
-    const int64_t base = (((int64_t)(t.page_ok ? page : 0) * p.Hkv + kvh) * p.P + slot) * D;
-    t.kbase = (const __hip_bfloat16 *)p.kc + base;
-    t.vbase = (const __hip_bfloat16 *)p.vc + base;
-    t.pos0 = pos0;
-    return t;
+__device__ __forceinline__ TileSrc<D> tile_src(const AttnParams &p, const ChunkPages &cp, int kvh, int c0, int t) {
+    TileSrc<D> ts;
+    const int pos0 = c0 + t * kTile;
+    const int slot = p.log2P >= 0 ? (pos0 & (p.P - 1)) : (pos0 % p.P);
+    const int page = tile_page(cp, t);
+    ts.page_ok = page >= 0 && (int64_t)page < p.num_pages;
+    const int64_t base = (((int64_t)(ts.page_ok ? page : 0) * p.Hkv + kvh) * p.P + slot) * D;
+    ts.kbase = (const __hip_bfloat16 *)p.kc + base;
+    ts.vbase = (const __hip_bfloat16 *)p.vc + base;
+    ts.pos0 = pos0;
+    return ts;
 }
 
 // -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the chunk
@@ -382,7 +387,7 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
     uint4 kreg[2][C::kLoads], vreg[2][C::kLoads];
 
     auto issue_loads = [&](int t, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
-        const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0 + t * kTile);
+        const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0, t);
 #pragma unroll
         for (int i = 0; i < C::kLoads; ++i) {
             const int row = i * C::kRowsPerLoad + ld_row;
@@ -506,15 +511,20 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
 // With this many rows per K/V byte the MFMA and softmax arithmetic are no longer negligible next to
 // the memory stream, and there are no registers to spare for staging, so:
 //   - tiles go from global memory straight into a ring of NS LDS slots (global_load_lds_dwordx4:
-//     lane i's 16 bytes land at slot base + 16*i), each wavefront fetching a quarter of every tile;
-//     NS-2 tiles are in flight while two are being consumed;
+//     lane i's 16 bytes land at slot base + 16*i).  The wavefronts take turns: tile t is fetched
+//     whole by wavefront t % 4, so the address arithmetic of a tile is paid once, not four times,
+//     and a wavefront only ever waits for the one tile it issued (s_waitcnt vmcnt(0));
 //   - rows are stored unpadded (256 B for D=128), so the 16-byte chunks of a row are XOR-swizzled
 //     with the row index on the way in (the lane picks which global chunk it fetches) to keep the
 //     column-wise fragment reads off a single bank;
-//   - the loop is software-pipelined inside a wavefront: the S^T contraction of tile t+1 is issued
-//     before the softmax of tile t, so the matrix pipe works while the vector ALU exponentiates.
-// LDS-DMA completion is tracked by hand with s_waitcnt vmcnt(N) (N = loads of the newer tiles that
-// may still be in flight); one workgroup barrier per tile publishes the tile to the other wavefronts.
+//   - the softmax reference of a row is FIXED at the maximum of the first tile in which the row sees
+//     anything, so the steady-state tile is branch-free: weights 2^(s*c - ref), no running maximum,
+//     no rescaling of the accumulators (any reference gives the same result after normalisation).
+//     Should a later score exceed the reference by so much that a weight overflows - the sums then
+//     turn non-finite or absurdly large - the chunk is redone: one pass that only raises the
+//     references to the exact row maxima, then a final pass;
+//   - registers stay under 256 so that two workgroups share a compute unit and one's wavefront
+//     fills the other's stalls; one workgroup barrier per tile publishes the tile.
 template <int D>
 struct WideCfg {
     static constexpr int kRowBytes = D * 2;
@@ -522,17 +532,16 @@ struct WideCfg {
     static constexpr int kSlot = 2 * kKT;
     static constexpr int kCPR = D / 8;                       // 16-byte chunks per row
     static constexpr int kRPI = 64 / kCPR;                   // rows per 1 KB load instruction
-    static constexpr int kInstr = kTile / kRPI;              // load instructions per K (or V) tile
-    static constexpr int kQ = kInstr / kWaves;               // ... per wavefront
+    static constexpr int kPieces = kTile / kRPI;             // 1 KB load instructions per K (or V) tile
 };
 
 // 16 bytes per lane from global memory straight into LDS: lane i's data lands at lds_base + 16*i.
 // Written as inline assembly on purpose: the compiler then neither reorders it (memory clobber) nor
-// adds its own conservative "wait for every outstanding LDS-DMA" in front of later LDS reads, which
-// would drain the ring on every tile; completion is tracked by wait_vmcnt() in the caller.  An
-// unknown VMEM instruction can only make the compiler's own vmcnt waits stricter, never weaker.
-__device__ __forceinline__ void lds_dma16(const void *gbase /* uniform */, unsigned voff, void *lds_base /* uniform */) {
-    const unsigned m = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) char *)lds_base);
+// adds its own conservative "wait for every outstanding LDS-DMA" in front of later LDS reads;
+// completion is awaited explicitly with s_waitcnt vmcnt(0) by the issuing wavefront.  An unknown VMEM
+// instruction can only make the compiler's own vmcnt waits stricter, never weaker.
+__device__ __forceinline__ void lds_dma16(const void *gbase /* uniform */, unsigned voff, unsigned lds_addr /* uniform */) {
+    const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
     unsigned saved;
     asm volatile(
         "s_mov_b32 %0, m0\n\t"
@@ -545,25 +554,55 @@ __device__ __forceinline__ void lds_dma16(const void *gbase /* uniform */, unsig
         : "memory");
 }
 
-__device__ __forceinline__ void wait_vmcnt(int n) {
-    // s_waitcnt with only the vmcnt field active (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
-    switch (n) {
-        case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
-        case 2: __builtin_amdgcn_s_waitcnt(0x0f72); break;
-        case 4: __builtin_amdgcn_s_waitcnt(0x0f74); break;
-        case 6: __builtin_amdgcn_s_waitcnt(0x0f76); break;
-        case 8: __builtin_amdgcn_s_waitcnt(0x0f78); break;
-        case 10: __builtin_amdgcn_s_waitcnt(0x0f7a); break;
-        case 12: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
-        case 16: __builtin_amdgcn_s_waitcnt(0x4f70); break;
-        case 20: __builtin_amdgcn_s_waitcnt(0x4f74); break;
-        case 24: __builtin_amdgcn_s_waitcnt(0x4f78); break;
-        default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
-    }
+// Tell the compiler a pointer is the same in every lane (keeps it in a scalar register pair).
+__device__ __forceinline__ const void *uniform_ptr(const void *ptr) {
+    const uint64_t v = (uint64_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const void *)(((uint64_t)hi << 32) | lo);
 }
 
-template <int D, int MT, int NS, bool PIPE>
-__global__ __launch_bounds__(256, PIPE ? 1 : 2) void attn_bf16_wide_kernel(const AttnParams p) {
+// A whole tile (all 1 KB pieces of K, then of V at +kKT) in one block; M0 is saved once.
+#define AGENTSAM_DMA_PIECE(J, G)                       \
+    "s_add_u32 m0, %1, " #J "*1024\n\ts_nop 0\n\t"     \
+    "global_load_lds_dwordx4 " G ", %2\n\t"            \
+    "s_add_u32 m0, %1, %c4+" #J "*1024\n\ts_nop 0\n\t" \
+    "global_load_lds_dwordx4 " G ", %3\n\t"
+template <int D>
+__device__ __forceinline__ void lds_dma_tile(const void *kb, const void *vb, const unsigned (&goff)[WideCfg<D>::kPieces],
+                                             unsigned slot_addr /* uniform LDS byte address */) {
+    const unsigned m = __builtin_amdgcn_readfirstlane(slot_addr);
+    unsigned saved;
+    if constexpr (D == 128) {
+        asm volatile("s_mov_b32 %0, m0\n\t"
+                     AGENTSAM_DMA_PIECE(0, "%5") AGENTSAM_DMA_PIECE(1, "%6") AGENTSAM_DMA_PIECE(2, "%7")
+                     AGENTSAM_DMA_PIECE(3, "%8") AGENTSAM_DMA_PIECE(4, "%9") AGENTSAM_DMA_PIECE(5, "%10")
+                     AGENTSAM_DMA_PIECE(6, "%11") AGENTSAM_DMA_PIECE(7, "%12")
+                     "s_mov_b32 m0, %0"
+                     : "=&s"(saved)
+                     : "s"(m), "s"(kb), "s"(vb), "n"(WideCfg<D>::kKT), "v"(goff[0]), "v"(goff[1]), "v"(goff[2]),
+                       "v"(goff[3]), "v"(goff[4]), "v"(goff[5]), "v"(goff[6]), "v"(goff[7])
+                     : "memory", "scc");
+    } else {
+        asm volatile("s_mov_b32 %0, m0\n\t"
+                     AGENTSAM_DMA_PIECE(0, "%5") AGENTSAM_DMA_PIECE(1, "%6") AGENTSAM_DMA_PIECE(2, "%7")
+                     AGENTSAM_DMA_PIECE(3, "%8")
+                     "s_mov_b32 m0, %0"
+                     : "=&s"(saved)
+                     : "s"(m), "s"(kb), "s"(vb), "n"(WideCfg<D>::kKT), "v"(goff[0]), "v"(goff[1]), "v"(goff[2]),
+                       "v"(goff[3])
+                     : "memory", "scc");
+    }
+}
+#undef AGENTSAM_DMA_PIECE
+
+__device__ __forceinline__ void wait_vmcnt0() {
+    // s_waitcnt with only the vmcnt field active (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+}
+
+template <int D, int MT, int NS>
+__global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
     using W = WideCfg<D>;
     __shared__ __align__(16) char smem[NS * W::kSlot];
 
@@ -591,15 +630,14 @@ __global__ __launch_bounds__(256, PIPE ? 1 : 2) void attn_bf16_wide_kernel(const
     const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
 
     // ---- per-lane constants of the tile loop (computed once; the loop only adds uniform bases)
-    // my 16-byte pieces of a tile: piece i is row ld_row[i], and I fetch the global chunk that belongs
-    // in my LDS chunk under the XOR swizzle
+    // piece j of a tile (1 KB = kRPI rows): my 16 bytes are row j*kRPI + lrow, and I fetch the global
+    // chunk that belongs in my LDS chunk under the XOR swizzle
     const int lrow = lane / W::kCPR, lslot = lane % W::kCPR;
-    int ld_row[W::kQ];
-    unsigned ld_goff[W::kQ];                                 // byte offset inside the tile in global memory
+    unsigned ld_goff[W::kPieces];                            // byte offset inside the tile in global memory
 #pragma unroll
-    for (int i = 0; i < W::kQ; ++i) {
-        ld_row[i] = (wave * W::kQ + i) * W::kRPI + lrow;
-        ld_goff[i] = (unsigned)(ld_row[i] * D + (lslot ^ (ld_row[i] & (W::kCPR - 1))) * 8) * 2u;
+    for (int j = 0; j < W::kPieces; ++j) {
+        const int row = j * W::kRPI + lrow;
+        ld_goff[j] = (unsigned)(row * D + (lslot ^ (row & (W::kCPR - 1))) * 8) * 2u;
     }
     // fragment reads: K rows n and n+16 (the swizzle only sees row & 15), V rows 4g+jq and +16
     int koff[D / 32], voff[D / 16];
@@ -613,155 +651,94 @@ __global__ __launch_bounds__(256, PIPE ? 1 : 2) void attn_bf16_wide_kernel(const
     }
     const int64_t page_bytes = (int64_t)p.Hkv * p.P * D * 2;
     const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
-    bool irregular = false;      // a load of this wavefront was (partly) replaced by zero fill
+    const unsigned smem_addr = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem;   // LDS byte address
 
+    // fetch tile t into its ring slot (called by one wavefront)
     auto issue = [&](int t) {
         const int pos0 = c0 + t * kTile;
-        const int pidx = p.log2P >= 0 ? (pos0 >> p.log2P) : (pos0 / p.P);
-        const int lp = pidx - cp.first_page;
-        const int sel = lp >> 6;
-        const int page = __builtin_amdgcn_readlane(sel == 0 ? cp.r0 : sel == 1 ? cp.r1 : sel == 2 ? cp.r2 : cp.r3, lp & 63);
+        const int page = tile_page(cp, t);
         const bool page_ok = page >= 0 && (int64_t)page < p.num_pages;
-        const int64_t base = (int64_t)(page_ok ? page : 0) * page_bytes + head_bytes + (int64_t)(pos0 - pidx * p.P) * (D * 2);
-        const char *kb = (const char *)p.kc + base;
-        const char *vb = (const char *)p.vc + base;
-        char *slot = smem + (t % NS) * W::kSlot + wave * (W::kQ * 1024);
+        const int slot_in_page = p.log2P >= 0 ? (pos0 & (p.P - 1)) : (pos0 % p.P);
+        const int64_t base = (int64_t)(page_ok ? page : 0) * page_bytes + head_bytes + (int64_t)slot_in_page * (D * 2);
+        const char *kb = (const char *)uniform_ptr((const char *)p.kc + base);
+        const char *vb = (const char *)uniform_ptr((const char *)p.vc + base);
+        const int slot_off = (t % NS) * W::kSlot;
         const int rows_left = S - pos0;                      // rows >= rows_left lie past the sequence
+        if (page_ok && rows_left >= kTile) {                 // the usual case: a full tile, all lanes load
+            lds_dma_tile<D>(kb, vb, ld_goff, smem_addr + slot_off);
+        } else {
 #pragma unroll
-        for (int i = 0; i < W::kQ; ++i) {
-            const bool ok = page_ok && ld_row[i] < rows_left;
-            char *lk = slot + i * 1024;
-            if (ok) {
-                lds_dma16(kb, ld_goff[i], lk);
-                lds_dma16(vb, ld_goff[i], lk + W::kKT);
-            } else {
-                // past the end of the sequence (or a bad page id): the slot must not keep stale bits,
-                // since 0 * NaN would poison the row sums
-                *(uint4 *)(lk + lane * 16) = uint4{0u, 0u, 0u, 0u};
-                *(uint4 *)(lk + W::kKT + lane * 16) = uint4{0u, 0u, 0u, 0u};
+            for (int j = 0; j < W::kPieces; ++j) {
+                char *lk = smem + slot_off + j * 1024;
+                if (page_ok && j * W::kRPI + lrow < rows_left) {
+                    lds_dma16(kb, ld_goff[j], smem_addr + slot_off + j * 1024);
+                    lds_dma16(vb, ld_goff[j], smem_addr + slot_off + j * 1024 + W::kKT);
+                } else {
+                    // past the end of the sequence (or a bad page id): the slot must not keep stale
+                    // bits, since 0 * NaN would poison the row sums
+                    *(uint4 *)(lk + lane * 16) = uint4{0u, 0u, 0u, 0u};
+                    *(uint4 *)(lk + W::kKT + lane * 16) = uint4{0u, 0u, 0u, 0u};
+                }
             }
         }
-        if (!page_ok || rows_left < kTile) irregular = true; // uniform
     };
-    constexpr int kPerTile = 2 * W::kQ;                      // load instructions per wavefront per tile
 
-    // S^T of the tile at `tile` (LDS address), fragments at the precomputed lane offsets
-    auto s_mfma_t = [&](const char *tile, f32x4 (&sacc)[2][MT]) {
-#pragma unroll
-        for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-            for (int rt = 0; rt < MT; ++rt) sacc[pt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < D / 32; ++ks) {
-            bf16x8 kf[2];
-#pragma unroll
-            for (int pt = 0; pt < 2; ++pt) kf[pt] = *(const bf16x8 *)(tile + koff[ks] + pt * 16 * W::kRowBytes);
+    // attempt: 0 optimistic (fixed references), 1 exact row maxima only, 2 final pass with those
+    for (int attempt = 0;; ++attempt) {
+        const bool raise_always = attempt == 1;
+        for (int t = 0; t < NS - 1; ++t)
+            if (t < ntiles && wave == (t & (kWaves - 1))) issue(t);
+        for (int t = 0; t < ntiles; ++t) {
+            if (wave == (t & (kWaves - 1))) wait_vmcnt0();   // the tile I fetched has landed
+            __syncthreads();                                 // tile t visible; everyone is done with tile t-1
+            const int tn = t + NS - 1;                       // goes into the slot tile t-1 occupied
+            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn);
+
+            const int pos0 = c0 + t * kTile;
+            const bool mask = pos0 + kTile > S - R;          // touches the new rows or the ragged end
+            const char *tile = smem + (t % NS) * W::kSlot;
+            // ---- S^T = K . Q^T
+            f32x4 sacc[2][MT];
 #pragma unroll
             for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-                for (int rt = 0; rt < MT; ++rt)
-                    sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
-        }
-    };
-    // O^T += V^T . P^T with the V part of the tile at `tile`
-    auto pv_mfma_t = [&](const char *tile, const bf16x8 (&pf)[MT]) {
+                for (int rt = 0; rt < MT; ++rt) sacc[pt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-            const char *a0 = tile + voff[dt];
-            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
-            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4 *)(a0 + 16 * W::kRowBytes));
-            s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            const bf16x8 vf = __builtin_bit_cast(bf16x8, cat);
+            for (int ks = 0; ks < D / 32; ++ks) {
+                bf16x8 kf[2];
 #pragma unroll
-            for (int rt = 0; rt < MT; ++rt)
-                w.oacc[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], w.oacc[dt][rt], 0, 0, 0);
-        }
-    };
-
-    // The reference maximum of a row is FIXED at the maximum of the first tile in which the row sees
-    // anything, so the steady-state tile is branch-free: weights 2^(s*c - ref), no running maximum, no
-    // rescaling of the accumulators (any reference gives the same result after normalisation).  Should
-    // a later score exceed the reference by so much that a weight overflows - the sums then turn
-    // non-finite or absurdly large - the chunk is redone: one pass that only raises the references to
-    // the exact row maxima, then a final pass.  attempt: 0 optimistic, 1 exact maxima, 2 final.
-    for (int attempt = 0;; ++attempt) {
-        const bool raise_always = attempt == 1;
-        irregular = false;
-
-        if (PIPE) {
-            // step 0 applies (zero) weights to the V part of ring slot NS-1: give it defined, finite contents
-            for (int i = tid; i < W::kKT / 16; i += 256)
-                *(uint4 *)(smem + (NS - 1) * W::kSlot + W::kKT + i * 16) = uint4{0u, 0u, 0u, 0u};
-
-            // prologue: tiles 0 .. NS-3 in flight; tile 0 must have landed before the first contraction
-            for (int t = 0; t < NS - 2; ++t)
-                if (t < ntiles) issue(t);
-            if (irregular || ntiles < NS - 2) wait_vmcnt(0); else wait_vmcnt(kPerTile * (NS - 3));
-            __syncthreads();
-            f32x4 s_a[2][MT], s_b[2][MT];
-            bf16x8 pf_prev[MT];                                  // weights of the previous tile, not yet applied to V
-    #pragma unroll
-            for (int rt = 0; rt < MT; ++rt) pf_prev[rt] = __builtin_bit_cast(bf16x8, s16x8{0, 0, 0, 0, 0, 0, 0, 0});
-            s_mfma_t(smem, s_a);
-
-            // Step t: the contraction S^T of tile t+1, the contraction P.V of tile t-1 and the softmax of
-            // tile t are mutually independent and sit in one straight-line block, so the 48 MFMAs and the
-            // vector-ALU work of a step can interleave.
-            auto step = [&](int t, f32x4 (&s_cur)[2][MT], f32x4 (&s_next)[2][MT]) {
-                // my quarter of tile t+1 has landed once at most the loads of tiles t+2 .. t+NS-3 are pending
-                if (irregular || t + NS - 3 >= ntiles) wait_vmcnt(0); else wait_vmcnt(kPerTile * (NS - 4));
-                __syncthreads();                                 // tile t+1 visible; everyone is done with tile t-2
-                if (t + NS - 2 < ntiles) issue(t + NS - 2);      // into the slot tile t-2 occupied
-                const int pos0 = c0 + t * kTile;
-                const bool mask = pos0 + kTile > S - R;          // touches the new rows or the ragged end
-                float c_eff = c;
-                if (t == 0 || mask || raise_always) {            // rare: maxima, reference, masking
-                    float mx[MT];
-                    if (mask) softmax_max<D, MT, true>(w, s_cur, mx, pos0, S, R, c, g);
-                    else softmax_max<D, MT, false>(w, s_cur, mx, pos0, S, R, c, g);
-    #pragma unroll
-                    for (int rt = 0; rt < MT; ++rt)              // mx = -inf (nothing visible) leaves it unset
-                        if (raise_always || w.m_run[rt] == kNegBig) w.m_run[rt] = fmaxf(w.m_run[rt], mx[rt]);
-                    if (mask) c_eff = 1.0f;                      // the masked form has scaled the scores in place
-                }
-                s_mfma_t(smem + ((t + 1) % NS) * W::kSlot, s_next);      // unused after the chunk's last tile
-                pv_mfma_t(smem + ((t + NS - 1) % NS) * W::kSlot, pf_prev);
-                softmax_exp<D, MT, false>(w, s_cur, c_eff, pf_prev);     // fma(-inf, 1, -ref) = -inf -> weight 0
-            };
-            for (int t = 0; t < ntiles; t += 2) {
-                step(t, s_a, s_b);
-                if (t + 1 < ntiles) step(t + 1, s_b, s_a);
-            }
-            pv_mfma_t(smem + ((ntiles - 1) % NS) * W::kSlot, pf_prev);
-        } else {
-            // two workgroups per compute unit: the other workgroup's wavefront on the same SIMD fills
-            // the gaps, so the loop stays simple (S^T, softmax, P.V of one tile per step)
-            for (int t = 0; t < NS - 1; ++t)
-                if (t < ntiles) issue(t);
-            for (int t = 0; t < ntiles; ++t) {
-                // my quarter of tile t has landed once at most the loads of tiles t+1 .. t+NS-2 are pending
-                if (irregular || t + NS - 2 >= ntiles) wait_vmcnt(0); else wait_vmcnt(kPerTile * (NS - 2));
-                __syncthreads();                             // tile t visible; everyone is done with tile t-1
-                if (t + NS - 1 < ntiles) issue(t + NS - 1);  // into the slot tile t-1 occupied
-                const int pos0 = c0 + t * kTile;
-                const bool mask = pos0 + kTile > S - R;
-                const char *tile = smem + (t % NS) * W::kSlot;
-                f32x4 sacc[2][MT];
-                bf16x8 pf[MT];
-                s_mfma_t(tile, sacc);
-                float c_eff = c;
-                if (t == 0 || mask || raise_always) {
-                    float mx[MT];
-                    if (mask) softmax_max<D, MT, true>(w, sacc, mx, pos0, S, R, c, g);
-                    else softmax_max<D, MT, false>(w, sacc, mx, pos0, S, R, c, g);
+                for (int pt = 0; pt < 2; ++pt) kf[pt] = *(const bf16x8 *)(tile + koff[ks] + pt * 16 * W::kRowBytes);
+#pragma unroll
+                for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
                     for (int rt = 0; rt < MT; ++rt)
-                        if (raise_always || w.m_run[rt] == kNegBig) w.m_run[rt] = fmaxf(w.m_run[rt], mx[rt]);
-                    if (mask) c_eff = 1.0f;
-                }
-                softmax_exp<D, MT, false>(w, sacc, c_eff, pf);
-                pv_mfma_t(tile, pf);
+                        sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
+            }
+            // ---- softmax weights
+            float c_eff = c;
+            if (t == 0 || mask || raise_always) {            // rare: maxima, reference, masking
+                float mx[MT];
+                if (mask) softmax_max<D, MT, true>(w, sacc, mx, pos0, S, R, c, g);
+                else softmax_max<D, MT, false>(w, sacc, mx, pos0, S, R, c, g);
+#pragma unroll
+                for (int rt = 0; rt < MT; ++rt)              // mx = -inf (nothing visible) leaves it unset
+                    if (raise_always || w.m_run[rt] == kNegBig) w.m_run[rt] = fmaxf(w.m_run[rt], mx[rt]);
+                if (mask) c_eff = 1.0f;                      // the masked form has scaled the scores in place
+            }
+            bf16x8 pf[MT];
+            softmax_exp<D, MT, false>(w, sacc, c_eff, pf);   // fma(-inf, 1, -ref) = -inf -> weight 0
+            // ---- O^T += V^T . P^T
+#pragma unroll
+            for (int dt = 0; dt < D / 16; ++dt) {
+                const char *a0 = tile + voff[dt];
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(a0 + 16 * W::kRowBytes));
+                s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, cat);
+#pragma unroll
+                for (int rt = 0; rt < MT; ++rt)
+                    w.oacc[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], w.oacc[dt][rt], 0, 0, 0);
             }
         }
 
@@ -991,13 +968,12 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
             if (chunk < 1024) chunk = 1024;
             if (chunk > 8192) chunk = 8192;
         }
-        // chunks start on page boundaries and span at most 64*kPageRegs pages
+        // chunks start on page boundaries (when a page fits) and span at most 256 tiles
         int64_t unit = 128;
-        while (unit % page_size != 0) unit += 128;           // lcm(128, page_size)
+        while (unit % page_size != 0 && unit < kMaxChunk) unit += 128;     // lcm(128, page_size) if it fits
+        if (unit % page_size != 0) unit = 128;
         chunk = (chunk + unit - 1) / unit * unit;
-        const int64_t cap = (int64_t)64 * kPageRegs * page_size / unit * unit;
-        if (cap < unit) return AGENTSAM_ERR_UNSUPPORTED;
-        if (chunk > cap) chunk = cap;
+        if (chunk > kMaxChunk) chunk = kMaxChunk / unit * unit;
         pl->chunk = (int)chunk;
     }
     pl->nchunks_max = (int)((smax + pl->chunk - 1) / pl->chunk);
@@ -1013,9 +989,9 @@ void launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st) {
         const int mt = (rpw + 15) / 16;
         // two workgroups per compute unit, each with a ring of 4 tile slots
         constexpr int NS = 4;
-        if (mt == 1) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS, false>), grid, dim3(256), 0, st, p);
-        else if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS, false>), grid, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 3, NS, false>), grid, dim3(256), 0, st, p);
+        if (mt == 1) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS>), grid, dim3(256), 0, st, p);
+        else if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS>), grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 3, NS>), grid, dim3(256), 0, st, p);
         return;
     }
     const int mt = (p.rows + 15) / 16;
