@@ -633,12 +633,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     // piece j of a tile (1 KB = kRPI rows): my 16 bytes are row j*kRPI + lrow, and I fetch the global
     // chunk that belongs in my LDS chunk under the XOR swizzle
     const int lrow = lane / W::kCPR, lslot = lane % W::kCPR;
-    unsigned ld_goff[W::kPieces];                            // byte offset inside the tile in global memory
-#pragma unroll
-    for (int j = 0; j < W::kPieces; ++j) {
-        const int row = j * W::kRPI + lrow;
-        ld_goff[j] = (unsigned)(row * D + (lslot ^ (row & (W::kCPR - 1))) * 8) * 2u;
-    }
     // fragment reads: K rows n and n+16 (the swizzle only sees row & 15), V rows 4g+jq and +16
     int koff[D / 32], voff[D / 16];
 #pragma unroll
@@ -664,6 +658,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         const char *vb = (const char *)uniform_ptr((const char *)p.vc + base);
         const int slot_off = (t % NS) * W::kSlot;
         const int rows_left = S - pos0;                      // rows >= rows_left lie past the sequence
+        unsigned ld_goff[W::kPieces];                        // my byte offsets inside the tile in global memory
+#pragma unroll                                               // (recomputed here: only every 4th tile is mine)
+        for (int j = 0; j < W::kPieces; ++j) {
+            const int row = j * W::kRPI + lrow;
+            ld_goff[j] = (unsigned)(row * D + (lslot ^ (row & (W::kCPR - 1))) * 8) * 2u;
+        }
         if (page_ok && rows_left >= kTile) {                 // the usual case: a full tile, all lanes load
             lds_dma_tile<D>(kb, vb, ld_goff, smem_addr + slot_off);
         } else {
@@ -714,6 +714,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
                     for (int rt = 0; rt < MT; ++rt)
                         sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
             }
+            // ---- first half of the V fragments: issued now so their LDS latency hides under the softmax
+            auto load_vf = [&](int dt) {
+                const char *a0 = tile + voff[dt];
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(a0 + 16 * W::kRowBytes));
+                s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                return __builtin_bit_cast(bf16x8, cat);
+            };
+            constexpr int kHalf = D / 32;
+            bf16x8 vfa[kHalf];
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i) vfa[i] = load_vf(i);
+            __builtin_amdgcn_sched_barrier(0);               // keep the reads above the arithmetic below
             // ---- softmax weights
             float c_eff = c;
             if (t == 0 || mask || raise_always) {            // rare: maxima, reference, masking
@@ -727,19 +741,21 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             }
             bf16x8 pf[MT];
             softmax_exp<D, MT, false>(w, sacc, c_eff, pf);   // fma(-inf, 1, -ref) = -inf -> weight 0
-            // ---- O^T += V^T . P^T
+            // ---- O^T += V^T . P^T ; the second half of V is fetched while the first is multiplied
+            bf16x8 vfb[kHalf];
 #pragma unroll
-            for (int dt = 0; dt < D / 16; ++dt) {
-                const char *a0 = tile + voff[dt];
-                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
-                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4 *)(a0 + 16 * W::kRowBytes));
-                s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, cat);
+            for (int i = 0; i < kHalf; ++i) vfb[i] = load_vf(kHalf + i);
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i)
 #pragma unroll
                 for (int rt = 0; rt < MT; ++rt)
-                    w.oacc[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], w.oacc[dt][rt], 0, 0, 0);
-            }
+                    w.oacc[i][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfa[i], pf[rt], w.oacc[i][rt], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i)
+#pragma unroll
+                for (int rt = 0; rt < MT; ++rt)
+                    w.oacc[kHalf + i][rt] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfb[i], pf[rt], w.oacc[kHalf + i][rt], 0, 0, 0);
         }
 
         bool bad = false;
