@@ -81,13 +81,19 @@ int sam_flat_sizes(const sam_t *s, int64_t *n_states, int64_t *n_edges, int64_t 
  *   lastpos[ns]   the largest end position of the state's strings that still has a
  *                 continuation (next token exists and is not sep_token), or -1
  *   corpus[nt]    the token memory itself
+ *   state_rec[4*ns] one 16-byte record per state for the draft walk, so that following a
+ *                 transition costs one dependent load in the common case:
+ *                   [0] token of the state's first (smallest-token) transition, -1 if none
+ *                   [1] its destination d if it is the only transition, -2-d if there are more
+ *                       (the rest are found in the CSR row), -1 if none
+ *                   [2] suffix link (as in link[])    [3] len of the suffix link's state (0 for the root)
  * Several automata can be packed back to back in one set of arrays: state ids (link,
  * edge_dst) are offset by state_base, row_ptr values by edge_base, lastpos by corpus_base,
  * and the pointers passed here address this automaton's slice (row_ptr[ns] of one slice is
  * row_ptr[0] of the next). */
 int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t corpus_base,
                 int32_t *len, int32_t *link, int32_t *row_ptr, int32_t *edge_tok,
-                int32_t *edge_dst, int32_t *lastpos, int32_t *corpus);
+                int32_t *edge_dst, int32_t *lastpos, int32_t *corpus, int32_t *state_rec);
 
 void sam_free(sam_t *s);
 
@@ -101,14 +107,15 @@ void sam_free(sam_t *s);
  * taken (falling back to shorter suffixes along the suffix links when none has), and the k tokens
  * after it are emitted, stopping before corpus_end[b] and before sep_token.
  *
- * Device inputs : the seven flattened arrays; root[B], corpus_end[B] (exclusive end of the
+ * Device inputs : the flattened arrays (len and link are not read: state_rec carries what the
+ *                 walk needs of them); root[B], corpus_end[B] (exclusive end of the
  *                 session's memory in `corpus`), recent[B,m], recent_len[B] (0..m).
  * Device outputs: draft[B,k] (-1 padded), n_draft[B], match_len[B], match_end[B] (index into
  *                 `corpus`, -1 when nothing matched).  match_len < min_match gives no draft.
  * Limits: 0 <= k <= 64, 1 <= m <= 64 (one wavefront holds a window), B >= 0. */
 int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
               const int32_t *edge_tok, const int32_t *edge_dst, const int32_t *lastpos,
-              const int32_t *corpus, const int32_t *root, const int32_t *corpus_end,
+              const int32_t *corpus, const int32_t *state_rec, const int32_t *root, const int32_t *corpus_end,
               const int32_t *recent, const int32_t *recent_len,
               int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
               int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,

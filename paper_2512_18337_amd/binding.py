@@ -47,10 +47,10 @@ def lib():
         L.sam_build.argtypes = [_i32p, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(_vp)]
         L.sam_append.argtypes = [_vp, _i32p, ctypes.c_int64]
         L.sam_flat_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 3
-        L.sam_flatten.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_i32p] * 7
+        L.sam_flatten.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_i32p] * 8
         L.sam_free.argtypes = [_vp]
         L.sam_free.restype = None
-        L.sam_draft.argtypes = [_vp] * 11 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp]
+        L.sam_draft.argtypes = [_vp] * 12 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp]
         L.spec_verify_attn_workspace.argtypes = [ctypes.c_int32] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
         L.spec_verify_attn.argtypes = ([_vp, _vp, _vp, _vp, ctypes.c_int32, _vp] + [ctypes.c_int32] * 6 +
                                        [ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
@@ -123,6 +123,7 @@ class FlatSam:
     edge_dst: object
     lastpos: object
     corpus: object
+    state_rec: object          # [4*ns] walk records (see sam_flatten in the header)
     roots: np.ndarray          # [n_automata] root state id of each automaton
     corpus_begin: np.ndarray   # [n_automata]
     corpus_end: np.ndarray     # [n_automata] exclusive
@@ -133,7 +134,7 @@ class FlatSam:
         # zero-length arrays still need a valid (non-null) device pointer
         pad = lambda a: a if a.shape[0] > 0 else np.zeros(1, dtype=np.int32)
         return FlatSam(cv(self.len), cv(self.link), cv(self.row_ptr), cv(pad(self.edge_tok)),
-                       cv(pad(self.edge_dst)), cv(self.lastpos), cv(pad(self.corpus)),
+                       cv(pad(self.edge_dst)), cv(self.lastpos), cv(pad(self.corpus)), cv(self.state_rec),
                        self.roots, self.corpus_begin, self.corpus_end)
 
 
@@ -143,14 +144,14 @@ def sam_flatten(sams: Sequence[Sam]) -> FlatSam:
     ns, ne, nt = (sum(x[i] for x in sizes) for i in range(3))
     out = FlatSam(np.zeros(ns, np.int32), np.zeros(ns, np.int32), np.zeros(ns + 1, np.int32),
                   np.zeros(ne, np.int32), np.zeros(ne, np.int32), np.zeros(ns, np.int32),
-                  np.zeros(nt, np.int32), np.zeros(len(sams), np.int32), np.zeros(len(sams), np.int32),
-                  np.zeros(len(sams), np.int32))
+                  np.zeros(nt, np.int32), np.zeros(4 * ns, np.int32), np.zeros(len(sams), np.int32),
+                  np.zeros(len(sams), np.int32), np.zeros(len(sams), np.int32))
     sb = eb = cb = 0
     for i, (s, (a, b, c)) in enumerate(zip(sams, sizes)):
         _check(lib().sam_flatten(s._h, sb, eb, cb, _npp(out.len[sb:]), _npp(out.link[sb:]),
                                  _npp(out.row_ptr[sb:]), _npp(out.edge_tok[eb:]) if b else None,
                                  _npp(out.edge_dst[eb:]) if b else None, _npp(out.lastpos[sb:]),
-                                 _npp(out.corpus[cb:]) if c else None), "sam_flatten")
+                                 _npp(out.corpus[cb:]) if c else None, _npp(out.state_rec[4 * sb:])), "sam_flatten")
         out.roots[i], out.corpus_begin[i], out.corpus_end[i] = sb, cb, cb + c
         sb, eb, cb = sb + a, eb + b, cb + c
     return out
@@ -186,7 +187,7 @@ def sam_draft(flat: FlatSam, root, corpus_end, recent, recent_len, k: int, sep_t
     match_len = torch.empty((B,), dtype=torch.int32, device=dev)
     match_end = torch.empty((B,), dtype=torch.int32, device=dev)
     rc = lib().sam_draft(_dp(flat.len), _dp(flat.link), _dp(flat.row_ptr), _dp(flat.edge_tok), _dp(flat.edge_dst),
-                         _dp(flat.lastpos), _dp(flat.corpus), _dp(root), _dp(corpus_end), _dp(recent),
+                         _dp(flat.lastpos), _dp(flat.corpus), _dp(flat.state_rec), _dp(root), _dp(corpus_end), _dp(recent),
                          _dp(recent_len), B, m, k, min_match, sep_token,
                          _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
                          _stream_ptr())

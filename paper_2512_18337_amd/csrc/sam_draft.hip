@@ -39,9 +39,9 @@ __device__ __forceinline__ int find_edge(const int32_t *__restrict__ edge_tok,
 }
 
 __global__ __launch_bounds__(64) void sam_draft_kernel(
-    const int32_t *__restrict__ len, const int32_t *__restrict__ link, const int32_t *__restrict__ row_ptr,
-    const int32_t *__restrict__ edge_tok, const int32_t *__restrict__ edge_dst,
-    const int32_t *__restrict__ lastpos, const int32_t *__restrict__ corpus,
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_tok,
+    const int32_t *__restrict__ edge_dst, const int32_t *__restrict__ lastpos,
+    const int32_t *__restrict__ corpus, const int4 *__restrict__ state_rec,
     const int32_t *__restrict__ root_arr, const int32_t *__restrict__ corpus_end,
     const int32_t *__restrict__ recent, const int32_t *__restrict__ recent_len,
     int m, int k, int min_match, int sep,
@@ -54,16 +54,25 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     // lane i holds the i-th token of the (right-aligned) window
     const int wtok = (lane < ql) ? recent[(int64_t)b * m + (m - ql) + lane] : -1;
 
-    // longest suffix of the window that occurs in the memory: state s, matched length l
+    // longest suffix of the window that occurs in the memory: state s, matched length l.
+    // One 16-byte record per state {first token, its destination (or -2-d when the state has
+    // more transitions), suffix link, len of the link's state} makes the common step - a state
+    // with a single transition that matches - cost one dependent load.
     int s = root, l = 0;
     for (int t = 0; t < ql; ++t) {
         const int c = wave_bcast(wtok, t);
         for (;;) {
-            const int dst = find_edge(edge_tok, edge_dst, row_ptr[s], row_ptr[s + 1], c, lane);
+            const int4 rec = state_rec[s];
+            int dst = -1;
+            if (rec.x == c) {
+                dst = rec.y >= 0 ? rec.y : -2 - rec.y;
+            } else if (rec.y < -1 && c > rec.x) {          // rows are sorted: c can only be further right
+                dst = find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane);
+            }
             if (dst >= 0) { s = dst; ++l; break; }
             if (s == root) { l = 0; break; }
-            s = link[s];
-            l = len[s];
+            s = rec.z;
+            l = rec.w;
         }
         s = __builtin_amdgcn_readfirstlane(s);
         l = __builtin_amdgcn_readfirstlane(l);
@@ -75,8 +84,9 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     while (s != root) {
         const int lp = lastpos[s];
         if (lp >= 0) { e = lp; break; }
-        s = link[s];
-        L = len[s];
+        const int4 rec = state_rec[s];
+        s = rec.z;
+        L = rec.w;
     }
     if (e < 0 || L < min_match) { e = -1; L = 0; }
 
@@ -101,20 +111,22 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
 
 extern "C" int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
                          const int32_t *edge_tok, const int32_t *edge_dst, const int32_t *lastpos,
-                         const int32_t *corpus, const int32_t *root, const int32_t *corpus_end,
+                         const int32_t *corpus, const int32_t *state_rec, const int32_t *root,
+                         const int32_t *corpus_end,
                          const int32_t *recent, const int32_t *recent_len,
                          int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
                          int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
                          void *stream) {
     if (B < 0 || m < 1 || m > 64 || k < 0 || k > 64 || min_match < 0) return AGENTSAM_ERR_ARG;
     if (B == 0) return AGENTSAM_OK;
-    if (!len || !link || !row_ptr || !lastpos || !root || !corpus_end || !recent || !recent_len ||
+    (void)len; (void)link;                                   // carried by state_rec
+    if (!row_ptr || !lastpos || !state_rec || !root || !corpus_end || !recent || !recent_len ||
         !n_draft || !match_len || !match_end || (k > 0 && !draft))
         return AGENTSAM_ERR_NULL;
     // edge_tok / edge_dst / corpus may be NULL only for an automaton with no transitions (empty
     // memory): then every row is empty and nothing matches, so they are never dereferenced.
     hipLaunchKernelGGL(sam_draft_kernel, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
-                       len, link, row_ptr, edge_tok, edge_dst, lastpos, corpus, root, corpus_end,
+                       row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
                        draft, n_draft, match_len, match_end);
     AGENTSAM_LAUNCH_CHECK();

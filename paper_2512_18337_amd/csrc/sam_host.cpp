@@ -173,8 +173,8 @@ int sam_flat_sizes(const sam_t *s, int64_t *n_states, int64_t *n_edges, int64_t 
 
 int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t corpus_base,
                 int32_t *len, int32_t *link, int32_t *row_ptr, int32_t *edge_tok,
-                int32_t *edge_dst, int32_t *lastpos, int32_t *corpus) {
-    if (!s || !len || !link || !row_ptr || !lastpos) return AGENTSAM_ERR_NULL;
+                int32_t *edge_dst, int32_t *lastpos, int32_t *corpus, int32_t *state_rec) {
+    if (!s || !len || !link || !row_ptr || !lastpos || !state_rec) return AGENTSAM_ERR_NULL;
     const int64_t ns = (int64_t)s->len.size(), ne = (int64_t)s->e_tok.size(), nt = (int64_t)s->corpus.size();
     if ((ne > 0 && (!edge_tok || !edge_dst)) || (nt > 0 && !corpus)) return AGENTSAM_ERR_NULL;
     if (state_base < 0 || edge_base < 0 || corpus_base < 0) return AGENTSAM_ERR_ARG;
@@ -210,6 +210,11 @@ int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t c
                 edge_dst[at] = pr.second + state_base;
                 ++at;
             }
+            int32_t *rec = state_rec + 4 * v;
+            rec[0] = tmp.empty() ? -1 : tmp[0].first;
+            rec[1] = tmp.empty() ? -1 : (tmp.size() == 1 ? tmp[0].second + state_base : -2 - (tmp[0].second + state_base));
+            rec[2] = link[v];
+            rec[3] = s->link[v] < 0 ? 0 : s->len[s->link[v]];
         }
         row_ptr[ns] = (int32_t)(at + edge_base);
         if (nt > 0) std::memcpy(corpus, s->corpus.data(), (size_t)nt * sizeof(int32_t));

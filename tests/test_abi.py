@@ -36,9 +36,9 @@ def test_argument_errors_without_a_gpu():
     assert L.spec_verify_attn_workspace(64, 9, 32, 8, 128, 64, 512, binding.BF16, ctypes.byref(n)) == 0
     assert n.value == 64 * 8 * 4 * 36 * 130 * 4          # 32768 / 8192 = 4 chunks of 36 packed rows
     # entry points reject bad sizes before touching the device
-    assert L.sam_draft(*([None] * 11), 4, 65, 4, 1, 0, *([None] * 5)) == -2
-    assert L.sam_draft(*([None] * 11), 4, 16, 4, 1, 0, *([None] * 5)) == -1
-    assert L.sam_draft(*([None] * 11), 0, 16, 4, 1, 0, *([None] * 5)) == 0
+    assert L.sam_draft(*([None] * 12), 4, 65, 4, 1, 0, *([None] * 5)) == -2
+    assert L.sam_draft(*([None] * 12), 4, 16, 4, 1, 0, *([None] * 5)) == -1
+    assert L.sam_draft(*([None] * 12), 0, 16, 4, 1, 0, *([None] * 5)) == 0
     assert L.spec_accept(None, 0, None, None, 4, 64, 100, None, None, None, None) == -2
     assert L.spec_accept(None, 7, None, None, 4, 4, 100, None, None, None, None) == -3
     assert L.spec_accept(None, 0, None, None, 4, 4, 100, None, None, None, None) == -1

@@ -70,6 +70,16 @@ def test_size_bounds_and_substring_count(seed):
             assert np.all(np.diff(row) > 0)
             assert np.all(f.len[f.edge_dst[f.row_ptr[v]:f.row_ptr[v + 1]]] >= f.len[v] + 1)
         assert f.row_ptr[0] == 0 and f.row_ptr[ns] == ne and np.array_equal(f.corpus, T)
+        # the 16-byte walk records restate the first transition, the link and the link's len
+        rec = f.state_rec.reshape(ns, 4)
+        for v in range(ns):
+            r0, r1 = f.row_ptr[v], f.row_ptr[v + 1]
+            if r1 == r0:
+                assert rec[v, 0] == -1 and rec[v, 1] == -1
+            else:
+                assert rec[v, 0] == f.edge_tok[r0]
+                assert rec[v, 1] == (f.edge_dst[r0] if r1 - r0 == 1 else -2 - f.edge_dst[r0])
+            assert rec[v, 2] == f.link[v] and rec[v, 3] == (0 if f.link[v] < 0 else f.len[f.link[v]])
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -97,7 +107,7 @@ def test_append_equals_build_and_updates_eligibility():
     b = A.sam_build(T[:77], sep_token=3)
     A.sam_append(b, T[77:150]); A.sam_append(b, T[150:]); A.sam_append(b, [])
     fa, fb = A.sam_flatten([a]), A.sam_flatten([b])
-    for name in ("len", "link", "row_ptr", "edge_tok", "edge_dst", "lastpos", "corpus"):
+    for name in ("len", "link", "row_ptr", "edge_tok", "edge_dst", "lastpos", "corpus", "state_rec"):
         assert np.array_equal(getattr(fa, name), getattr(fb, name)), name
     # the old tail becomes a usable end position once a token follows it
     s = A.sam_build([1, 2, 3], sep_token=9)
