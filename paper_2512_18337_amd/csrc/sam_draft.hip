@@ -49,8 +49,8 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     int32_t *__restrict__ match_end) {
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
-    const int root = root_arr[b];
-    const int ql = max(0, min(m, recent_len[b]));
+    const int root = __builtin_amdgcn_readfirstlane(root_arr[b]);
+    const int ql = __builtin_amdgcn_readfirstlane(max(0, min(m, recent_len[b])));
     // lane i holds the i-th token of the (right-aligned) window
     const int wtok = (lane < ql) ? recent[(int64_t)b * m + (m - ql) + lane] : -1;
 
@@ -58,24 +58,26 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     // One 16-byte record per state {first token, its destination (or -2-d when the state has
     // more transitions), suffix link, len of the link's state} makes the common step - a state
     // with a single transition that matches - cost one dependent load.
-    int s = root, l = 0;
+    // s, l and every branch below are wave-uniform and kept in scalar registers, so the record is
+    // fetched with a scalar load and the loop carries no exec-mask bookkeeping.
+    int s = __builtin_amdgcn_readfirstlane(root), l = 0;
     for (int t = 0; t < ql; ++t) {
-        const int c = wave_bcast(wtok, t);
+        const int c = __builtin_amdgcn_readlane(wtok, t);
         for (;;) {
             const int4 rec = state_rec[s];
+            const int r0 = __builtin_amdgcn_readfirstlane(rec.x), r1 = __builtin_amdgcn_readfirstlane(rec.y);
             int dst = -1;
-            if (rec.x == c) {
-                dst = rec.y >= 0 ? rec.y : -2 - rec.y;
-            } else if (rec.y < -1 && c > rec.x) {          // rows are sorted: c can only be further right
-                dst = find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane);
+            if (r0 == c) {
+                dst = r1 >= 0 ? r1 : -2 - r1;
+            } else if (r1 < -1 && c > r0) {                // rows are sorted: c can only be further right
+                dst = __builtin_amdgcn_readfirstlane(
+                    find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane));
             }
             if (dst >= 0) { s = dst; ++l; break; }
             if (s == root) { l = 0; break; }
-            s = rec.z;
-            l = rec.w;
+            s = __builtin_amdgcn_readfirstlane(rec.z);
+            l = __builtin_amdgcn_readfirstlane(rec.w);
         }
-        s = __builtin_amdgcn_readfirstlane(s);
-        l = __builtin_amdgcn_readfirstlane(l);
     }
 
     // most recent occurrence that still has a continuation; all strings of one state share their
