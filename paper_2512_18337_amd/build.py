@@ -21,6 +21,7 @@ def build(verbose: bool = False) -> str:
     for s in SOURCES:
         path = os.path.join(CSRC, s)
         cmd += (["-x", "hip", path] if s.endswith(".hip") else ["-x", "hip", path])
+    cmd += os.environ.get("AGENTSAM_EXTRA_HIPCC_FLAGS", "").split()     # timing experiments only
     cmd += ["-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -62,6 +62,14 @@ struct AttnParams {
     int out_bf16;
 };
 
+// A session of S positions is cut into ceil(S / max_chunk) chunks of EQUAL size (rounded up to 128
+// positions), so a ragged batch has no tiny trailing workgroups: every workgroup streams between
+// half a maximum chunk and a full one.
+__device__ __forceinline__ void chunk_geometry(int S, int max_chunk, int &nchunks, int &chunk_len) {
+    nchunks = (S + max_chunk - 1) / max_chunk;
+    chunk_len = nchunks > 0 ? (((S + nchunks - 1) / nchunks + 127) & ~127) : max_chunk;
+}
+
 // workspace record of one (session, head group, chunk): o[rows_pad][D], m[rows_pad], l[rows_pad]
 __device__ __forceinline__ int64_t ws_record_floats(int rows_pad, int D) { return (int64_t)rows_pad * (D + 2); }
 
@@ -361,13 +369,14 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
     // (a common prefix) run back to back on the same XCD and meet in its L2.
     const int kvh = blockIdx.x % p.Hkv;
     const int b = (blockIdx.x / p.Hkv) % p.B;
-    const int chunk = blockIdx.x / (p.B * p.Hkv);
     const int S = min(p.seq[b], p.max_pages * p.P);          // never index past the block table
-    const int c0 = chunk * p.chunk;
-    if (c0 >= S) return;                                     // uniform over the workgroup
-    const int c1 = min(S, c0 + p.chunk);
+    int nchunks_b, chunk_len;
+    chunk_geometry(S, p.chunk, nchunks_b, chunk_len);
+    const int chunk = blockIdx.x / (p.B * p.Hkv);
+    if (chunk >= nchunks_b) return;                          // uniform over the workgroup
+    const int c0 = chunk * chunk_len;
+    const int c1 = min(S, c0 + chunk_len);
     const int ntiles = (c1 - c0 + kTile - 1) / kTile;
-    const int nchunks_b = (S + p.chunk - 1) / p.chunk;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
@@ -565,9 +574,9 @@ __device__ __forceinline__ const void *uniform_ptr(const void *ptr) {
 // A whole tile (all 1 KB pieces of K, then of V at +kKT) in one block; M0 is saved once.
 #define AGENTSAM_DMA_PIECE(J, G)                       \
     "s_add_u32 m0, %1, " #J "*1024\n\ts_nop 0\n\t"     \
-    "global_load_lds_dwordx4 " G ", %2\n\t"            \
+    "global_load_lds_dwordx4 " G ", %2 nt\n\t"         \
     "s_add_u32 m0, %1, %c4+" #J "*1024\n\ts_nop 0\n\t" \
-    "global_load_lds_dwordx4 " G ", %3\n\t"
+    "global_load_lds_dwordx4 " G ", %3 nt\n\t"
 template <int D>
 __device__ __forceinline__ void lds_dma_tile(const void *kb, const void *vb, const unsigned (&goff)[WideCfg<D>::kPieces],
                                              unsigned slot_addr /* uniform LDS byte address */) {
@@ -608,13 +617,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
 
     const int kvh = blockIdx.x % p.Hkv;
     const int b = (blockIdx.x / p.Hkv) % p.B;
-    const int chunk = blockIdx.x / (p.B * p.Hkv);
     const int S = min(p.seq[b], p.max_pages * p.P);
-    const int c0 = chunk * p.chunk;
-    if (c0 >= S) return;
-    const int c1 = min(S, c0 + p.chunk);
+    int nchunks_b, chunk_len;
+    chunk_geometry(S, p.chunk, nchunks_b, chunk_len);
+    const int chunk = blockIdx.x / (p.B * p.Hkv);
+    if (chunk >= nchunks_b) return;
+    const int c0 = chunk * chunk_len;
+    const int c1 = min(S, c0 + chunk_len);
     const int ntiles = (c1 - c0 + kTile - 1) / kTile;
-    const int nchunks_b = (S + p.chunk - 1) / p.chunk;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
@@ -648,7 +658,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     const unsigned smem_addr = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem;   // LDS byte address
 
     // fetch tile t into its ring slot (called by one wavefront)
-    auto issue = [&](int t) {
+    auto issue = [&](int t, int slot_idx) {
         const int pos0 = c0 + t * kTile;
         const int page = tile_page(cp, t);
         const bool page_ok = page >= 0 && (int64_t)page < p.num_pages;
@@ -656,7 +666,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         const int64_t base = (int64_t)(page_ok ? page : 0) * page_bytes + head_bytes + (int64_t)slot_in_page * (D * 2);
         const char *kb = (const char *)uniform_ptr((const char *)p.kc + base);
         const char *vb = (const char *)uniform_ptr((const char *)p.vc + base);
-        const int slot_off = (t % NS) * W::kSlot;
+        const int slot_off = slot_idx * W::kSlot;
         const int rows_left = S - pos0;                      // rows >= rows_left lie past the sequence
         unsigned ld_goff[W::kPieces];                        // my byte offsets inside the tile in global memory
 #pragma unroll                                               // (recomputed here: only every 4th tile is mine)
@@ -687,16 +697,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     for (int attempt = 0;; ++attempt) {
         const bool raise_always = attempt == 1;
         for (int t = 0; t < NS - 1; ++t)
-            if (t < ntiles && wave == (t & (kWaves - 1))) issue(t);
-        for (int t = 0; t < ntiles; ++t) {
+            if (t < ntiles && wave == (t & (kWaves - 1))) issue(t, t);
+        int slot_cur = 0;                                    // ring slot of tile t (t mod NS, kept incrementally)
+        for (int t = 0; t < ntiles; ++t, slot_cur = (slot_cur + 1 == NS) ? 0 : slot_cur + 1) {
+#ifndef AGENTSAM_EXP_NO_DMA
             if (wave == (t & (kWaves - 1))) wait_vmcnt0();   // the tile I fetched has landed
+#endif
             __syncthreads();                                 // tile t visible; everyone is done with tile t-1
             const int tn = t + NS - 1;                       // goes into the slot tile t-1 occupied
-            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn);
+#ifndef AGENTSAM_EXP_NO_DMA
+            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn, slot_cur == 0 ? NS - 1 : slot_cur - 1);
+#endif
+#ifdef AGENTSAM_EXP_NO_COMPUTE
+            continue;
+#endif
 
             const int pos0 = c0 + t * kTile;
             const bool mask = pos0 + kTile > S - R;          // touches the new rows or the ragged end
-            const char *tile = smem + (t % NS) * W::kSlot;
+            const char *tile = smem + slot_cur * W::kSlot;
             // ---- S^T = K . Q^T
             f32x4 sacc[2][MT];
 #pragma unroll
@@ -761,8 +779,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         bool bad = false;
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt) bad = bad || !(w.l_part[rt] < 1.0e30f);    // also catches NaN
-        // the barrier also keeps a fast wavefront from refilling ring slots others still read
-        const bool redo = __syncthreads_or(bad) != 0;
+        // Workgroup-wide OR through the first word of the (now idle) ring: the ring takes the whole
+        // LDS share of a workgroup, so there is no room for a separate flag.  The first barrier also
+        // keeps a fast wavefront from refilling ring slots others still read.
+        __syncthreads();
+        if (tid == 0) *(volatile int *)smem = 0;
+        __syncthreads();
+        if (bad) *(volatile int *)smem = 1;
+        __syncthreads();
+        const bool redo = *(volatile int *)smem != 0;
+        __syncthreads();                                     // everyone has read it before the ring refills
         if (attempt == 2 || (attempt == 0 && !redo)) break;
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt) {
@@ -1003,8 +1029,8 @@ void launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st) {
     if (wide) {
         const int rpw = (p.rows + kWaves - 1) / kWaves;
         const int mt = (rpw + 15) / 16;
-        // two workgroups per compute unit, each with a ring of 4 tile slots
-        constexpr int NS = 4;
+        // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS
+        constexpr int NS = 65536 / WideCfg<D>::kSlot;
         if (mt == 1) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS>), grid, dim3(256), 0, st, p);
         else if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS>), grid, dim3(256), 0, st, p);
         else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 3, NS>), grid, dim3(256), 0, st, p);
