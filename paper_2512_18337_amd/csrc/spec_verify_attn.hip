@@ -610,7 +610,7 @@ __device__ __forceinline__ void wait_vmcnt0() {
     __builtin_amdgcn_s_waitcnt(0x0f70);
 }
 
-template <int D, int MT, int NS>
+template <int D, int MT, int NS, bool XT>
 __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
     using W = WideCfg<D>;
     __shared__ __align__(16) char smem[NS * W::kSlot];
@@ -632,26 +632,34 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     const int R = p.R;
     const float c = p.scale_log2;
 
-    const int rpw = (p.rows + kWaves - 1) / kWaves;          // packed rows per wavefront (<= 16*MT)
+    // Row assignment.  Plain: rows split evenly, ceil(rows/4) per wavefront.  XT ("extra tile"): every
+    // wavefront owns 16*MT rows outright and the remaining <= 16 rows form one more row tile that is
+    // processed by wavefront t % 4 for tile t, so its work is spread evenly (136 rows = 4 x 32 + 8 cost
+    // 2.25 row tiles per wavefront instead of 3); the four partial results of those rows are merged
+    // at the end.
+    const int rpw = XT ? 16 * MT : (p.rows + kWaves - 1) / kWaves;
     const int row0 = wave * rpw;
     const int row_end = min(p.rows, row0 + rpw);
+    constexpr int kXRow0 = kWaves * 16 * MT;                 // first extra row (XT only)
     WaveState<D, MT> w;
     init_state<D, MT>(w, p, b, kvh, row0, row_end, n, g);
+    WaveState<D, 1> wx;
+    if (XT) init_state<D, 1>(wx, p, b, kvh, kXRow0, p.rows, n, g);
     const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
 
     // ---- per-lane constants of the tile loop (computed once; the loop only adds uniform bases)
     // piece j of a tile (1 KB = kRPI rows): my 16 bytes are row j*kRPI + lrow, and I fetch the global
     // chunk that belongs in my LDS chunk under the XOR swizzle
     const int lrow = lane / W::kCPR, lslot = lane % W::kCPR;
-    // fragment reads: K rows n and n+16 (the swizzle only sees row & 15), V rows 4g+jq and +16
-    int koff[D / 32], voff[D / 16];
-#pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) koff[ks] = n * W::kRowBytes + (((ks * 4 + g) ^ (n & (W::kCPR - 1))) * 16);
+    // fragment reads: K rows n and n+16 (the swizzle only sees row & 15), V rows 4g+jq and +16.
+    // Under the XOR swizzle the offset for k-step ks is koff0 ^ (ks << 6) and for d-tile dt it is
+    // voff0 ^ (dt << 5); since slot offsets are multiples of 16 KB the XOR can be applied after the
+    // slot offset is added, so only two lane constants stay live.
+    const int koff0 = n * W::kRowBytes + ((g ^ (n & (W::kCPR - 1))) * 16);
+    int voff0;
     {
         const int bq = n & 3, jq = n >> 2, vrow = 4 * g + jq;    // transpose-read lane roles, see pv_mfma
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt)
-            voff[dt] = W::kKT + vrow * W::kRowBytes + (((dt * 2 + (bq >> 1)) ^ (vrow & (W::kCPR - 1))) * 16) + (bq & 1) * 8;
+        voff0 = W::kKT + vrow * W::kRowBytes + (((bq >> 1) ^ (vrow & (W::kCPR - 1))) * 16) + (bq & 1) * 8;
     }
     const int64_t page_bytes = (int64_t)p.Hkv * p.P * D * 2;
     const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
@@ -714,27 +722,36 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
 
             const int pos0 = c0 + t * kTile;
             const bool mask = pos0 + kTile > S - R;          // touches the new rows or the ragged end
-            const char *tile = smem + slot_cur * W::kSlot;
+            const int kx = slot_cur * W::kSlot + koff0, vx = slot_cur * W::kSlot + voff0;   // offsets in the ring
             // ---- S^T = K . Q^T
+            const bool mine = XT && wave == (t & (kWaves - 1));      // my turn for the extra row tile
             f32x4 sacc[2][MT];
+            f32x4 sx[2][1];
 #pragma unroll
-            for (int pt = 0; pt < 2; ++pt)
+            for (int pt = 0; pt < 2; ++pt) {
 #pragma unroll
                 for (int rt = 0; rt < MT; ++rt) sacc[pt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                sx[pt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
             for (int ks = 0; ks < D / 32; ++ks) {
                 bf16x8 kf[2];
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt) kf[pt] = *(const bf16x8 *)(tile + koff[ks] + pt * 16 * W::kRowBytes);
+                for (int pt = 0; pt < 2; ++pt) kf[pt] = *(const bf16x8 *)(smem + (kx ^ (ks << 6)) + pt * 16 * W::kRowBytes);
 #pragma unroll
                 for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
                     for (int rt = 0; rt < MT; ++rt)
                         sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
+                if (mine) {
+#pragma unroll
+                    for (int pt = 0; pt < 2; ++pt)
+                        sx[pt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], wx.qf[0][ks], sx[pt][0], 0, 0, 0);
+                }
             }
             // ---- first half of the V fragments: issued now so their LDS latency hides under the softmax
             auto load_vf = [&](int dt) {
-                const char *a0 = tile + voff[dt];
+                const char *a0 = smem + (vx ^ (dt << 5));
                 s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
                 s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (__attribute__((address_space(3))) s16x4 *)(a0 + 16 * W::kRowBytes));
@@ -759,6 +776,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             }
             bf16x8 pf[MT];
             softmax_exp<D, MT, false>(w, sacc, c_eff, pf);   // fma(-inf, 1, -ref) = -inf -> weight 0
+            bf16x8 pfx[1];
+            if (mine) {
+                if (t < kWaves || mask || raise_always) {    // t < 4: my first extra tile of this pass
+                    float mx1[1];
+                    if (mask) softmax_max<D, 1, true>(wx, sx, mx1, pos0, S, R, c, g);
+                    else softmax_max<D, 1, false>(wx, sx, mx1, pos0, S, R, c, g);
+                    if (raise_always || wx.m_run[0] == kNegBig) wx.m_run[0] = fmaxf(wx.m_run[0], mx1[0]);
+                }
+                softmax_exp<D, 1, false>(wx, sx, c_eff, pfx);
+            }
             // ---- O^T += V^T . P^T ; the second half of V is fetched while the first is multiplied
             bf16x8 vfb[kHalf];
 #pragma unroll
@@ -774,11 +801,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
                 for (int rt = 0; rt < MT; ++rt)
                     w.oacc[kHalf + i][rt] =
                         __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfb[i], pf[rt], w.oacc[kHalf + i][rt], 0, 0, 0);
+            if (mine) {
+#pragma unroll
+                for (int i = 0; i < kHalf; ++i) {
+                    wx.oacc[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfa[i], pfx[0], wx.oacc[i][0], 0, 0, 0);
+                    wx.oacc[kHalf + i][0] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfb[i], pfx[0], wx.oacc[kHalf + i][0], 0, 0, 0);
+                }
+            }
         }
 
         bool bad = false;
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt) bad = bad || !(w.l_part[rt] < 1.0e30f);    // also catches NaN
+        if (XT) bad = bad || !(wx.l_part[0] < 1.0e30f);
         // Workgroup-wide OR through the first word of the (now idle) ring: the ring takes the whole
         // LDS share of a workgroup, so there is no room for a separate flag.  The first barrier also
         // keeps a fast wavefront from refilling ring slots others still read.
@@ -796,6 +832,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             w.l_part[rt] = 0.f;
 #pragma unroll
             for (int dt = 0; dt < D / 16; ++dt) w.oacc[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        if (XT) {
+            if (attempt == 0) wx.m_run[0] = kNegBig;
+            wx.l_part[0] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < D / 16; ++dt) wx.oacc[dt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
 
@@ -832,6 +874,59 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
                 if (g == 0) { wm[pr] = w.m_run[rt]; wl[pr] = l; }
             }
         }
+    }
+
+    // ---- extra rows: each wavefront holds the contribution of the tiles it took; merge through LDS
+    // (the ring is idle: the last barriers of the tile loop are behind every wavefront)
+    if (XT) {
+        float *xm = (float *)smem;                           // [4][16]
+        float *xl = xm + kWaves * 16;                        // [4][16]
+        float *xo = xl + kWaves * 16;                        // [16][D + 4]
+        constexpr int kXStr = D + 4;
+        float lx = wx.l_part[0];
+        lx += __shfl_xor(lx, 16, 64);
+        lx += __shfl_xor(lx, 32, 64);
+        if (g == 0) { xm[wave * 16 + n] = wx.m_run[0]; xl[wave * 16 + n] = lx; }
+        __syncthreads();
+        float M = xm[n];
+#pragma unroll
+        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, xm[ww * 16 + n]);
+        float L = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) L += xl[ww * 16 + n] * __builtin_amdgcn_exp2f(xm[ww * 16 + n] - M);
+        const float my_scale = __builtin_amdgcn_exp2f(wx.m_run[0] - M);
+        for (int ww = 0; ww < kWaves; ++ww) {
+            if (wave == ww) {
+#pragma unroll
+                for (int dt = 0; dt < D / 16; ++dt) {
+                    float4 *dst = (float4 *)(xo + n * kXStr + dt * 16 + 4 * g);
+                    const f32x4 a = wx.oacc[dt][0] * my_scale;
+                    float4 v{a[0], a[1], a[2], a[3]};
+                    if (ww > 0) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+                    *dst = v;
+                }
+            }
+            __syncthreads();
+        }
+        // every wavefront computed the same M and L; wavefront 0 publishes them over its own entries
+        if (wave == 0 && g == 0) { xm[n] = M; xl[n] = L; }
+        __syncthreads();
+        const int rows_x = p.rows - kXRow0;
+        for (int idx = tid; idx < rows_x * (D / 4); idx += 256) {
+            const int row = idx / (D / 4), c4 = idx % (D / 4);
+            const int pr = kXRow0 + row;
+            float4 v = *(const float4 *)(xo + row * kXStr + c4 * 4);
+            if (nchunks_b == 1) {
+                const int hh = pr / R, i = pr % R;
+                const float inv = 1.0f / xl[row];
+                v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
+                const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
+                store_out(p.out, o, v, p.out_bf16);
+            } else {
+                *(float4 *)(wo + (int64_t)pr * D + c4 * 4) = v;
+            }
+        }
+        if (nchunks_b > 1 && tid < rows_x) { wm[kXRow0 + tid] = xm[tid]; wl[kXRow0 + tid] = xl[tid]; }
     }
 }
 
@@ -1031,9 +1126,14 @@ void launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st) {
         const int mt = (rpw + 15) / 16;
         // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS
         constexpr int NS = 65536 / WideCfg<D>::kSlot;
-        if (mt == 1) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS>), grid, dim3(256), 0, st, p);
-        else if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS>), grid, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 3, NS>), grid, dim3(256), 0, st, p);
+        // 4 x 16 x (mt-1) rows owned outright plus at most one shared extra row tile, when that fits
+        const int extra = p.rows - kWaves * 16 * (mt - 1);
+        if (mt >= 2 && extra >= 1 && extra <= 16) {
+            if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS, true>), grid, dim3(256), 0, st, p);
+            else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS, true>), grid, dim3(256), 0, st, p);
+        } else if (mt == 1) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS, false>), grid, dim3(256), 0, st, p);
+        else if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS, false>), grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 3, NS, false>), grid, dim3(256), 0, st, p);
         return;
     }
     const int mt = (p.rows + 15) / 16;
