@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only spec_verify_attn (for profiling)")
     ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--schedule", type=int, default=0, help="attn_schedule option: 0 auto, 1 chunk grid, 2 balanced")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (5 times): a kernel of known HBM traffic "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with")
@@ -128,6 +129,8 @@ def main():
                        **{kv.split("=")[0]: ast.literal_eval(kv.split("=", 1)[1]) for kv in args.set})
     if args.kv_chunk:
         A.agentsam_set_option("attn_kv_chunk", args.kv_chunk)
+    if args.schedule:
+        A.agentsam_set_option("attn_schedule", args.schedule)
 
     # ---- inputs (all resident in HBM before timing)
     nmem = cfg.B if cfg.sam_mode == "per_session" else 1

@@ -49,6 +49,11 @@ const char *agentsam_strerror(int code);
 /* Tuning knobs for experiments and for tests of split invariance.
  *   "attn_kv_chunk"  KV positions handled by one workgroup of spec_verify_attn
  *                    (0 = choose automatically; otherwise a multiple of 128, >= 128).
+ *   "attn_schedule"  how spec_verify_attn (bf16) spreads the batch over the GPU: 1 = every
+ *                    (session, kv head) stream cut into chunks, one workgroup per chunk;
+ *                    2 = all streams laid end to end and cut into one equal share per resident
+ *                    workgroup; 0 = choose (2 for large batches unless a chunk size is set).
+ *   "attn_v_mode"    0/1: how the bf16 kernels transpose V out of LDS (same results).
  * Returns AGENTSAM_ERR_ARG for an unknown key or a bad value. */
 int agentsam_set_option(const char *key, int64_t value);
 

@@ -27,6 +27,7 @@
 
 namespace agentsam {
 int64_t option_attn_v_mode();
+int64_t option_attn_schedule();
 }
 
 namespace {
@@ -60,6 +61,9 @@ struct AttnParams {
     int rows;                // G*R packed rows per kv head
     int rows_pad;            // rows per workspace record
     int out_bf16;
+    int balanced;            // 1: balanced partition of the whole batch over the grid, 0: chunk grid
+    int32_t *plan;           // balanced only: exclusive prefix sums of the sessions' tile counts, [B+1]
+    float *wsr;              // workspace records (after the plan, if any)
 };
 
 // A session of S positions is cut into ceil(S / max_chunk) chunks of EQUAL size (rounded up to 128
@@ -110,6 +114,13 @@ __device__ __forceinline__ uint4 ld_stream(const void *ptr) {
     return uint4{v[0], v[1], v[2], v[3]};
 }
 
+// Returns x, but opaque to the optimiser: index arithmetic derived from the result is not hoisted out
+// of an enclosing loop (where it would sit in registers across the whole tile loop).
+__device__ __forceinline__ int opaque(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 // Per-wavefront state: the packed query rows [row0, row_end) of one kv head, their running softmax
 // statistics and the transposed output accumulators.
 template <int D, int MT>
@@ -123,7 +134,8 @@ struct WaveState {
 
 template <int D, int MT>
 __device__ __forceinline__ void init_state(WaveState<D, MT> &w, const AttnParams &p, int b, int kvh,
-                                           int row0, int row_end, int n, int g) {
+                                           int row0, int row_end, int n_in, int g_in) {
+    const int n = opaque(n_in), g = opaque(g_in);            // per-segment work: keep its index arithmetic here
     const __hip_bfloat16 *qg = (const __hip_bfloat16 *)p.q;
     const int R = p.R;
 #pragma unroll
@@ -301,6 +313,145 @@ __device__ __forceinline__ void compute_tile(WaveState<D, MT> &w, const char *Ks
     pv_mfma<D, MT, VMODE>(w, Vs, pf, n, g);
 }
 
+// ------------------------------------------------------------------------------------------
+// Work distribution.  A (session, kv head) pair is a stream of ceil(S/32) tiles.  Two schedules:
+//
+//   chunk grid   every stream is cut into equal chunks of at most p.chunk positions; workgroup
+//                (chunk, session, kv head), kv head fastest and chunk slowest.  Streams of different
+//                sessions are cut at (nearly) the same positions and those pieces are dispatched
+//                together, so sessions that share the pages of a prefix meet in the L2 / the memory-side
+//                cache.  Used when there are fewer streams than about two per workgroup slot, where
+//                every stream has to be split anyway.
+//   balanced     the streams are laid end to end (session-major, kv head minor) and that sequence of
+//                T tiles is cut into gridDim.x equal shares, one per workgroup, all resident at once.
+//                A workgroup walks its share segment by segment; only its first and last segment can
+//                be part of a stream (everything in between is a whole stream, written out directly),
+//                so there are at most two partial records per workgroup and no tail of unevenly sized
+//                workgroups, however ragged the batch.  seq_lens lives on the device, so every
+//                workgroup derives its share itself: a block-wide scan of the tile counts.
+// ------------------------------------------------------------------------------------------
+constexpr int kMinShare = 4;                 // tiles; smaller problems leave workgroups idle
+
+struct Segment {
+    int b, kvh, S;           // session, kv head, clamped sequence length
+    int t0, nt;              // tile range [t0, t0+nt) of the stream
+    int64_t rec;             // workspace record for the partial result, -1: whole stream, write the output
+};
+
+__device__ __forceinline__ int session_len(const AttnParams &p, int b) {
+    return min(p.seq[b], p.max_pages * p.P);                 // never index past the block table
+}
+__device__ __forceinline__ int tiles_of(int S) { return S > 0 ? (S + kTile - 1) / kTile : 0; }
+
+// exclusive prefix of v over the 256 threads of the workgroup, and the total; `tmp` is 4 ints of LDS
+__device__ __forceinline__ int block_scan_excl(int v, int *tmp, int &total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int u = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += u;
+    }
+    if (lane == 63) tmp[wave] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) {
+        const int x = tmp[ww];
+        if (ww < wave) base += x;
+        tot += x;
+    }
+    __syncthreads();                                         // tmp may be reused
+    total = tot;
+    return base + incl - v;
+}
+
+__device__ __forceinline__ int balanced_share(int T, int nslots) {
+    const int s = (T + nslots - 1) / nslots;
+    return s < kMinShare ? kMinShare : s;
+}
+
+// Calls body(Segment) for every segment of this workgroup, in order.  `tmp`: 8 ints of LDS that the
+// body does not touch.  Everything handed to the body is uniform over the workgroup (scalar registers).
+template <class Body>
+__device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, Body body) {
+    Segment sg;
+    int nt_b;                    // tiles of the current stream (chunk grid: end of my chunk)
+    int remaining;               // tiles of my share still to do
+    int64_t chunk_rec = -1;      // chunk grid: the one record
+    if (!p.balanced) {
+        sg.kvh = blockIdx.x % p.Hkv;
+        sg.b = (blockIdx.x / p.Hkv) % p.B;
+        sg.S = session_len(p, sg.b);
+        int nchunks_b, chunk_len;
+        chunk_geometry(sg.S, p.chunk, nchunks_b, chunk_len);
+        const int chunk = blockIdx.x / (p.B * p.Hkv);
+        if (chunk >= nchunks_b) return;
+        const int c0 = chunk * chunk_len, c1 = min(sg.S, c0 + chunk_len);
+        sg.t0 = c0 / kTile;                                  // chunk_len is a multiple of 128
+        remaining = (c1 - c0 + kTile - 1) / kTile;
+        nt_b = sg.t0 + remaining;
+        if (nchunks_b > 1) chunk_rec = ((int64_t)sg.b * p.Hkv + sg.kvh) * p.nchunks_max + chunk;
+    } else {
+        const int tid = threadIdx.x;
+        // pass 1: T
+        int sessions_tiles = 0;
+        for (int base = 0; base < p.B; base += 256) {
+            const int bb = base + tid;
+            int tot;
+            block_scan_excl(bb < p.B ? tiles_of(session_len(p, bb)) : 0, tmp, tot);
+            sessions_tiles += tot;
+        }
+        const int T = __builtin_amdgcn_readfirstlane(sessions_tiles) * p.Hkv;   // uniform: scalar registers
+        const int share = balanced_share(T, (int)gridDim.x);
+        const int lo = (int)blockIdx.x * share;
+        if (blockIdx.x != 0 && lo >= T) return;              // workgroup 0 stays to write the plan
+        // pass 2: the stream my share starts in; workgroup 0 also leaves the prefix sums for the merge
+        int carry = 0;
+        if (tid == 0) tmp[4] = -1;                           // ordered before the writes below by the scan's barriers
+        for (int base = 0; base < p.B; base += 256) {
+            const int bb = base + tid;
+            const int nt = bb < p.B ? tiles_of(session_len(p, bb)) : 0;
+            int tot;
+            const int excl = carry + block_scan_excl(nt, tmp, tot);
+            if (blockIdx.x == 0 && bb < p.B) p.plan[bb] = excl;
+            if (nt > 0 && excl * p.Hkv <= lo && lo < (excl + nt) * p.Hkv) { tmp[4] = bb; tmp[5] = excl; }
+            carry += tot;
+        }
+        if (blockIdx.x == 0 && tid == 0) p.plan[p.B] = carry;
+        __syncthreads();
+        if (lo >= T) return;
+        sg.b = __builtin_amdgcn_readfirstlane(tmp[4]);
+        if (sg.b < 0 || sg.b >= p.B) return;                 // cannot happen: some stream contains tile `lo`
+        const int excl0 = __builtin_amdgcn_readfirstlane(tmp[5]);
+        sg.S = __builtin_amdgcn_readfirstlane(session_len(p, sg.b));
+        nt_b = tiles_of(sg.S);
+        const int r = lo - excl0 * p.Hkv;
+        sg.kvh = r / nt_b;
+        sg.t0 = r % nt_b;
+        remaining = min(T, lo + share) - lo;
+    }
+    bool first = true;
+    while (remaining > 0) {                                  // (one round on the chunk grid)
+        sg.nt = min(remaining, nt_b - sg.t0);
+        const bool whole = sg.t0 == 0 && sg.nt == nt_b;
+        sg.rec = !p.balanced ? chunk_rec : whole ? -1 : 2 * (int64_t)blockIdx.x + (first ? 0 : 1);
+        body(sg);
+        remaining -= sg.nt;
+        first = false;
+        sg.t0 = 0;
+        if (remaining > 0 && ++sg.kvh == p.Hkv) {
+            sg.kvh = 0;
+            do {                                             // sessions without tiles own no part of the sequence
+                ++sg.b;
+                if (sg.b >= p.B) return;                     // cannot happen while seq_lens is unchanged
+                sg.S = __builtin_amdgcn_readfirstlane(session_len(p, sg.b));
+                nt_b = tiles_of(sg.S);
+            } while (nt_b == 0);
+        }
+    }
+}
+
 // The page id of every 32-position tile of a chunk, fetched once at kernel start (lane i of register
 // r holds the id for tile 64*r + i) and handed out with v_readlane: the tile loop never waits on a
 // block-table load, and no vector load of its own sits between the streaming loads whose completion
@@ -353,7 +504,7 @@ __device__ __forceinline__ TileSrc<D> tile_src(const AttnParams &p, const ChunkP
     return ts;
 }
 
-// -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the chunk
+// -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the segment
 template <int D, int MT, int VMODE>
 __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams p) {
     using C = Bf16Cfg<D>;
@@ -362,157 +513,152 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
     __shared__ __align__(16) char smem[kStage > kMerge ? kStage : kMerge];
     __shared__ float red_m[kWaves * kRowsPerGroup];
     __shared__ float red_l[kWaves * kRowsPerGroup];
-
-    // 1-D grid, kv head fastest and chunk slowest.  Workgroups are handed to the 8 XCDs round-robin,
-    // so with 8 kv heads every XCD streams one kv head of every session: the load is balanced
-    // whatever the length distribution, and sessions that share the pages of a (kv head, chunk)
-    // (a common prefix) run back to back on the same XCD and meet in its L2.
-    const int kvh = blockIdx.x % p.Hkv;
-    const int b = (blockIdx.x / p.Hkv) % p.B;
-    const int S = min(p.seq[b], p.max_pages * p.P);          // never index past the block table
-    int nchunks_b, chunk_len;
-    chunk_geometry(S, p.chunk, nchunks_b, chunk_len);
-    const int chunk = blockIdx.x / (p.B * p.Hkv);
-    if (chunk >= nchunks_b) return;                          // uniform over the workgroup
-    const int c0 = chunk * chunk_len;
-    const int c1 = min(S, c0 + chunk_len);
-    const int ntiles = (c1 - c0 + kTile - 1) / kTile;
+    __shared__ int sched_tmp[8];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
     const int n = lane & 15, g = lane >> 4;
     const int R = p.R;
-
     char *Ks = smem + wave * C::kTileBytes;
     char *Vs = Ks + kTile * C::kKStr;
-
-    WaveState<D, MT> w;
-    init_state<D, MT>(w, p, b, kvh, 0, p.rows, n, g);
-    const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
-
-    // tile loads: lane -> (row, 16-byte column); one instruction reads 1 KB contiguous.  Two tiles
-    // are kept in flight in registers while a third is being computed from LDS.
+    // tile loads: lane -> (row, 16-byte column); one instruction reads 1 KB contiguous
     const int ld_row = lane / C::kLanesPerRow, ld_col = lane % C::kLanesPerRow;
-    uint4 kreg[2][C::kLoads], vreg[2][C::kLoads];
 
-    auto issue_loads = [&](int t, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
-        const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0, t);
+    for_each_segment(p, sched_tmp, [&](const Segment &sg) __attribute__((always_inline)) {
+        const int b = sg.b, kvh = sg.kvh, S = sg.S;
+        WaveState<D, MT> w;
+        init_state<D, MT>(w, p, b, kvh, 0, p.rows, n, g);
+
+        // page ids are held for 256 tiles at a time
+        for (int sub = 0; sub < sg.nt; sub += kMaxChunk / kTile) {
+            const int c0 = (sg.t0 + sub) * kTile;
+            const int ntiles = min(sg.nt - sub, kMaxChunk / kTile);
+            const int c1 = min(S, c0 + ntiles * kTile);
+            const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
+
+            // Two tiles are kept in flight in registers while a third is being computed from LDS.
+            uint4 kreg[2][C::kLoads], vreg[2][C::kLoads];
+            auto issue_loads = [&](int t, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
+                const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0, t);
 #pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) {
-            const int row = i * C::kRowsPerLoad + ld_row;
-            const bool ok = src.page_ok && (src.pos0 + row < S);
-            const int off = row * D + ld_col * 8;
-            kr[i] = ok ? ld_stream(src.kbase + off) : uint4{0u, 0u, 0u, 0u};
-            vr[i] = ok ? ld_stream(src.vbase + off) : uint4{0u, 0u, 0u, 0u};
+                for (int i = 0; i < C::kLoads; ++i) {
+                    const int row = i * C::kRowsPerLoad + ld_row;
+                    const bool ok = src.page_ok && (src.pos0 + row < S);
+                    const int off = row * D + ld_col * 8;
+                    kr[i] = ok ? ld_stream(src.kbase + off) : uint4{0u, 0u, 0u, 0u};
+                    vr[i] = ok ? ld_stream(src.vbase + off) : uint4{0u, 0u, 0u, 0u};
+                }
+            };
+            auto stage = [&](const uint4 (&kr)[C::kLoads], const uint4 (&vr)[C::kLoads]) {
+#pragma unroll
+                for (int i = 0; i < C::kLoads; ++i) {
+                    const int row = i * C::kRowsPerLoad + ld_row;
+                    *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[i];
+                    *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[i];
+                }
+            };
+
+            int t = wave;
+            if (t < ntiles) issue_loads(t, kreg[0], vreg[0]);
+            if (t + kWaves < ntiles) issue_loads(t + kWaves, kreg[1], vreg[1]);
+            while (t < ntiles) {
+                stage(kreg[0], vreg[0]);
+                wave_lds_fence();
+                if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[0], vreg[0]);
+                compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
+                wave_lds_fence();
+                t += kWaves;
+                if (t >= ntiles) break;
+                stage(kreg[1], vreg[1]);
+                wave_lds_fence();
+                if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[1], vreg[1]);
+                compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
+                wave_lds_fence();
+                t += kWaves;
+            }
         }
-    };
-    auto stage = [&](const uint4 (&kr)[C::kLoads], const uint4 (&vr)[C::kLoads]) {
-#pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) {
-            const int row = i * C::kRowsPerLoad + ld_row;
-            *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[i];
-            *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[i];
-        }
-    };
 
-    int t = wave;
-    if (t < ntiles) issue_loads(t, kreg[0], vreg[0]);
-    if (t + kWaves < ntiles) issue_loads(t + kWaves, kreg[1], vreg[1]);
-    while (t < ntiles) {
-        stage(kreg[0], vreg[0]);
-        wave_lds_fence();
-        if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[0], vreg[0]);
-        compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
-        wave_lds_fence();
-        t += kWaves;
-        if (t >= ntiles) break;
-        stage(kreg[1], vreg[1]);
-        wave_lds_fence();
-        if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[1], vreg[1]);
-        compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
-        wave_lds_fence();
-        t += kWaves;
-    }
-
-    // ---- merge the 4 wavefronts through LDS
-    float l_tot[MT];
-#pragma unroll
-    for (int rt = 0; rt < MT; ++rt) {
-        float l = w.l_part[rt];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
-        l_tot[rt] = l;
-    }
-    __syncthreads();                                         // staging LDS is free from here on
-    if (g == 0) {
+        // ---- merge the 4 wavefronts through LDS
+        const int n_e = opaque(n), g_e = opaque(g), tid_e = opaque(tid);   // not hoisted out of the segment loop
+        float l_tot[MT];
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt) {
-            red_m[wave * kRowsPerGroup + rt * 16 + n] = w.m_run[rt];
-            red_l[wave * kRowsPerGroup + rt * 16 + n] = l_tot[rt];
+            float l = w.l_part[rt];
+            l += __shfl_xor(l, 16, 64);
+            l += __shfl_xor(l, 32, 64);
+            l_tot[rt] = l;
         }
-    }
-    __syncthreads();
-    float my_scale[MT], M_all[MT], L_all[MT];
+        __syncthreads();                                     // staging LDS is free from here on
+        if (g_e == 0) {
 #pragma unroll
-    for (int rt = 0; rt < MT; ++rt) {
-        const int row = rt * 16 + n;
-        float M = red_m[row];
-#pragma unroll
-        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, red_m[ww * kRowsPerGroup + row]);
-        float L = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww)
-            L += red_l[ww * kRowsPerGroup + row] * __builtin_amdgcn_exp2f(red_m[ww * kRowsPerGroup + row] - M);
-        M_all[rt] = M;
-        L_all[rt] = L;
-        my_scale[rt] = __builtin_amdgcn_exp2f(w.m_run[rt] - M);
-    }
-    float *Osum = (float *)smem;
-    for (int ww = 0; ww < kWaves; ++ww) {
-        if (wave == ww) {
-#pragma unroll
-            for (int rt = 0; rt < MT; ++rt)
-#pragma unroll
-                for (int dt = 0; dt < D / 16; ++dt) {
-                    float4 *dst = (float4 *)(Osum + (rt * 16 + n) * C::kOStr + dt * 16 + 4 * g);
-                    const f32x4 a = w.oacc[dt][rt] * my_scale[rt];
-                    float4 v{a[0], a[1], a[2], a[3]};
-                    if (ww > 0) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
-                    *dst = v;
-                }
+            for (int rt = 0; rt < MT; ++rt) {
+                red_m[wave * kRowsPerGroup + rt * 16 + n_e] = w.m_run[rt];
+                red_l[wave * kRowsPerGroup + rt * 16 + n_e] = l_tot[rt];
+            }
         }
         __syncthreads();
-    }
-    // every wavefront computed the same merged maximum and sum; the per-wavefront entries were last
-    // read before the barriers above, so wavefront 0 may now overwrite its own with the merged values
-    if (wave == 0 && g == 0) {
+        float my_scale[MT], M_all[MT], L_all[MT];
 #pragma unroll
-        for (int rt = 0; rt < MT; ++rt) { red_m[rt * 16 + n] = M_all[rt]; red_l[rt * 16 + n] = L_all[rt]; }
-    }
-    __syncthreads();
+        for (int rt = 0; rt < MT; ++rt) {
+            const int row = rt * 16 + n_e;
+            float M = red_m[row];
+#pragma unroll
+            for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, red_m[ww * kRowsPerGroup + row]);
+            float L = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww)
+                L += red_l[ww * kRowsPerGroup + row] * __builtin_amdgcn_exp2f(red_m[ww * kRowsPerGroup + row] - M);
+            M_all[rt] = M;
+            L_all[rt] = L;
+            my_scale[rt] = __builtin_amdgcn_exp2f(w.m_run[rt] - M);
+        }
+        float *Osum = (float *)smem;
+        for (int ww = 0; ww < kWaves; ++ww) {
+            if (wave == ww) {
+#pragma unroll
+                for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+                    for (int dt = 0; dt < D / 16; ++dt) {
+                        float4 *dst = (float4 *)(Osum + (rt * 16 + n_e) * C::kOStr + dt * 16 + 4 * g_e);
+                        const f32x4 a = w.oacc[dt][rt] * my_scale[rt];
+                        float4 v{a[0], a[1], a[2], a[3]};
+                        if (ww > 0) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+                        *dst = v;
+                    }
+            }
+            __syncthreads();
+        }
+        // every wavefront computed the same merged maximum and sum; the per-wavefront entries were last
+        // read before the barriers above, so wavefront 0 may now overwrite its own with the merged values
+        if (wave == 0 && g_e == 0) {
+#pragma unroll
+            for (int rt = 0; rt < MT; ++rt) { red_m[rt * 16 + n_e] = M_all[rt]; red_l[rt * 16 + n_e] = L_all[rt]; }
+        }
+        __syncthreads();
 
-    const int rows_here = p.rows;
-    if (nchunks_b == 1) {
-        for (int idx = tid; idx < rows_here * (D / 4); idx += 256) {
-            const int row = idx / (D / 4), c4 = idx % (D / 4);
-            const int hh = row / R, i = row % R;
-            const float inv = 1.0f / red_l[row];
-            float4 v = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
-            v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
-            const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
-            store_out(p.out, o, v, p.out_bf16);
+        const int rows_here = p.rows;
+        if (sg.rec < 0) {
+            for (int idx = tid_e; idx < rows_here * (D / 4); idx += 256) {
+                const int row = idx / (D / 4), c4 = idx % (D / 4);
+                const int hh = row / R, i = row % R;
+                const float inv = 1.0f / red_l[row];
+                float4 v = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
+                v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
+                const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
+                store_out(p.out, o, v, p.out_bf16);
+            }
+        } else {
+            float *wo = p.wsr + sg.rec * ws_record_floats(p.rows_pad, D);
+            float *wm = wo + (int64_t)p.rows_pad * D;
+            float *wl = wm + p.rows_pad;
+            for (int idx = tid_e; idx < rows_here * (D / 4); idx += 256) {
+                const int row = idx / (D / 4), c4 = idx % (D / 4);
+                *(float4 *)(wo + (int64_t)row * D + c4 * 4) = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
+            }
+            if (tid_e < rows_here) { wm[tid_e] = red_m[tid_e]; wl[tid_e] = red_l[tid_e]; }
         }
-    } else {
-        const int64_t rec = ((int64_t)b * p.Hkv + kvh) * p.nchunks_max + chunk;
-        float *wo = p.ws + rec * ws_record_floats(p.rows_pad, D);
-        float *wm = wo + (int64_t)p.rows_pad * D;
-        float *wl = wm + p.rows_pad;
-        for (int idx = tid; idx < rows_here * (D / 4); idx += 256) {
-            const int row = idx / (D / 4), c4 = idx % (D / 4);
-            *(float4 *)(wo + (int64_t)row * D + c4 * 4) = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
-        }
-        if (tid < rows_here) { wm[tid] = red_m[tid]; wl[tid] = red_l[tid]; }
-    }
+        __syncthreads();                                     // the next segment stages into the same LDS
+    });
 }
 
 // -------- wide kernel: 49..192 packed rows; the 4 wavefronts take different rows of the SAME tile.
@@ -614,17 +760,7 @@ template <int D, int MT, int NS, bool XT>
 __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
     using W = WideCfg<D>;
     __shared__ __align__(16) char smem[NS * W::kSlot];
-
-    const int kvh = blockIdx.x % p.Hkv;
-    const int b = (blockIdx.x / p.Hkv) % p.B;
-    const int S = min(p.seq[b], p.max_pages * p.P);
-    int nchunks_b, chunk_len;
-    chunk_geometry(S, p.chunk, nchunks_b, chunk_len);
-    const int chunk = blockIdx.x / (p.B * p.Hkv);
-    if (chunk >= nchunks_b) return;
-    const int c0 = chunk * chunk_len;
-    const int c1 = min(S, c0 + chunk_len);
-    const int ntiles = (c1 - c0 + kTile - 1) / kTile;
+    __shared__ int sched_tmp[8];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
@@ -641,11 +777,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     const int row0 = wave * rpw;
     const int row_end = min(p.rows, row0 + rpw);
     constexpr int kXRow0 = kWaves * 16 * MT;                 // first extra row (XT only)
-    WaveState<D, MT> w;
-    init_state<D, MT>(w, p, b, kvh, row0, row_end, n, g);
-    WaveState<D, 1> wx;
-    if (XT) init_state<D, 1>(wx, p, b, kvh, kXRow0, p.rows, n, g);
-    const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
 
     // ---- per-lane constants of the tile loop (computed once; the loop only adds uniform bases)
     // piece j of a tile (1 KB = kRPI rows): my 16 bytes are row j*kRPI + lrow, and I fetch the global
@@ -662,8 +793,29 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         voff0 = W::kKT + vrow * W::kRowBytes + (((bq >> 1) ^ (vrow & (W::kCPR - 1))) * 16) + (bq & 1) * 8;
     }
     const int64_t page_bytes = (int64_t)p.Hkv * p.P * D * 2;
-    const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
     const unsigned smem_addr = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem;   // LDS byte address
+
+    for_each_segment(p, sched_tmp, [&](const Segment &sg) __attribute__((always_inline)) {
+    const int b = sg.b, kvh = sg.kvh, S = sg.S;
+    const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
+    WaveState<D, MT> w;
+    init_state<D, MT>(w, p, b, kvh, row0, row_end, n, g);
+    WaveState<D, 1> wx;
+    if (XT) init_state<D, 1>(wx, p, b, kvh, kXRow0, p.rows, n, g);
+
+    // attempt: 0 optimistic (fixed references), 1 exact row maxima only, 2 final pass with those
+    for (int attempt = 0;; ++attempt) {
+      const bool raise_always = attempt == 1;
+      // page ids are held for 256 tiles at a time; the ring drains and refills at such a boundary
+      for (int sub = 0; sub < sg.nt; sub += kMaxChunk / kTile) {
+        const int c0 = (sg.t0 + sub) * kTile;
+        const int ntiles = min(sg.nt - sub, kMaxChunk / kTile);
+        const int c1 = min(S, c0 + ntiles * kTile);
+        const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
+        // The query fragments and the page ids are needed at once; waiting for them here, explicitly,
+        // keeps the compiler from guarding their first use inside the tile loop with a wait that would
+        // also drain the tile this wavefront has just started to fetch.
+        wait_vmcnt0();
 
     // fetch tile t into its ring slot (called by one wavefront)
     auto issue = [&](int t, int slot_idx) {
@@ -701,9 +853,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         }
     };
 
-    // attempt: 0 optimistic (fixed references), 1 exact row maxima only, 2 final pass with those
-    for (int attempt = 0;; ++attempt) {
-        const bool raise_always = attempt == 1;
         for (int t = 0; t < NS - 1; ++t)
             if (t < ntiles && wave == (t & (kWaves - 1))) issue(t, t);
         int slot_cur = 0;                                    // ring slot of tile t (t mod NS, kept incrementally)
@@ -765,7 +914,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             __builtin_amdgcn_sched_barrier(0);               // keep the reads above the arithmetic below
             // ---- softmax weights
             float c_eff = c;
-            if (t == 0 || mask || raise_always) {            // rare: maxima, reference, masking
+            if ((sub == 0 && t == 0) || mask || raise_always) {   // rare: maxima, reference, masking
                 float mx[MT];
                 if (mask) softmax_max<D, MT, true>(w, sacc, mx, pos0, S, R, c, g);
                 else softmax_max<D, MT, false>(w, sacc, mx, pos0, S, R, c, g);
@@ -778,7 +927,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             softmax_exp<D, MT, false>(w, sacc, c_eff, pf);   // fma(-inf, 1, -ref) = -inf -> weight 0
             bf16x8 pfx[1];
             if (mine) {
-                if (t < kWaves || mask || raise_always) {    // t < 4: my first extra tile of this pass
+                if ((sub == 0 && t < kWaves) || mask || raise_always) {   // t < 4: my first extra tile of this pass
                     float mx1[1];
                     if (mask) softmax_max<D, 1, true>(wx, sx, mx1, pos0, S, R, c, g);
                     else softmax_max<D, 1, false>(wx, sx, mx1, pos0, S, R, c, g);
@@ -811,14 +960,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             }
         }
 
+        __syncthreads();                                     // everyone is done with the ring before it refills
+      }   // sub
+
         bool bad = false;
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt) bad = bad || !(w.l_part[rt] < 1.0e30f);    // also catches NaN
         if (XT) bad = bad || !(wx.l_part[0] < 1.0e30f);
         // Workgroup-wide OR through the first word of the (now idle) ring: the ring takes the whole
-        // LDS share of a workgroup, so there is no room for a separate flag.  The first barrier also
-        // keeps a fast wavefront from refilling ring slots others still read.
-        __syncthreads();
+        // LDS share of a workgroup, so there is no room for a separate flag.
         if (tid == 0) *(volatile int *)smem = 0;
         __syncthreads();
         if (bad) *(volatile int *)smem = 1;
@@ -842,10 +992,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     }
 
     // ---- every wavefront owns its rows outright: normalise (or leave a partial) straight from registers
+    const int n_e = opaque(n), g_e = opaque(g), tid_e = opaque(tid);   // epilogue indices: computed here, not hoisted
+    const bool final_out = sg.rec < 0;
     float *wo = nullptr, *wm = nullptr, *wl = nullptr;
-    if (nchunks_b > 1) {
-        const int64_t rec = ((int64_t)b * p.Hkv + kvh) * p.nchunks_max + chunk;
-        wo = p.ws + rec * ws_record_floats(p.rows_pad, D);
+    if (!final_out) {
+        wo = p.wsr + sg.rec * ws_record_floats(p.rows_pad, D);
         wm = wo + (int64_t)p.rows_pad * D;
         wl = wm + p.rows_pad;
     }
@@ -854,24 +1005,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         float l = w.l_part[rt];
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
-        const int pr = row0 + rt * 16 + n;
+        const int pr = row0 + rt * 16 + n_e;
         if (pr < row_end) {
-            if (nchunks_b == 1) {
+            if (final_out) {
                 const int hh = pr / R, i = pr % R;
                 const float inv = 1.0f / l;
                 const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D;
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) {
                     const f32x4 a = w.oacc[dt][rt] * inv;
-                    store_out(p.out, o + dt * 16 + 4 * g, float4{a[0], a[1], a[2], a[3]}, p.out_bf16);
+                    store_out(p.out, o + dt * 16 + 4 * g_e, float4{a[0], a[1], a[2], a[3]}, p.out_bf16);
                 }
             } else {
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) {
                     const f32x4 a = w.oacc[dt][rt];
-                    *(float4 *)(wo + (int64_t)pr * D + dt * 16 + 4 * g) = float4{a[0], a[1], a[2], a[3]};
+                    *(float4 *)(wo + (int64_t)pr * D + dt * 16 + 4 * g_e) = float4{a[0], a[1], a[2], a[3]};
                 }
-                if (g == 0) { wm[pr] = w.m_run[rt]; wl[pr] = l; }
+                if (g_e == 0) { wm[pr] = w.m_run[rt]; wl[pr] = l; }
             }
         }
     }
@@ -886,20 +1037,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         float lx = wx.l_part[0];
         lx += __shfl_xor(lx, 16, 64);
         lx += __shfl_xor(lx, 32, 64);
-        if (g == 0) { xm[wave * 16 + n] = wx.m_run[0]; xl[wave * 16 + n] = lx; }
+        if (g_e == 0) { xm[wave * 16 + n_e] = wx.m_run[0]; xl[wave * 16 + n_e] = lx; }
         __syncthreads();
-        float M = xm[n];
+        float M = xm[n_e];
 #pragma unroll
-        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, xm[ww * 16 + n]);
+        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, xm[ww * 16 + n_e]);
         float L = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) L += xl[ww * 16 + n] * __builtin_amdgcn_exp2f(xm[ww * 16 + n] - M);
+        for (int ww = 0; ww < kWaves; ++ww) L += xl[ww * 16 + n_e] * __builtin_amdgcn_exp2f(xm[ww * 16 + n_e] - M);
         const float my_scale = __builtin_amdgcn_exp2f(wx.m_run[0] - M);
         for (int ww = 0; ww < kWaves; ++ww) {
             if (wave == ww) {
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) {
-                    float4 *dst = (float4 *)(xo + n * kXStr + dt * 16 + 4 * g);
+                    float4 *dst = (float4 *)(xo + n_e * kXStr + dt * 16 + 4 * g_e);
                     const f32x4 a = wx.oacc[dt][0] * my_scale;
                     float4 v{a[0], a[1], a[2], a[3]};
                     if (ww > 0) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
@@ -909,14 +1060,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             __syncthreads();
         }
         // every wavefront computed the same M and L; wavefront 0 publishes them over its own entries
-        if (wave == 0 && g == 0) { xm[n] = M; xl[n] = L; }
+        if (wave == 0 && g_e == 0) { xm[n_e] = M; xl[n_e] = L; }
         __syncthreads();
         const int rows_x = p.rows - kXRow0;
-        for (int idx = tid; idx < rows_x * (D / 4); idx += 256) {
+        for (int idx = tid_e; idx < rows_x * (D / 4); idx += 256) {
             const int row = idx / (D / 4), c4 = idx % (D / 4);
             const int pr = kXRow0 + row;
             float4 v = *(const float4 *)(xo + row * kXStr + c4 * 4);
-            if (nchunks_b == 1) {
+            if (final_out) {
                 const int hh = pr / R, i = pr % R;
                 const float inv = 1.0f / xl[row];
                 v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
@@ -926,8 +1077,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
                 *(float4 *)(wo + (int64_t)pr * D + c4 * 4) = v;
             }
         }
-        if (nchunks_b > 1 && tid < rows_x) { wm[kXRow0 + tid] = xm[tid]; wl[kXRow0 + tid] = xl[tid]; }
+        if (!final_out && tid_e < rows_x) { wm[kXRow0 + tid_e] = xm[tid_e]; wl[kXRow0 + tid_e] = xl[tid_e]; }
     }
+    __syncthreads();                                         // the ring is reused by the next segment
+    });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -961,6 +1114,44 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnParams p, int
         acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
         const int hh = pr / p.R, i = pr % p.R;
         const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)ho * G_eff + hh) * D + c4 * 4;
+        store_out(p.out, o, acc, p.out_bf16);
+    }
+}
+
+// The same merge for the balanced schedule: the partials of stream (b, kv head) are the records of
+// the workgroups whose shares overlap it, found from the prefix sums workgroup 0 left in the plan.
+// Workgroup i keeps the partial of its first segment in record 2i and that of its last in 2i+1.
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_balanced_kernel(const AttnParams p, int nslots) {
+    const int kvh = blockIdx.x, b = blockIdx.y;
+    const int nt_b = tiles_of(session_len(p, b));
+    if (nt_b == 0) return;
+    const int T = p.plan[p.B] * p.Hkv;
+    const int share = balanced_share(T, nslots);
+    const int g0 = p.plan[b] * p.Hkv + kvh * nt_b, g1 = g0 + nt_b;      // the stream's place in the sequence
+    const int i0 = g0 / share, i1 = (g1 - 1) / share;
+    if (i0 == i1) return;                                    // one workgroup had all of it and wrote the output
+    const int64_t recf = ws_record_floats(p.rows_pad, D);
+    // the stream's piece is the first segment of every workgroup but possibly the first one
+    const int first_slot = (i0 * share < g0) ? 1 : 0;
+    auto record = [&](int i) { return p.wsr + (2 * (int64_t)i + (i == i0 ? first_slot : 0)) * recf; };
+    for (int idx = threadIdx.x; idx < p.rows * (D / 4); idx += 256) {
+        const int pr = idx / (D / 4), c4 = idx % (D / 4);
+        float M = kNegBig;
+        for (int i = i0; i <= i1; ++i) M = fmaxf(M, record(i)[(int64_t)p.rows_pad * D + pr]);
+        float L = 0.f;
+        float4 acc{0.f, 0.f, 0.f, 0.f};
+        for (int i = i0; i <= i1; ++i) {
+            const float *rec = record(i);
+            const float w = exp2f(rec[(int64_t)p.rows_pad * D + pr] - M);
+            L += w * rec[(int64_t)p.rows_pad * D + p.rows_pad + pr];
+            const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
+            acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
+        }
+        const float inv = 1.0f / L;
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+        const int hh = pr / p.R, i = pr % p.R;
+        const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
         store_out(p.out, o, acc, p.out_bf16);
     }
 }
@@ -1071,8 +1262,15 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p) {
 struct Plan {
     int chunk, nchunks_max, rows_pad, heads_outer;
     bool wide;
+    bool balanced;           // balanced partition over `nslots` workgroups instead of the chunk grid
+    int nslots;
+    size_t plan_bytes;       // balanced: the prefix sums in front of the records
     size_t ws_bytes;
 };
+
+// Workgroups an MI355X keeps resident at once: 256 compute units x 2 (wide kernel, 64 KB of LDS and
+// <= 256 registers) or x 1 (narrow kernel, which takes the whole register file of a SIMD).
+constexpr int kComputeUnits = 256;
 
 int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages, int dtype, Plan *pl) {
     if (B < 0 || R < 1 || Hq < 1 || Hkv < 1 || page_size < 1 || max_pages < 1) return AGENTSAM_ERR_ARG;
@@ -1084,6 +1282,9 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
     const int G = Hq / Hkv;
     const int64_t opt = agentsam::option_attn_kv_chunk();
     pl->wide = false;
+    pl->balanced = false;
+    pl->nslots = 0;
+    pl->plan_bytes = 0;
     if (dtype == AGENTSAM_F32) {
         if (R > kF32MaxR) return AGENTSAM_ERR_UNSUPPORTED;
         pl->chunk = kF32Chunk;                               // fixed: the score tile lives in LDS
@@ -1112,10 +1313,27 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
         chunk = (chunk + unit - 1) / unit * unit;
         if (chunk > kMaxChunk) chunk = kMaxChunk / unit * unit;
         pl->chunk = (int)chunk;
+        // With at least two (session, kv head) streams per resident workgroup the batch is cut into
+        // equal shares; with fewer, every stream is split anyway and the chunk grid keeps sessions
+        // that share a prefix in step.  An explicit chunk size asks for the chunk grid.
+        pl->nslots = kComputeUnits * (pl->wide ? 2 : 1);
+        const int64_t sched = agentsam::option_attn_schedule();
+        const int64_t tiles_max = (int64_t)B * Hkv * ((smax + kTile - 1) / kTile);
+        pl->balanced = sched == 2 || (sched == 0 && opt == 0 && (int64_t)B * Hkv >= 2 * (int64_t)pl->nslots);
+        if (pl->balanced && tiles_max > 0x7fffffffll) {
+            if (sched == 2) return AGENTSAM_ERR_ARG;
+            pl->balanced = false;
+        }
     }
     pl->nchunks_max = (int)((smax + pl->chunk - 1) / pl->chunk);
-    pl->ws_bytes = (size_t)B * pl->heads_outer * pl->nchunks_max * (size_t)pl->rows_pad * (D + 2) * sizeof(float);
-    if (pl->nchunks_max <= 1) pl->ws_bytes = 0;
+    const size_t rec_bytes = (size_t)pl->rows_pad * (D + 2) * sizeof(float);
+    if (pl->balanced) {
+        pl->plan_bytes = (((size_t)B + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+        pl->ws_bytes = pl->plan_bytes + 2 * (size_t)pl->nslots * rec_bytes;
+    } else {
+        pl->ws_bytes = (size_t)B * pl->heads_outer * pl->nchunks_max * rec_bytes;
+        if (pl->nchunks_max <= 1) pl->ws_bytes = 0;
+    }
     return AGENTSAM_OK;
 }
 
@@ -1125,7 +1343,11 @@ void launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st) {
         const int rpw = (p.rows + kWaves - 1) / kWaves;
         const int mt = (rpw + 15) / 16;
         // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS
+#ifdef AGENTSAM_EXP_NS
+        constexpr int NS = AGENTSAM_EXP_NS;
+#else
         constexpr int NS = 65536 / WideCfg<D>::kSlot;
+#endif
         // 4 x 16 x (mt-1) rows owned outright plus at most one shared extra row tile, when that fits
         const int extra = p.rows - kWaves * 16 * (mt - 1);
         if (mt >= 2 && extra >= 1 && extra <= 16) {
@@ -1182,6 +1404,9 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     p.chunk = pl.chunk; p.nchunks_max = pl.nchunks_max;
     p.rows = p.G * R; p.rows_pad = pl.rows_pad;
     p.out_bf16 = (out_dtype == AGENTSAM_BF16);
+    p.balanced = pl.balanced ? 1 : 0;
+    p.plan = (int32_t *)workspace;
+    p.wsr = (float *)((char *)workspace + pl.plan_bytes);
     hipStream_t st = (hipStream_t)stream;
 
     if (dtype == AGENTSAM_F32) {
@@ -1199,12 +1424,17 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     }
 
     if ((int64_t)pl.nchunks_max * Hkv * B > 0x7fffffffll) return AGENTSAM_ERR_ARG;
-    dim3 grid((unsigned)((int64_t)pl.nchunks_max * Hkv * B));
+    dim3 grid(pl.balanced ? (unsigned)pl.nslots : (unsigned)((int64_t)pl.nchunks_max * Hkv * B));
     const bool tr = agentsam::option_attn_v_mode() == 1;
     if (D == 64) { if (tr) launch_bf16<64, 1>(p, pl.wide, grid, st); else launch_bf16<64, 0>(p, pl.wide, grid, st); }
     else { if (tr) launch_bf16<128, 1>(p, pl.wide, grid, st); else launch_bf16<128, 0>(p, pl.wide, grid, st); }
     AGENTSAM_LAUNCH_CHECK();
-    if (pl.nchunks_max > 1) {
+    if (pl.balanced) {
+        dim3 mg((unsigned)Hkv, (unsigned)B);
+        if (D == 64) hipLaunchKernelGGL(attn_merge_balanced_kernel<64>, mg, dim3(256), 0, st, p, pl.nslots);
+        else hipLaunchKernelGGL(attn_merge_balanced_kernel<128>, mg, dim3(256), 0, st, p, pl.nslots);
+        AGENTSAM_LAUNCH_CHECK();
+    } else if (pl.nchunks_max > 1) {
         dim3 mg((unsigned)Hkv, (unsigned)B);
         if (D == 64) hipLaunchKernelGGL(attn_merge_kernel<64>, mg, dim3(256), 0, st, p, (int)Hkv, p.G);
         else hipLaunchKernelGGL(attn_merge_kernel<128>, mg, dim3(256), 0, st, p, (int)Hkv, p.G);

@@ -34,7 +34,15 @@ def test_argument_errors_without_a_gpu():
     assert L.spec_verify_attn_workspace(1, 33, 8, 1, 128, 64, 4, binding.BF16, ctypes.byref(n)) == -3
     assert L.spec_verify_attn_workspace(1, 5, 4, 1, 64, 64, 4, binding.F32, None) == -1
     assert L.spec_verify_attn_workspace(64, 9, 32, 8, 128, 64, 512, binding.BF16, ctypes.byref(n)) == 0
-    assert n.value == 64 * 8 * 4 * 36 * 130 * 4          # 32768 / 8192 = 4 chunks of 36 packed rows
+    # 512 streams on 256 resident workgroups: balanced schedule, prefix sums + two records per workgroup
+    assert n.value == 512 + 2 * 256 * 36 * 130 * 4
+    assert L.agentsam_set_option(b"attn_schedule", 1) == 0
+    try:
+        assert L.spec_verify_attn_workspace(64, 9, 32, 8, 128, 64, 512, binding.BF16, ctypes.byref(n)) == 0
+        assert n.value == 64 * 8 * 4 * 36 * 130 * 4      # chunk grid: 32768 / 8192 = 4 chunks of 36 packed rows
+    finally:
+        assert L.agentsam_set_option(b"attn_schedule", 0) == 0
+    assert L.agentsam_set_option(b"attn_schedule", 3) == -2
     # entry points reject bad sizes before touching the device
     assert L.sam_draft(*([None] * 12), 4, 65, 4, 1, 0, *([None] * 5)) == -2
     assert L.sam_draft(*([None] * 12), 4, 16, 4, 1, 0, *([None] * 5)) == -1
