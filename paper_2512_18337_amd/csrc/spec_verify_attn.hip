@@ -108,6 +108,11 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_wave_barrier();
 }
 
+__device__ __forceinline__ void wait_vmcnt0() {
+    // s_waitcnt with only the vmcnt field active (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+}
+
 __device__ __forceinline__ uint4 ld_stream(const void *ptr) {
     // K/V are read exactly once per launch: keep them from displacing reusable lines
     const u32x4 v = __builtin_nontemporal_load((const u32x4 *)ptr);
@@ -535,46 +540,76 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
             const int ntiles = min(sg.nt - sub, kMaxChunk / kTile);
             const int c1 = min(S, c0 + ntiles * kTile);
             const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
+            // Nothing else may be outstanding when the tile pipeline starts (the page ids are needed at
+            // once anyway): with only its own loads in flight, in a known order, the compiler's waits
+            // inside the loop count exactly; a pending store of the previous segment would make every
+            // wait at the top of the loop a wait for everything.
+            wait_vmcnt0();
 
-            // Two tiles are kept in flight in registers while a third is being computed from LDS.
+            // Two tiles are kept in flight in registers while a third is being computed from LDS.  The
+            // loads are issued unconditionally (past the wavefront's last tile every lane re-reads the first
+            // bytes of q, one hot cache line; an unusable page id reads page 0) and what must not be seen
+            // is zeroed when the tile is staged:
+            // with a fixed number of loads per step the compiler can wait for exactly the older of the two
+            // tiles in flight instead of for everything outstanding.
             uint4 kreg[2][C::kLoads], vreg[2][C::kLoads];
-            auto issue_loads = [&](int t, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
-                const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0, t);
+            auto issue_loads = [&](int t, int last, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
+                const bool live = t <= last;                     // uniform
+                const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0, live ? t : last);
+                const __hip_bfloat16 *kb = live ? src.kbase : (const __hip_bfloat16 *)p.q;
+                const __hip_bfloat16 *vb = live ? src.vbase : (const __hip_bfloat16 *)p.q;
+                const int lane_off = live ? ld_row * D + ld_col * 8 : 0;
+                const int step = live ? C::kRowsPerLoad * D : 0;
 #pragma unroll
                 for (int i = 0; i < C::kLoads; ++i) {
-                    const int row = i * C::kRowsPerLoad + ld_row;
-                    const bool ok = src.page_ok && (src.pos0 + row < S);
-                    const int off = row * D + ld_col * 8;
-                    kr[i] = ok ? ld_stream(src.kbase + off) : uint4{0u, 0u, 0u, 0u};
-                    vr[i] = ok ? ld_stream(src.vbase + off) : uint4{0u, 0u, 0u, 0u};
+                    kr[i] = ld_stream(kb + lane_off + i * step);
+                    vr[i] = ld_stream(vb + lane_off + i * step);
                 }
             };
-            auto stage = [&](const uint4 (&kr)[C::kLoads], const uint4 (&vr)[C::kLoads]) {
+            auto stage = [&](int t, const uint4 (&kr)[C::kLoads], const uint4 (&vr)[C::kLoads]) {
+                const int pos0 = c0 + t * kTile;
+                const int page = tile_page(cp, t);
+                const bool page_ok = page >= 0 && (int64_t)page < p.num_pages;
+                if (page_ok && pos0 + kTile <= S) {              // the usual case: a full tile
 #pragma unroll
-                for (int i = 0; i < C::kLoads; ++i) {
-                    const int row = i * C::kRowsPerLoad + ld_row;
-                    *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[i];
-                    *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[i];
+                    for (int i = 0; i < C::kLoads; ++i) {
+                        const int row = i * C::kRowsPerLoad + ld_row;
+                        *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[i];
+                        *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[i];
+                    }
+                } else {                                         // rows past the end, or a page of zeros
+#pragma unroll
+                    for (int i = 0; i < C::kLoads; ++i) {
+                        const int row = i * C::kRowsPerLoad + ld_row;
+                        const bool ok = page_ok && pos0 + row < S;
+                        *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = ok ? kr[i] : uint4{0u, 0u, 0u, 0u};
+                        *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = ok ? vr[i] : uint4{0u, 0u, 0u, 0u};
+                    }
                 }
             };
 
-            int t = wave;
-            if (t < ntiles) issue_loads(t, kreg[0], vreg[0]);
-            if (t + kWaves < ntiles) issue_loads(t + kWaves, kreg[1], vreg[1]);
-            while (t < ntiles) {
-                stage(kreg[0], vreg[0]);
-                wave_lds_fence();
-                if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[0], vreg[0]);
-                compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
-                wave_lds_fence();
-                t += kWaves;
-                if (t >= ntiles) break;
-                stage(kreg[1], vreg[1]);
-                wave_lds_fence();
-                if (t + 2 * kWaves < ntiles) issue_loads(t + 2 * kWaves, kreg[1], vreg[1]);
-                compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
-                wave_lds_fence();
-                t += kWaves;
+            const int n_my = wave < ntiles ? (ntiles - wave + kWaves - 1) / kWaves : 0;   // tiles of this wavefront
+            if (n_my > 0) {
+                const int last = wave + kWaves * (n_my - 1);
+                int t = wave;
+                issue_loads(t, last, kreg[0], vreg[0]);
+                issue_loads(t + kWaves, last, kreg[1], vreg[1]);
+                for (int i = 0;; i += 2) {
+                    stage(t, kreg[0], vreg[0]);
+                    wave_lds_fence();
+                    issue_loads(t + 2 * kWaves, last, kreg[0], vreg[0]);
+                    compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
+                    wave_lds_fence();
+                    t += kWaves;
+                    if (i + 1 >= n_my) break;
+                    stage(t, kreg[1], vreg[1]);
+                    wave_lds_fence();
+                    issue_loads(t + 2 * kWaves, last, kreg[1], vreg[1]);
+                    compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
+                    wave_lds_fence();
+                    t += kWaves;
+                    if (i + 2 >= n_my) break;
+                }
             }
         }
 
@@ -750,11 +785,6 @@ __device__ __forceinline__ void lds_dma_tile(const void *kb, const void *vb, con
     }
 }
 #undef AGENTSAM_DMA_PIECE
-
-__device__ __forceinline__ void wait_vmcnt0() {
-    // s_waitcnt with only the vmcnt field active (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-}
 
 template <int D, int MT, int NS, bool XT>
 __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
@@ -1297,11 +1327,13 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
         pl->wide = rows > kRowsPerGroup;
         pl->rows_pad = (rows + 3) & ~3;                      // keeps every record 16-byte aligned
         pl->heads_outer = Hkv;
+        pl->nslots = kComputeUnits * (pl->wide ? 2 : 1);
         int64_t chunk = opt;
         if (chunk == 0) {
-            // aim at ~2048 workgroups (8 per compute unit) when the sequences are long enough
+            // about one workgroup per resident slot when every session has the maximum length: a
+            // single round of workgroups, each streaming for as long as possible
             const int64_t pairs = (int64_t)B * Hkv;
-            chunk = smax * (pairs > 0 ? pairs : 1) / 2048;
+            chunk = smax * (pairs > 0 ? pairs : 1) / pl->nslots;
             chunk = (chunk + 127) / 128 * 128;
             if (chunk < 1024) chunk = 1024;
             if (chunk > 8192) chunk = 8192;
@@ -1316,7 +1348,6 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
         // With at least two (session, kv head) streams per resident workgroup the batch is cut into
         // equal shares; with fewer, every stream is split anyway and the chunk grid keeps sessions
         // that share a prefix in step.  An explicit chunk size asks for the chunk grid.
-        pl->nslots = kComputeUnits * (pl->wide ? 2 : 1);
         const int64_t sched = agentsam::option_attn_schedule();
         const int64_t tiles_max = (int64_t)B * Hkv * ((smax + kTile - 1) / kTile);
         pl->balanced = sched == 2 || (sched == 0 && opt == 0 && (int64_t)B * Hkv >= 2 * (int64_t)pl->nslots);
@@ -1384,7 +1415,7 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     Plan pl;
     const int rc = make_plan(B, R, Hq, Hkv, D, page_size, max_pages, dtype, &pl);
     if (rc) return rc;
-    if (!(scale > 0.f) || num_pages < 0) return AGENTSAM_ERR_ARG;
+    if (!(scale > 0.f) || num_pages < 0 || (B > 0 && num_pages < 1)) return AGENTSAM_ERR_ARG;
     if (out_dtype != AGENTSAM_F32 && out_dtype != AGENTSAM_BF16) return AGENTSAM_ERR_UNSUPPORTED;
     if (B == 0) return AGENTSAM_OK;
     if (!q || !k_cache || !v_cache || !block_table || !seq_lens || !out) return AGENTSAM_ERR_NULL;
