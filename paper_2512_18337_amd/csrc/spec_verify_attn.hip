@@ -244,26 +244,36 @@ __device__ __forceinline__ void rescale(WaveState<D, MT> &w, const float (&mx)[M
     }
 }
 
-// Online softmax, part 2: weights 2^(s*c - m), their row sums, and the bf16 B operand of the
-// second contraction (k-slot 8g+j <-> position j<4 ? 4g+j : 16+4g+j-4).
+// Online softmax, part 2: weights 2^(s*c - m), rounded to bf16 for the second contraction (k-slot
+// 8g+j <-> position j<4 ? 4g+j : 16+4g+j-4), and their row sums.  The sums are taken over the ROUNDED
+// weights (packed dot product with ones, one instruction per two weights): numerator and denominator of
+// the output then use the same weights, so a row dominated by a few keys is not off by the rounding
+// error of its largest weight.
 template <int D, int MT, bool MASK>
 __device__ __forceinline__ void softmax_exp(WaveState<D, MT> &w, const f32x4 (&sacc)[2][MT], float c,
                                             bf16x8 (&pf)[MT]) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef short s16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, s16x2{0x3f80, 0x3f80});
 #pragma unroll
     for (int rt = 0; rt < MT; ++rt) {
         const float mref = w.m_run[rt];
-        float psum = 0.f;
+        float psum = w.l_part[rt];
         bf16x8 pk;
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float e = MASK ? __builtin_amdgcn_exp2f(sacc[pt][rt][r] - mref)   // -inf -> 0
-                                     : __builtin_amdgcn_exp2f(fmaf(sacc[pt][rt][r], c, -mref));
-                psum += e;
-                pk[pt * 4 + r] = (__bf16)e;
+            for (int r = 0; r < 4; r += 2) {
+                const float e0 = MASK ? __builtin_amdgcn_exp2f(sacc[pt][rt][r] - mref)   // -inf -> 0
+                                      : __builtin_amdgcn_exp2f(fmaf(sacc[pt][rt][r], c, -mref));
+                const float e1 = MASK ? __builtin_amdgcn_exp2f(sacc[pt][rt][r + 1] - mref)
+                                      : __builtin_amdgcn_exp2f(fmaf(sacc[pt][rt][r + 1], c, -mref));
+                const bf16x2 pr = {(__bf16)e0, (__bf16)e1};
+                pk[pt * 4 + r] = pr[0];
+                pk[pt * 4 + r + 1] = pr[1];
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
             }
-        w.l_part[rt] += psum;
+        w.l_part[rt] = psum;
         pf[rt] = pk;
     }
 }
