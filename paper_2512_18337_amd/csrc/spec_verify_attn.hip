@@ -902,10 +902,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
 #endif
             __syncthreads();                                 // tile t visible; everyone is done with tile t-1
             const int tn = t + NS - 1;                       // goes into the slot tile t-1 occupied
-#ifndef AGENTSAM_EXP_NO_DMA
-            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn, slot_cur == 0 ? NS - 1 : slot_cur - 1);
-#endif
 #ifdef AGENTSAM_EXP_NO_COMPUTE
+            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn, slot_cur == 0 ? NS - 1 : slot_cur - 1);
             continue;
 #endif
 
@@ -922,22 +920,33 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
                 for (int rt = 0; rt < MT; ++rt) sacc[pt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
                 sx[pt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
+            // K fragments one k-step ahead of the multiplications that use them
+            bf16x8 kf[2][2];
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt) kf[0][pt] = *(const bf16x8 *)(smem + kx + pt * 16 * W::kRowBytes);
 #pragma unroll
             for (int ks = 0; ks < D / 32; ++ks) {
-                bf16x8 kf[2];
+                if (ks + 1 < D / 32) {
 #pragma unroll
-                for (int pt = 0; pt < 2; ++pt) kf[pt] = *(const bf16x8 *)(smem + (kx ^ (ks << 6)) + pt * 16 * W::kRowBytes);
+                    for (int pt = 0; pt < 2; ++pt)
+                        kf[(ks + 1) & 1][pt] = *(const bf16x8 *)(smem + (kx ^ ((ks + 1) << 6)) + pt * 16 * W::kRowBytes);
+                }
 #pragma unroll
                 for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
                     for (int rt = 0; rt < MT; ++rt)
-                        sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
+                        sacc[pt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks & 1][pt], w.qf[rt][ks], sacc[pt][rt], 0, 0, 0);
                 if (mine) {
 #pragma unroll
                     for (int pt = 0; pt < 2; ++pt)
-                        sx[pt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pt], wx.qf[0][ks], sx[pt][0], 0, 0, 0);
+                        sx[pt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks & 1][pt], wx.qf[0][ks], sx[pt][0], 0, 0, 0);
                 }
             }
+#ifndef AGENTSAM_EXP_NO_DMA
+            // The next tile is requested here rather than right after the barrier: the address arithmetic
+            // and the load instructions of the fetching wavefront then run while its multiplications drain.
+            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn, slot_cur == 0 ? NS - 1 : slot_cur - 1);
+#endif
             // ---- first half of the V fragments: issued now so their LDS latency hides under the softmax
             auto load_vf = [&](int dt) {
                 const char *a0 = smem + (vx ^ (dt << 5));
