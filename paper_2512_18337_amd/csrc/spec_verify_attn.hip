@@ -961,6 +961,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
 #pragma unroll
             for (int i = 0; i < kHalf; ++i) vfa[i] = load_vf(i);
             __builtin_amdgcn_sched_barrier(0);               // keep the reads above the arithmetic below
+            // The wavefront yields to the other workgroup's wavefront on this SIMD while it does its
+            // softmax arithmetic and takes priority again for the matrix instructions: the two then tend
+            // to alternate on the matrix pipe instead of both queueing for it.
+            __builtin_amdgcn_s_setprio(0);
             // ---- softmax weights
             float c_eff = c;
             if ((sub == 0 && t == 0) || mask || raise_always) {   // rare: maxima, reference, masking
@@ -984,6 +988,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
                 }
                 softmax_exp<D, 1, false>(wx, sx, c_eff, pfx);
             }
+            __builtin_amdgcn_s_setprio(1);
             // ---- O^T += V^T . P^T ; the second half of V is fetched while the first is multiplied
             bf16x8 vfb[kHalf];
 #pragma unroll
