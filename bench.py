@@ -25,7 +25,10 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 
 # HBM bytes of one spec_verify_attn launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE
 # runs, scaled by a copy kernel of known size); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"cfg2-b64-32k": 8.68e9}      # profiles/spec_verify_attn_cfg2_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2-b64-32k": 8.605e9,         # profiles/spec_verify_attn_cfg2_hbm_traffic.txt
+    "cfg3-ragged-b128": 18.32e9,     # profiles/spec_verify_attn_cfg3_kernel_trace_and_traffic.txt
+}
 
 
 def parse():
