@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--attn-only", action="store_true", help="time only spec_verify_attn (for profiling)")
     ap.add_argument("--kv-chunk", type=int, default=0)
     ap.add_argument("--schedule", type=int, default=0, help="attn_schedule option: 0 auto, 1 chunk grid, 2 balanced")
+    ap.add_argument("--maintain", type=int, default=0, metavar="STEPS",
+                    help="also time STEPS rounds of incremental automaton maintenance (append, delta export, "
+                         "device update, sam_draft_delta); reported under detail.sam_maintenance")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (5 times): a kernel of known HBM traffic "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with")
@@ -102,6 +105,60 @@ def cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h,
                    f"KV positions to {t_attn_full:.1f} s)"),
         "host_cpus": os.cpu_count(),
     }
+
+
+def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev):
+    """Incremental maintenance of the device automaton: every round appends 2 tokens per session (about
+    what a verified step commits) to the memories, exports the delta, updates the device copy and drafts
+    from it.  Host times are wall clock, device times HIP events."""
+    import torch
+    rng = np.random.default_rng(cfg.seed)
+    mems = [list(m) for m in mems]
+    sams = [A.sam_build(np.asarray(m, np.int32), cfg.sep) for m in mems]
+    per_mem = 2 * cfg.B // len(mems)
+    t0 = time.perf_counter()
+    flat = A.sam_flatten(sams, grow_tokens=per_mem * (steps + 1))
+    t_flatten = time.perf_counter() - t0
+    fd = flat.to(dev)
+    mem_len = [len(m) for m in mems]
+    root_d = torch.as_tensor(flat.roots[idx], device=dev)
+    rows_end_d = torch.as_tensor(flat.rows_end[idx], device=dev)
+    t_host, t_dev, t_draft, n_ov = [], [], [], 0
+    for _ in range(steps):
+        th = time.perf_counter()
+        for i, T in enumerate(mems):
+            p = int(rng.integers(0, max(1, len(T) - per_mem)))
+            add = [x for x in T[p:p + per_mem] if x != cfg.sep] or [0]      # text seen before: matches, clones
+            A.sam_append(sams[i], np.asarray(add, np.int32))
+            T += add
+        n_ov = sum(A.sam_delta_sizes(s)[2] for s in sams)
+        cap = 2
+        while cap < 2 * n_ov:
+            cap *= 2
+        keys, dsts = A.overlay_table(cap)
+        deltas = [A.sam_delta_export(s, keys, dsts, int(flat.roots[i]), int(flat.corpus_begin[i]))
+                  for i, s in enumerate(sams)]
+        t_host.append(time.perf_counter() - th)
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record()
+        for i, d in enumerate(deltas):
+            A.sam_apply_delta(d, fd.state_rec, fd.lastpos)
+            n = d.new_tokens.shape[0]
+            at = int(flat.corpus_begin[i]) + mem_len[i]
+            fd.corpus[at:at + n] = torch.as_tensor(d.new_tokens, device=dev)
+            mem_len[i] += n
+        keys_d, dsts_d = torch.as_tensor(keys.view(np.int64), device=dev), torch.as_tensor(dsts, device=dev)
+        cend_d = torch.as_tensor((flat.corpus_begin + np.asarray(mem_len))[idx].astype(np.int32), device=dev)
+        e1.record()
+        A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
+        e2.record()
+        torch.cuda.synchronize()
+        t_dev.append(e0.elapsed_time(e1)); t_draft.append(e1.elapsed_time(e2))
+    return {"rounds": steps, "tokens_appended_per_round": per_mem * len(mems),
+            "host_append_and_export_us": float(np.median(t_host)) * 1e6,
+            "device_update_us_incl_uploads": float(np.median(t_dev)) * 1e3,
+            "t_draft_delta_us": float(np.median(t_draft)) * 1e3,
+            "overlay_transitions_at_end": int(n_ov), "full_flatten_ms": t_flatten * 1e3}
 
 
 def main():
@@ -228,6 +285,9 @@ def main():
                    "sam_build_tokens_per_s": sum(len(m) for m in mems) / t_build,
                    "attn_workspace_bytes": ws_bytes},
     }
+    if args.maintain > 0:
+        result["detail"]["sam_maintenance"] = measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx,
+                                                                  args.maintain, dev)
     if not args.no_cpu_baseline and not args.attn_only:
         result["cpu_baseline"] = cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h)
     else:

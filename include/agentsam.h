@@ -103,6 +103,60 @@ int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t c
 void sam_free(sam_t *s);
 
 /* ------------------------------------------------------------------------------------------
+ * Keeping a device copy current without flattening again (Sec. 5.4.2: verified tokens are
+ * inserted as the context grows; Alg. 4, "incrementally extend S with streamed tokens").
+ *
+ * After sam_flatten() the automaton records what a device copy of those arrays is missing once
+ * sam_append() has run: states whose walk record or last eligible end position changed (new
+ * states included), transitions added or redirected to a clone, and the new tokens.
+ *
+ *   sam_delta_sizes   counts of each; flat_states = states covered by the last sam_flatten
+ *                     (only those have a transition row).  AGENTSAM_ERR_ARG before any flatten.
+ *   sam_delta_export  writes, into caller-provided HOST arrays,
+ *       rec_idx[n_rec], rec_val[4*n_rec]          state ids and their new 16-byte walk records; a
+ *                                                 record of a maintained state names ANY one of its
+ *                                                 transitions, flagged -2-d when there are others
+ *       lastpos_idx[n_lastpos], lastpos_val[..]   state ids and their new lastpos
+ *       overlay_key[cap], overlay_dst[cap]        open-addressing table (linear probing, the hash of
+ *                                                 csrc/sam_hash.h) of ALL transitions added or
+ *                                                 redirected since the last sam_flatten, key =
+ *                                                 state << 32 | token; the caller passes it filled
+ *                                                 with ~0 keys (several automata packed in one set of
+ *                                                 arrays may be exported into the same table);
+ *                                                 cap a power of two >= 2 * n_overlay
+ *       new_tokens[n_new_tokens]                  to be written at corpus[corpus_base + old length ..)
+ *     and forgets the record / lastpos / token changes (the overlay keeps growing until the next
+ *     sam_flatten, which the caller should do once it is no longer small next to the automaton).
+ *     Ids are offset by state_base / corpus_base as in sam_flatten.  The device arrays state_rec and
+ *     lastpos must have room for the grown automaton (at most 2 states per token).
+ *   sam_apply_delta   device: scatters the exported records and lastpos values (device copies of
+ *                     the exported arrays) into state_rec and lastpos.
+ *   sam_draft_delta   device: sam_draft on a maintained copy.  A transition is looked up in the
+ *                     state's record, then in the overlay, then - for states below rows_end[b], the
+ *                     end of the state-id range that has flattened rows in session b's automaton -
+ *                     in the flattened row.  Same outputs and limits as sam_draft.
+ * ---------------------------------------------------------------------------------------- */
+int sam_delta_sizes(const sam_t *s, int64_t *n_rec, int64_t *n_lastpos, int64_t *n_overlay,
+                    int64_t *n_new_tokens, int64_t *flat_states);
+
+int sam_delta_export(sam_t *s, int32_t state_base, int32_t corpus_base,
+                     int32_t *rec_idx, int32_t *rec_val, int32_t *lastpos_idx, int32_t *lastpos_val,
+                     uint64_t *overlay_key, int32_t *overlay_dst, int64_t overlay_cap, int32_t *new_tokens);
+
+int sam_apply_delta(const int32_t *rec_idx, const int32_t *rec_val, int64_t n_rec,
+                    const int32_t *lastpos_idx, const int32_t *lastpos_val, int64_t n_lastpos,
+                    int32_t *state_rec, int32_t *lastpos, void *stream);
+
+int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
+                    const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,
+                    const uint64_t *overlay_key, const int32_t *overlay_dst, int64_t overlay_cap,
+                    const int32_t *rows_end, const int32_t *root, const int32_t *corpus_end,
+                    const int32_t *recent, const int32_t *recent_len,
+                    int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
+                    int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+                    void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * sam_draft (paper Sec. 5.4.2 and Alg. 4, FollowTransitions: "given the current verified
  * suffix, follow SAM transitions to retrieve a matching continuation with a specified length").
  *

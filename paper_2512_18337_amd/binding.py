@@ -23,8 +23,8 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 _vp = ctypes.c_void_p
 
 EXPORTS = ["agentsam_strerror", "agentsam_set_option", "sam_build", "sam_append", "sam_flat_sizes",
-           "sam_flatten", "sam_free", "sam_draft", "spec_verify_attn_workspace", "spec_verify_attn",
-           "spec_accept"]
+           "sam_flatten", "sam_free", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
+           "sam_draft", "sam_draft_delta", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept"]
 
 
 class AgentSamError(RuntimeError):
@@ -51,6 +51,11 @@ def lib():
         L.sam_free.argtypes = [_vp]
         L.sam_free.restype = None
         L.sam_draft.argtypes = [_vp] * 12 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp]
+        L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 5
+        L.sam_delta_export.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32] + [_vp] * 6 + [ctypes.c_int64, _vp]
+        L.sam_apply_delta.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
+        L.sam_draft_delta.argtypes = ([_vp] * 8 + [ctypes.c_int64] + [_vp] * 5 + [ctypes.c_int32] * 5 +
+                                      [_vp] * 4 + [_vp])
         L.spec_verify_attn_workspace.argtypes = [ctypes.c_int32] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
         L.spec_verify_attn.argtypes = ([_vp, _vp, _vp, _vp, ctypes.c_int32, _vp] + [ctypes.c_int32] * 6 +
                                        [ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
@@ -127,6 +132,7 @@ class FlatSam:
     roots: np.ndarray          # [n_automata] root state id of each automaton
     corpus_begin: np.ndarray   # [n_automata]
     corpus_end: np.ndarray     # [n_automata] exclusive
+    rows_end: np.ndarray = None  # [n_automata] end of the state ids that have a transition row (root + states flattened)
 
     def to(self, device):
         import torch
@@ -135,26 +141,71 @@ class FlatSam:
         pad = lambda a: a if a.shape[0] > 0 else np.zeros(1, dtype=np.int32)
         return FlatSam(cv(self.len), cv(self.link), cv(self.row_ptr), cv(pad(self.edge_tok)),
                        cv(pad(self.edge_dst)), cv(self.lastpos), cv(pad(self.corpus)), cv(self.state_rec),
-                       self.roots, self.corpus_begin, self.corpus_end)
+                       self.roots, self.corpus_begin, self.corpus_end, self.rows_end)
 
 
-def sam_flatten(sams: Sequence[Sam]) -> FlatSam:
-    """sam_flatten of each automaton into one packed set of host arrays."""
+def sam_flatten(sams: Sequence[Sam], grow_tokens: int = 0) -> FlatSam:
+    """sam_flatten of each automaton into one packed set of host arrays.
+
+    With grow_tokens > 0 every automaton gets room for that many more tokens (and two states per
+    token) behind its slice, so that the copy can be maintained with sam_delta_export / sam_apply_delta;
+    the unused entries hold -1."""
     sizes = [sam_flat_sizes(s) for s in sams]
-    ns, ne, nt = (sum(x[i] for x in sizes) for i in range(3))
-    out = FlatSam(np.zeros(ns, np.int32), np.zeros(ns, np.int32), np.zeros(ns + 1, np.int32),
-                  np.zeros(ne, np.int32), np.zeros(ne, np.int32), np.zeros(ns, np.int32),
-                  np.zeros(nt, np.int32), np.zeros(4 * ns, np.int32), np.zeros(len(sams), np.int32),
-                  np.zeros(len(sams), np.int32), np.zeros(len(sams), np.int32))
+    g = int(grow_tokens)
+    scap = [a + (2 * g if g else 0) for a, _, _ in sizes]
+    ccap = [c + g for _, _, c in sizes]
+    ns, ne, nt = sum(scap), sum(x[1] for x in sizes), sum(ccap)
+    fill = lambda n: np.full(n, -1, np.int32)
+    out = FlatSam(fill(ns), fill(ns), np.zeros(ns + 1, np.int32), np.zeros(ne, np.int32), np.zeros(ne, np.int32),
+                  fill(ns), fill(nt), fill(4 * ns), np.zeros(len(sams), np.int32),
+                  np.zeros(len(sams), np.int32), np.zeros(len(sams), np.int32), np.zeros(len(sams), np.int32))
     sb = eb = cb = 0
     for i, (s, (a, b, c)) in enumerate(zip(sams, sizes)):
         _check(lib().sam_flatten(s._h, sb, eb, cb, _npp(out.len[sb:]), _npp(out.link[sb:]),
                                  _npp(out.row_ptr[sb:]), _npp(out.edge_tok[eb:]) if b else None,
                                  _npp(out.edge_dst[eb:]) if b else None, _npp(out.lastpos[sb:]),
                                  _npp(out.corpus[cb:]) if c else None, _npp(out.state_rec[4 * sb:])), "sam_flatten")
-        out.roots[i], out.corpus_begin[i], out.corpus_end[i] = sb, cb, cb + c
-        sb, eb, cb = sb + a, eb + b, cb + c
+        out.roots[i], out.corpus_begin[i], out.corpus_end[i], out.rows_end[i] = sb, cb, cb + c, sb + a
+        out.row_ptr[sb + a:sb + scap[i] + 1] = eb + b          # states without a row (not read; kept consistent)
+        sb, eb, cb = sb + scap[i], eb + b, cb + ccap[i]
     return out
+
+
+@dataclass
+class SamDelta:
+    """What sam_delta_export wrote (host numpy arrays), see the header."""
+    rec_idx: np.ndarray
+    rec_val: np.ndarray        # [n_rec, 4]
+    lastpos_idx: np.ndarray
+    lastpos_val: np.ndarray
+    new_tokens: np.ndarray
+    n_overlay: int             # transitions in the overlay log since the last sam_flatten
+    flat_states: int
+
+
+def sam_delta_sizes(s: Sam):
+    v = [ctypes.c_int64() for _ in range(5)]
+    _check(lib().sam_delta_sizes(s._h, *[ctypes.byref(x) for x in v]), "sam_delta_sizes")
+    return tuple(x.value for x in v)      # n_rec, n_lastpos, n_overlay, n_new_tokens, flat_states
+
+
+def overlay_table(cap: int):
+    """An empty overlay table (host): keys ~0, capacity a power of two."""
+    assert cap >= 2 and cap & (cap - 1) == 0
+    return np.full(cap, np.uint64(0xFFFFFFFFFFFFFFFF), dtype=np.uint64), np.full(cap, -1, dtype=np.int32)
+
+
+def sam_delta_export(s: Sam, overlay_key: np.ndarray, overlay_dst: np.ndarray, state_base: int = 0,
+                     corpus_base: int = 0) -> SamDelta:
+    n_rec, n_lp, n_ov, n_tok, flat_states = sam_delta_sizes(s)
+    d = SamDelta(np.zeros(n_rec, np.int32), np.zeros((n_rec, 4), np.int32), np.zeros(n_lp, np.int32),
+                 np.zeros(n_lp, np.int32), np.zeros(n_tok, np.int32), n_ov, flat_states)
+    assert overlay_key.dtype == np.uint64 and overlay_dst.dtype == np.int32 and overlay_key.flags.c_contiguous
+    ptr = lambda a: _vp(a.ctypes.data) if a.size else _vp(0)
+    _check(lib().sam_delta_export(s._h, int(state_base), int(corpus_base), ptr(d.rec_idx), ptr(d.rec_val),
+                                  ptr(d.lastpos_idx), ptr(d.lastpos_val), ptr(overlay_key), ptr(overlay_dst),
+                                  overlay_key.shape[0], ptr(d.new_tokens)), "sam_delta_export")
+    return d
 
 
 # ----------------------------------------------------------------------------- device entry points
@@ -192,6 +243,40 @@ def sam_draft(flat: FlatSam, root, corpus_end, recent, recent_len, k: int, sep_t
                          _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
                          _stream_ptr())
     _check(rc, "sam_draft")
+    return draft, n_draft, match_len, match_end
+
+
+def sam_apply_delta(delta: SamDelta, state_rec, lastpos) -> None:
+    """Scatter an exported delta into the device arrays state_rec [4*cap] and lastpos [cap]."""
+    import torch
+    dev = state_rec.device
+    ri, rv = _dev_i32(delta.rec_idx, dev), _dev_i32(delta.rec_val.reshape(-1), dev)
+    li, lv = _dev_i32(delta.lastpos_idx, dev), _dev_i32(delta.lastpos_val, dev)
+    z = lambda t: _dp(t) if t.numel() else _vp(0)
+    _check(lib().sam_apply_delta(z(ri), z(rv), ri.numel(), z(li), z(lv), li.numel(), _dp(state_rec), _dp(lastpos),
+                                 _stream_ptr()), "sam_apply_delta")
+    torch.cuda.current_stream().synchronize()      # the staging tensors above die with this frame
+
+
+def sam_draft_delta(flat: FlatSam, overlay_key, overlay_dst, rows_end, root, corpus_end, recent, recent_len, k: int,
+                    sep_token: int, min_match: int = 1):
+    """sam_draft on a maintained device copy; overlay_key is a device int64/uint64 tensor, overlay_dst int32."""
+    import torch
+    dev = flat.state_rec.device
+    root, corpus_end, rows_end = _dev_i32(root, dev), _dev_i32(corpus_end, dev), _dev_i32(rows_end, dev)
+    recent, recent_len = _dev_i32(recent, dev), _dev_i32(recent_len, dev)
+    B, m = recent.shape
+    draft = torch.empty((B, k), dtype=torch.int32, device=dev)
+    n_draft = torch.empty((B,), dtype=torch.int32, device=dev)
+    match_len = torch.empty((B,), dtype=torch.int32, device=dev)
+    match_end = torch.empty((B,), dtype=torch.int32, device=dev)
+    rc = lib().sam_draft_delta(_dp(flat.row_ptr), _dp(flat.edge_tok), _dp(flat.edge_dst), _dp(flat.lastpos),
+                               _dp(flat.corpus), _dp(flat.state_rec), _dp(overlay_key), _dp(overlay_dst),
+                               overlay_key.numel(), _dp(rows_end), _dp(root), _dp(corpus_end), _dp(recent),
+                               _dp(recent_len), B, m, k, min_match, sep_token,
+                               _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
+                               _stream_ptr())
+    _check(rc, "sam_draft_delta")
     return draft, n_draft, match_len, match_end
 
 

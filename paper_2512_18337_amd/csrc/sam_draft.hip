@@ -10,8 +10,29 @@
 // states such as the root), and the continuation is read and cut with one load and a ballot.
 // Throughput comes from the sessions running side by side on different compute units.
 #include "common.h"
+#include "sam_hash.h"
 
 namespace {
+
+// The overlay of an incrementally maintained automaton: transitions added or redirected since the
+// last full flatten, in an open-addressing table keyed by (state, token).  Wave-uniform probe.
+struct Overlay {
+    const unsigned long long *key;
+    const int32_t *dst;
+    unsigned mask;                   // capacity - 1 (capacity a power of two, at most half full)
+};
+
+__device__ __forceinline__ int overlay_find(const Overlay &ov, int s, int c) {
+    const unsigned long long k = ((unsigned long long)(unsigned)s << 32) | (unsigned)c;
+    unsigned j = (unsigned)agentsam_hash64(k) & ov.mask;
+    for (unsigned probes = 0; probes <= ov.mask; ++probes) {          // bounded even for a full table
+        const unsigned long long kk = ov.key[j];
+        if (kk == k) return ov.dst[j];
+        if (kk == AGENTSAM_HASH_EMPTY) return -1;
+        j = (j + 1) & ov.mask;
+    }
+    return -1;
+}
 
 __device__ __forceinline__ int wave_bcast(int v, int src_lane) { return __shfl(v, src_lane, 64); }
 
@@ -38,6 +59,7 @@ __device__ __forceinline__ int find_edge(const int32_t *__restrict__ edge_tok,
     return wave_bcast(ds, __ffsll((long long)eq) - 1);
 }
 
+template <bool OVERLAY>
 __global__ __launch_bounds__(64) void sam_draft_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_tok,
     const int32_t *__restrict__ edge_dst, const int32_t *__restrict__ lastpos,
@@ -46,7 +68,7 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     const int32_t *__restrict__ recent, const int32_t *__restrict__ recent_len,
     int m, int k, int min_match, int sep,
     int32_t *__restrict__ draft, int32_t *__restrict__ n_draft, int32_t *__restrict__ match_len,
-    int32_t *__restrict__ match_end) {
+    int32_t *__restrict__ match_end, Overlay ov, const int32_t *__restrict__ rows_end) {
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
     const int root = __builtin_amdgcn_readfirstlane(root_arr[b]);
@@ -69,9 +91,18 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
             int dst = -1;
             if (r0 == c) {
                 dst = r1 >= 0 ? r1 : -2 - r1;
-            } else if (r1 < -1 && c > r0) {                // rows are sorted: c can only be further right
-                dst = __builtin_amdgcn_readfirstlane(
-                    find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane));
+            } else if (!OVERLAY) {
+                if (r1 < -1 && c > r0)                     // rows are sorted: c can only be further right
+                    dst = __builtin_amdgcn_readfirstlane(
+                        find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane));
+            } else if (r1 < -1) {
+                // Maintained automaton: the record holds any one transition; the overlay overrides the
+                // flattened row (a transition may have been redirected to a clone), and only states
+                // that existed at the last flatten have a row at all.
+                dst = __builtin_amdgcn_readfirstlane(overlay_find(ov, s, c));
+                if (dst < 0 && s < __builtin_amdgcn_readfirstlane(rows_end[b]))
+                    dst = __builtin_amdgcn_readfirstlane(
+                        find_edge(edge_tok, edge_dst, row_ptr[s], row_ptr[s + 1], c, lane));
             }
             if (dst >= 0) { s = dst; ++l; break; }
             if (s == root) { l = 0; break; }
@@ -127,10 +158,60 @@ extern "C" int sam_draft(const int32_t *len, const int32_t *link, const int32_t 
         return AGENTSAM_ERR_NULL;
     // edge_tok / edge_dst / corpus may be NULL only for an automaton with no transitions (empty
     // memory): then every row is empty and nothing matches, so they are never dereferenced.
-    hipLaunchKernelGGL(sam_draft_kernel, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(sam_draft_kernel<false>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
                        row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       draft, n_draft, match_len, match_end);
+                       draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, nullptr);
+    AGENTSAM_LAUNCH_CHECK();
+    return AGENTSAM_OK;
+}
+
+extern "C" int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
+                               const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,
+                               const uint64_t *overlay_key, const int32_t *overlay_dst, int64_t overlay_cap,
+                               const int32_t *rows_end, const int32_t *root, const int32_t *corpus_end,
+                               const int32_t *recent, const int32_t *recent_len,
+                               int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
+                               int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+                               void *stream) {
+    if (B < 0 || m < 1 || m > 64 || k < 0 || k > 64 || min_match < 0) return AGENTSAM_ERR_ARG;
+    if (overlay_cap < 2 || (overlay_cap & (overlay_cap - 1)) != 0 || overlay_cap > (1ll << 31)) return AGENTSAM_ERR_ARG;
+    if (B == 0) return AGENTSAM_OK;
+    if (!row_ptr || !lastpos || !state_rec || !overlay_key || !overlay_dst || !rows_end || !root || !corpus_end ||
+        !recent || !recent_len || !n_draft || !match_len || !match_end || (k > 0 && !draft))
+        return AGENTSAM_ERR_NULL;
+    const Overlay ov{(const unsigned long long *)overlay_key, overlay_dst, (unsigned)(overlay_cap - 1)};
+    hipLaunchKernelGGL(sam_draft_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
+                       row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
+                       recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
+                       draft, n_draft, match_len, match_end, ov, rows_end);
+    AGENTSAM_LAUNCH_CHECK();
+    return AGENTSAM_OK;
+}
+
+namespace {
+__global__ __launch_bounds__(256) void sam_apply_delta_kernel(const int32_t *__restrict__ rec_idx, const int4 *__restrict__ rec_val,
+                                                              int64_t n_rec, const int32_t *__restrict__ lp_idx,
+                                                              const int32_t *__restrict__ lp_val, int64_t n_lp,
+                                                              int4 *__restrict__ state_rec, int32_t *__restrict__ lastpos) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n_rec) state_rec[rec_idx[i]] = rec_val[i];
+    if (i < n_lp) lastpos[lp_idx[i]] = lp_val[i];
+}
+}  // namespace
+
+extern "C" int sam_apply_delta(const int32_t *rec_idx, const int32_t *rec_val, int64_t n_rec,
+                               const int32_t *lastpos_idx, const int32_t *lastpos_val, int64_t n_lastpos,
+                               int32_t *state_rec, int32_t *lastpos, void *stream) {
+    if (n_rec < 0 || n_lastpos < 0) return AGENTSAM_ERR_ARG;
+    if ((n_rec > 0 && (!rec_idx || !rec_val || !state_rec)) || (n_lastpos > 0 && (!lastpos_idx || !lastpos_val || !lastpos)))
+        return AGENTSAM_ERR_NULL;
+    const int64_t n = n_rec > n_lastpos ? n_rec : n_lastpos;
+    if (n == 0) return AGENTSAM_OK;
+    if ((n + 255) / 256 > 0x7fffffffll) return AGENTSAM_ERR_ARG;
+    hipLaunchKernelGGL(sam_apply_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       rec_idx, (const int4 *)rec_val, n_rec, lastpos_idx, lastpos_val, n_lastpos,
+                       (int4 *)state_rec, lastpos);
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }

@@ -18,6 +18,7 @@
 #include <vector>
 
 #include "agentsam.h"
+#include "sam_hash.h"
 
 struct sam {
     int32_t sep = -1;
@@ -30,12 +31,33 @@ struct sam {
     uint64_t h_used = 0;
     std::vector<int32_t> corpus;
 
+    // Incremental maintenance (Sec. 5.4.2: verified tokens are inserted as the context grows; Alg. 4,
+    // "incrementally extend S with streamed tokens").  After a full sam_flatten the automaton keeps
+    // track of what the device copy is missing: states whose walk record or last eligible end position
+    // changed, transitions added or redirected (they go into an overlay hash table that the draft
+    // lookup consults before the flattened transition rows), and the new tokens.
+    mutable bool track = false;
+    mutable int32_t flat_states = 0;                 // states of the last full flatten: rows exist below this id
+    mutable int64_t exported_tokens = 0;             // memory tokens the device copy already has
+    mutable std::vector<int32_t> lp;                 // last eligible end position per state, kept online
+    mutable std::vector<uint8_t> rec_dirty, lp_dirty;
+    mutable std::vector<int32_t> rec_list, lp_list;
+    mutable std::vector<int32_t> ov_state, ov_tok, ov_dst;
+
+    void mark_rec(int32_t v) {
+        if (!track || rec_dirty[(size_t)v]) return;
+        rec_dirty[(size_t)v] = 1;
+        rec_list.push_back(v);
+    }
+    void mark_lp(int32_t v) {
+        if (!track || lp_dirty[(size_t)v]) return;
+        lp_dirty[(size_t)v] = 1;
+        lp_list.push_back(v);
+    }
+
     static constexpr uint64_t kEmpty = ~0ull;
 
-    static uint64_t mix(uint64_t k) {
-        k ^= k >> 33; k *= 0xff51afd7ed558ccdull; k ^= k >> 33; k *= 0xc4ceb9fe1a85ec53ull; k ^= k >> 33;
-        return k;
-    }
+    static uint64_t mix(uint64_t k) { return agentsam_hash64(k); }
     static uint64_t key_of(int32_t st, int32_t tok) { return ((uint64_t)(uint32_t)st << 32) | (uint32_t)tok; }
 
     void rehash(uint64_t cap) {
@@ -66,10 +88,19 @@ struct sam {
         uint64_t k = key_of(st, tok), j = mix(k) & h_mask;
         while (h_key[j] != kEmpty) j = (j + 1) & h_mask;
         h_key[j] = k; h_val[j] = e; ++h_used;
+        if (track) {
+            ov_state.push_back(st); ov_tok.push_back(tok); ov_dst.push_back(dst);
+            mark_rec(st);
+        }
     }
     int32_t new_state(int32_t l, int32_t lk, int32_t created) {
         len.push_back(l); link.push_back(lk); created_at.push_back(created); head.push_back(-1);
-        return (int32_t)len.size() - 1;
+        const int32_t v = (int32_t)len.size() - 1;
+        if (track) {
+            lp.push_back(-1); rec_dirty.push_back(0); lp_dirty.push_back(0);
+            mark_rec(v); mark_lp(v);                         // a new state needs both of its device entries
+        }
+        return v;
     }
     void init(int32_t sep_token) {
         sep = sep_token;
@@ -79,6 +110,7 @@ struct sam {
     }
     void extend(int32_t c) {
         const int32_t pos = (int32_t)corpus.size();
+        const int32_t prev_last = last;
         corpus.push_back(c);
         const int32_t cur = new_state(len[last] + 1, 0, pos);
         int32_t p = last;
@@ -94,17 +126,32 @@ struct sam {
             } else {
                 const int32_t cl = new_state(len[p] + 1, link[q], -1);
                 for (int32_t x = head[q]; x != -1; x = e_next[x]) add_edge(cl, e_tok[x], e_dst[x]);
+                if (track) lp[(size_t)cl] = lp[(size_t)q];   // the clone ends wherever q ended so far
                 while (p != -1) {
                     const int32_t ee = find(p, c);
                     if (ee < 0 || e_dst[ee] != q) break;
                     e_dst[ee] = cl;
+                    if (track) {
+                        ov_state.push_back(p); ov_tok.push_back(c); ov_dst.push_back(cl);
+                        mark_rec(p);
+                    }
                     p = link[p];
                 }
                 link[q] = cl;
                 link[cur] = cl;
+                mark_rec(q);
             }
         }
         last = cur;
+        // The previous position now has a continuation (unless the new token is the separator): it is
+        // the most recent eligible end position of every string that ends there, i.e. of the state of
+        // the previous prefix and of all its suffix-link ancestors.
+        if (track && pos >= 1 && c != sep) {
+            for (int32_t v = prev_last; v != -1; v = link[v]) {
+                lp[(size_t)v] = pos - 1;
+                mark_lp(v);
+            }
+        }
     }
 };
 
@@ -218,9 +265,83 @@ int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t c
         }
         row_ptr[ns] = (int32_t)(at + edge_base);
         if (nt > 0) std::memcpy(corpus, s->corpus.data(), (size_t)nt * sizeof(int32_t));
+        // from here on the automaton records what a device copy of these arrays will be missing
+        s->track = true;
+        s->flat_states = (int32_t)ns;
+        s->exported_tokens = nt;
+        s->lp.swap(lp);
+        s->rec_dirty.assign((size_t)ns, 0); s->lp_dirty.assign((size_t)ns, 0);
+        s->rec_list.clear(); s->lp_list.clear();
+        s->ov_state.clear(); s->ov_tok.clear(); s->ov_dst.clear();
     } catch (const std::bad_alloc &) {
         return AGENTSAM_ERR_NOMEM;
     }
+    return AGENTSAM_OK;
+}
+
+int sam_delta_sizes(const sam_t *s, int64_t *n_rec, int64_t *n_lastpos, int64_t *n_overlay,
+                    int64_t *n_new_tokens, int64_t *flat_states) {
+    if (!s) return AGENTSAM_ERR_NULL;
+    if (!s->track) return AGENTSAM_ERR_ARG;                  // nothing to be relative to: flatten first
+    if (n_rec) *n_rec = (int64_t)s->rec_list.size();
+    if (n_lastpos) *n_lastpos = (int64_t)s->lp_list.size();
+    if (n_overlay) *n_overlay = (int64_t)s->ov_state.size();
+    if (n_new_tokens) *n_new_tokens = (int64_t)s->corpus.size() - s->exported_tokens;
+    if (flat_states) *flat_states = s->flat_states;
+    return AGENTSAM_OK;
+}
+
+int sam_delta_export(sam_t *s, int32_t state_base, int32_t corpus_base,
+                     int32_t *rec_idx, int32_t *rec_val, int32_t *lastpos_idx, int32_t *lastpos_val,
+                     uint64_t *overlay_key, int32_t *overlay_dst, int64_t overlay_cap, int32_t *new_tokens) {
+    if (!s) return AGENTSAM_ERR_NULL;
+    if (!s->track) return AGENTSAM_ERR_ARG;
+    const size_t nr = s->rec_list.size(), nl = s->lp_list.size(), no = s->ov_state.size();
+    const int64_t ntok = (int64_t)s->corpus.size() - s->exported_tokens;
+    if ((nr > 0 && (!rec_idx || !rec_val)) || (nl > 0 && (!lastpos_idx || !lastpos_val)) ||
+        (no > 0 && (!overlay_key || !overlay_dst)) || (ntok > 0 && !new_tokens))
+        return AGENTSAM_ERR_NULL;
+    if (state_base < 0 || corpus_base < 0) return AGENTSAM_ERR_ARG;
+    if ((int64_t)state_base + (int64_t)s->len.size() > INT32_MAX ||
+        (int64_t)corpus_base + (int64_t)s->corpus.size() > INT32_MAX) return AGENTSAM_ERR_ARG;
+    if (no > 0 && (overlay_cap < 2 || (overlay_cap & (overlay_cap - 1)) != 0 || (int64_t)no * 2 > overlay_cap))
+        return AGENTSAM_ERR_ARG;                             // power of two, at most half full
+    // transitions: later entries of the log override earlier ones with the same (state, token)
+    const uint64_t mask = (uint64_t)overlay_cap - 1;
+    for (size_t i = 0; i < no; ++i) {
+        const uint64_t key = ((uint64_t)(uint32_t)(s->ov_state[i] + state_base) << 32) | (uint32_t)s->ov_tok[i];
+        uint64_t j = agentsam_hash64(key) & mask;
+        while (overlay_key[j] != AGENTSAM_HASH_EMPTY && overlay_key[j] != key) j = (j + 1) & mask;
+        overlay_key[j] = key;
+        overlay_dst[j] = s->ov_dst[i] + state_base;
+    }
+    for (size_t i = 0; i < nr; ++i) {
+        const int32_t v = s->rec_list[i];
+        const int32_t h = s->head[(size_t)v];
+        rec_idx[i] = v + state_base;
+        int32_t *rec = rec_val + 4 * i;
+        if (h < 0) {
+            rec[0] = -1; rec[1] = -1;
+        } else {                                             // any one transition; the others are in the overlay or the rows
+            const int32_t d = s->e_dst[(size_t)h] + state_base;
+            rec[0] = s->e_tok[(size_t)h];
+            rec[1] = s->e_next[(size_t)h] == -1 ? d : -2 - d;
+        }
+        const int32_t lk = s->link[(size_t)v];
+        rec[2] = lk < 0 ? -1 : lk + state_base;
+        rec[3] = lk < 0 ? 0 : s->len[(size_t)lk];
+        s->rec_dirty[(size_t)v] = 0;
+    }
+    for (size_t i = 0; i < nl; ++i) {
+        const int32_t v = s->lp_list[i];
+        lastpos_idx[i] = v + state_base;
+        lastpos_val[i] = s->lp[(size_t)v] < 0 ? -1 : s->lp[(size_t)v] + corpus_base;
+        s->lp_dirty[(size_t)v] = 0;
+    }
+    if (ntok > 0)
+        std::memcpy(new_tokens, s->corpus.data() + s->exported_tokens, (size_t)ntok * sizeof(int32_t));
+    s->rec_list.clear(); s->lp_list.clear();
+    s->exported_tokens = (int64_t)s->corpus.size();
     return AGENTSAM_OK;
 }
 

@@ -1,0 +1,101 @@
+"""GPU parity of the maintained automaton copy (sam_delta_export -> sam_apply_delta -> sam_draft_delta)
+against the CPU oracle on the grown memory, bit-exact, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_18337_amd as A
+from oracle import draft_oracle
+from paper_2512_18337_amd import workloads as W
+from _util import to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _sync(sams, fd, flat, mem_len):
+    """Export every automaton's delta into one overlay table and bring the device copy up to date."""
+    n_ov = sum(A.sam_delta_sizes(s)[2] for s in sams)
+    cap = 2
+    while cap < 2 * n_ov:
+        cap *= 2
+    keys, dsts = A.overlay_table(cap)
+    for i, s in enumerate(sams):
+        d = A.sam_delta_export(s, keys, dsts, int(flat.roots[i]), int(flat.corpus_begin[i]))
+        assert int(flat.roots[i]) + d.flat_states == int(flat.rows_end[i])
+        A.sam_apply_delta(d, fd.state_rec, fd.lastpos)
+        n = d.new_tokens.shape[0]
+        if n:
+            at = int(flat.corpus_begin[i]) + mem_len[i]
+            fd.corpus[at:at + n] = torch.as_tensor(d.new_tokens, device=DEV)
+            mem_len[i] += n
+    return torch.as_tensor(keys.view(np.int64), device=DEV), torch.as_tensor(dsts, device=DEV)
+
+
+def _windows(rng, mems, owner, m, vocab):
+    B = len(owner)
+    recent = np.zeros((B, m), np.int32); rlen = np.zeros(B, np.int32)
+    for b in range(B):
+        T = mems[owner[b]]
+        if len(T) > m + 2 and rng.random() < 0.85:
+            p = int(rng.integers(m, len(T)))                 # may end inside the freshly appended tail
+            w = np.array(T[p - m:p], np.int32)
+            w[m - 1 - int(rng.integers(1, m))] = int(rng.integers(0, vocab))
+        else:
+            w = rng.integers(0, vocab, m).astype(np.int32)
+        recent[b], rlen[b] = w, m if rng.random() < 0.9 else int(rng.integers(0, m))
+    return recent, rlen
+
+
+@pytest.mark.parametrize("shared", [True, False])
+def test_maintained_copy_on_device_matches_oracle(shared):
+    cfg = W.scaled(W.baseline_config(2), B=24, sam_sessions=6, sam_session_len=1500, vocab=2000, m=32, k=8)
+    rng = np.random.default_rng(77 + int(shared))
+    if shared:
+        mems = [list(W.token_memory(cfg))]
+        owner = [0] * cfg.B
+    else:
+        one = W.scaled(cfg, sam_mode="per_session", sam_sessions=1, sam_session_len=2500)
+        mems = [list(W.token_memory(one, i)) for i in range(3)]
+        owner = [b % 3 for b in range(cfg.B)]
+    sams = [A.sam_build(np.asarray(T, np.int32), cfg.sep) for T in mems]
+    grow = 1200
+    flat = A.sam_flatten(sams, grow_tokens=grow)
+    fd = flat.to(DEV)
+    mem_len = [len(T) for T in mems]
+    for rnd in range(12):
+        for i, T in enumerate(mems):
+            add = []
+            for _ in range(int(rng.integers(1, 5))):         # a few spans: copies of earlier text and fresh tokens
+                if rng.random() < 0.6 and len(T) > 50:
+                    p = int(rng.integers(0, len(T) - 20)); add += T[p:p + int(rng.integers(2, 20))]
+                else:
+                    add += [int(x) for x in rng.integers(0, cfg.vocab, int(rng.integers(1, 9)))]
+            if rnd % 4 == 1:
+                add.append(cfg.sep)                          # a session ends inside the appended text
+            add = add[:grow // 12 - 1]
+            A.sam_append(sams[i], np.asarray(add, np.int32))
+            T += add
+        keys, dsts = _sync(sams, fd, flat, mem_len)
+        assert mem_len == [len(T) for T in mems]
+        cend = np.array([int(flat.corpus_begin[owner[b]]) + mem_len[owner[b]] for b in range(cfg.B)], np.int32)
+        root = np.array([flat.roots[owner[b]] for b in range(cfg.B)], np.int32)
+        rows_end = np.array([flat.rows_end[owner[b]] for b in range(cfg.B)], np.int32)
+        recent, rlen = _windows(rng, mems, owner, cfg.m, cfg.vocab)
+        print(f"maintained copy round {rnd}: overlay capacity {keys.numel()}", flush=True)
+        d, nd, ml, me = A.sam_draft_delta(fd, keys, dsts, rows_end, root, cend, recent, rlen, cfg.k, cfg.sep)
+        torch.cuda.synchronize()
+        d, nd, ml, me = to_np(d), to_np(nd), to_np(ml), to_np(me)
+        for b in range(cfg.B):
+            T = np.asarray(mems[owner[b]], np.int32)
+            q = recent[b, cfg.m - rlen[b]:]
+            od, ond, oml, ome = draft_oracle(T, q, cfg.k, cfg.sep, 1)
+            got_end = int(me[b]) - int(flat.corpus_begin[owner[b]]) if me[b] >= 0 else -1
+            assert (int(ml[b]), got_end, int(nd[b])) == (oml, ome, ond), (rnd, b)
+            assert list(d[b, :ond]) == list(od[:ond]) and (d[b, ond:] == -1).all()
+    # a fresh flatten of the grown automata, read by the plain kernel, gives the same answers
+    flat2 = A.sam_flatten(sams)
+    d2, nd2, ml2, me2 = A.sam_draft(flat2.to(DEV), [flat2.roots[o] for o in owner], [flat2.corpus_end[o] for o in owner],
+                                    recent, rlen, cfg.k, cfg.sep)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(d2), d) and np.array_equal(to_np(ml2), ml) and np.array_equal(to_np(nd2), nd)
