@@ -157,6 +157,35 @@ int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32
                     void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Asynchronous construction (Sec. 5.4.2, "Asynchronous SAM construction"; Alg. 4 step 2: a
+ * background thread extends the automaton with streamed tokens).  A builder owns one child thread, a
+ * waiting queue and the automata of the requests submitted to it.
+ *
+ *   sam_builder_submit   copies the tokens (a prompt, or tokens generated since) into the queue and
+ *                        returns at once; the request's automaton is created by its first entry.
+ *   sam_builder_poll     *out = the request's automaton if none of its entries is waiting or being
+ *                        processed, else NULL: the automaton is "not yet available" and the caller
+ *                        decodes that request without drafts.  *pending_tokens = tokens not yet in it.
+ *                        A returned automaton stays valid and unchanged until the caller's next submit
+ *                        or release for that request (use it with sam_flatten, sam_delta_export, ...;
+ *                        never sam_free it).  Returns the error of a failed background append, if any.
+ *   sam_builder_wait     blocks until the request has nothing pending.
+ *   sam_builder_release  forgets the request; its automaton is freed (at once, or when the child
+ *                        thread reaches its last entry).  The id may not be reused until then.
+ *   sam_builder_destroy  stops the child thread (entries still waiting are abandoned) and frees
+ *                        every automaton.
+ * Calls on one builder may come from any thread; AGENTSAM_ERR_ARG for an unknown request id.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct sam_builder sam_builder_t;
+
+int sam_builder_create(sam_builder_t **out);
+int sam_builder_submit(sam_builder_t *b, int64_t request_id, const int32_t *tokens, int64_t n, int32_t sep_token);
+int sam_builder_poll(sam_builder_t *b, int64_t request_id, sam_t **out, int64_t *pending_tokens);
+int sam_builder_wait(sam_builder_t *b, int64_t request_id);
+int sam_builder_release(sam_builder_t *b, int64_t request_id);
+void sam_builder_destroy(sam_builder_t *b);
+
+/* ------------------------------------------------------------------------------------------
  * sam_draft (paper Sec. 5.4.2 and Alg. 4, FollowTransitions: "given the current verified
  * suffix, follow SAM transitions to retrieve a matching continuation with a specified length").
  *

@@ -23,7 +23,8 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 _vp = ctypes.c_void_p
 
 EXPORTS = ["agentsam_strerror", "agentsam_set_option", "sam_build", "sam_append", "sam_flat_sizes",
-           "sam_flatten", "sam_free", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
+           "sam_flatten", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
+           "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
            "sam_draft", "sam_draft_delta", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept"]
 
 
@@ -52,6 +53,13 @@ def lib():
         L.sam_free.restype = None
         L.sam_draft.argtypes = [_vp] * 12 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp]
         L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 5
+        L.sam_builder_create.argtypes = [ctypes.POINTER(_vp)]
+        L.sam_builder_submit.argtypes = [_vp, ctypes.c_int64, _i32p, ctypes.c_int64, ctypes.c_int32]
+        L.sam_builder_poll.argtypes = [_vp, ctypes.c_int64, ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_int64)]
+        L.sam_builder_wait.argtypes = [_vp, ctypes.c_int64]
+        L.sam_builder_release.argtypes = [_vp, ctypes.c_int64]
+        L.sam_builder_destroy.argtypes = [_vp]
+        L.sam_builder_destroy.restype = None
         L.sam_delta_export.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32] + [_vp] * 6 + [ctypes.c_int64, _vp]
         L.sam_apply_delta.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
         L.sam_draft_delta.argtypes = ([_vp] * 8 + [ctypes.c_int64] + [_vp] * 5 + [ctypes.c_int32] * 5 +
@@ -91,13 +99,48 @@ def _npp(a: np.ndarray):
 class Sam:
     """Owner of one sam_t handle."""
 
-    def __init__(self, handle: int):
+    def __init__(self, handle: int, owned: bool = True):
         self._h = _vp(handle)
+        self._owned = owned            # False: the handle belongs to a SamBuilder
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h is not None and h.value and _lib is not None:
+        if h is not None and h.value and _lib is not None and getattr(self, "_owned", True):
             _lib.sam_free(h)
+
+
+class SamBuilder:
+    """Asynchronous construction: one child thread, a waiting queue, the automata of the submitted requests."""
+
+    def __init__(self):
+        h = _vp()
+        _check(lib().sam_builder_create(ctypes.byref(h)), "sam_builder_create")
+        self._h = h
+
+    def submit(self, request_id: int, tokens, sep_token: int) -> None:
+        t = _np_i32(tokens)
+        _check(lib().sam_builder_submit(self._h, int(request_id), _npp(t), t.shape[0], int(sep_token)),
+               "sam_builder_submit")
+
+    def poll(self, request_id: int):
+        """(Sam or None, tokens not yet in the automaton).  None: not available yet, decode without drafts."""
+        out, pending = _vp(), ctypes.c_int64()
+        _check(lib().sam_builder_poll(self._h, int(request_id), ctypes.byref(out), ctypes.byref(pending)),
+               "sam_builder_poll")
+        return (Sam(out.value, owned=False) if out.value else None), pending.value
+
+    def wait(self, request_id: int) -> None:
+        _check(lib().sam_builder_wait(self._h, int(request_id)), "sam_builder_wait")
+
+    def release(self, request_id: int) -> None:
+        _check(lib().sam_builder_release(self._h, int(request_id)), "sam_builder_release")
+
+    def close(self) -> None:
+        h, self._h = getattr(self, "_h", None), None
+        if h is not None and h.value and _lib is not None:
+            _lib.sam_builder_destroy(h)
+
+    __del__ = close
 
 
 def sam_build(tokens, sep_token: int) -> Sam:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagentsam.so")
-SOURCES = ["sam_host.cpp", "options.cpp", "sam_draft.hip", "spec_accept.hip", "spec_verify_attn.hip"]
+SOURCES = ["sam_host.cpp", "sam_builder.cpp", "options.cpp", "sam_draft.hip", "spec_accept.hip", "spec_verify_attn.hip"]
 
 
 def build(verbose: bool = False) -> str:
@@ -22,7 +22,7 @@ def build(verbose: bool = False) -> str:
         path = os.path.join(CSRC, s)
         cmd += (["-x", "hip", path] if s.endswith(".hip") else ["-x", "hip", path])
     cmd += os.environ.get("AGENTSAM_EXTRA_HIPCC_FLAGS", "").split()     # timing experiments only
-    cmd += ["-o", LIB]
+    cmd += ["-pthread", "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
