@@ -250,6 +250,31 @@ int spec_accept(const void *logits, int32_t logits_dtype, const int32_t *draft,
                 const int32_t *n_draft, int32_t B, int32_t k, int64_t V,
                 int32_t *accept_len, int32_t *out_tokens, int32_t *tgt, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Host-side controllers of the serving loop.
+ *
+ * spec_adaptive_k (Sec. 5.4.2, "Adaptive switch for speculative decoding"; Alg. 4 step 4): beyond a
+ * context length or a batch size - thresholds the deployment determines empirically - speculation no
+ * longer pays.  *k_out = 0 if context_len > context_threshold or batch > batch_threshold, else k.
+ *
+ * agentsched_pick (Alg. 3, Agent Scheduler): which queued request to admit next.  Per request i:
+ * hit[i] = KV blocks it would reuse, need[i] = new KV blocks it needs, prompt_tok[i] = prompt length,
+ * wait[i] = time waited.  With H = sum hit, U = max(0, free_blocks - H), D = sum need:
+ *     lambda   = lambda_max * logistic(k * (D / (U + eps) - 1))
+ *     sjf_mix  = clamp(1 - lambda / lambda_max, 0, 1)
+ *     need_eff = sjf_mix * prompt_tok[i] / tokens_per_block + (1 - sjf_mix) * need[i]
+ *     score[i] = a * hit[i] - (b + lambda) * need_eff + c * wait[i]
+ * *picked = the highest-scoring request with need[i] <= free_blocks (the earlier one on equal
+ * scores), -1 if none fits.  score may be NULL.  All arrays are host memory; a, b, c, k, lambda_max,
+ * eps are the deployment's constants (the paper prints none).
+ * ---------------------------------------------------------------------------------------- */
+int spec_adaptive_k(int32_t batch, int64_t context_len, int32_t k, int32_t batch_threshold,
+                    int64_t context_threshold, int32_t *k_out);
+
+int agentsched_pick(int64_t free_blocks, const int64_t *hit, const int64_t *need, const int64_t *prompt_tok,
+                    const double *wait, int64_t n, double lambda_max, double k, double eps, double a, double b,
+                    double c, int32_t tokens_per_block, double *lambda_out, double *score, int64_t *picked);
+
 #ifdef __cplusplus
 }
 #endif

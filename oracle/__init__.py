@@ -13,6 +13,8 @@ code.
                paged KV cache                                [Alg. 4 "Validate with main LLM"]
   accept     - first-index argmax per row and the matched draft prefix
                                                              [Alg. 4 "commit matched prefix"]
+  sched      - AgentSched shadow price, scores and pick; the adaptive
+               speculation switch                            [Alg. 3; Alg. 4 step 4]
 
 Every function is pinned by tests that run without a GPU (worked examples,
 closed forms, invariants, an independent brute force, library special cases);
@@ -21,3 +23,4 @@ none is "parity unpinned".
 from .draft import draft_oracle, draft_oracle_batch, build_oracle_lib  # noqa: F401
 from .attention import attention_oracle, attention_oracle_head          # noqa: F401
 from .accept import accept_oracle                                        # noqa: F401
+from .sched import adaptive_k_oracle, agentsched_oracle                   # noqa: F401

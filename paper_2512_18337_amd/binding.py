@@ -25,7 +25,8 @@ _vp = ctypes.c_void_p
 EXPORTS = ["agentsam_strerror", "agentsam_set_option", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
-           "sam_draft", "sam_draft_delta", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept"]
+           "sam_draft", "sam_draft_delta", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
+           "spec_adaptive_k", "agentsched_pick"]
 
 
 class AgentSamError(RuntimeError):
@@ -53,6 +54,11 @@ def lib():
         L.sam_free.restype = None
         L.sam_draft.argtypes = [_vp] * 12 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp]
         L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 5
+        L.spec_adaptive_k.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+                                      ctypes.POINTER(ctypes.c_int32)]
+        L.agentsched_pick.argtypes = ([ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64] + [ctypes.c_double] * 6 +
+                                      [ctypes.c_int32, ctypes.POINTER(ctypes.c_double), _vp,
+                                       ctypes.POINTER(ctypes.c_int64)])
         L.sam_builder_create.argtypes = [ctypes.POINTER(_vp)]
         L.sam_builder_submit.argtypes = [_vp, ctypes.c_int64, _i32p, ctypes.c_int64, ctypes.c_int32]
         L.sam_builder_poll.argtypes = [_vp, ctypes.c_int64, ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_int64)]
@@ -321,6 +327,29 @@ def sam_draft_delta(flat: FlatSam, overlay_key, overlay_dst, rows_end, root, cor
                                _stream_ptr())
     _check(rc, "sam_draft_delta")
     return draft, n_draft, match_len, match_end
+
+
+def spec_adaptive_k(batch: int, context_len: int, k: int, batch_threshold: int, context_threshold: int) -> int:
+    out = ctypes.c_int32()
+    _check(lib().spec_adaptive_k(int(batch), int(context_len), int(k), int(batch_threshold), int(context_threshold),
+                                 ctypes.byref(out)), "spec_adaptive_k")
+    return out.value
+
+
+def agentsched_pick(free_blocks: int, hit, need, prompt_tok, wait, *, lambda_max: float, k: float, eps: float,
+                    a: float, b: float, c: float, tokens_per_block: int):
+    """Returns (lambda, scores[n], picked index or -1)."""
+    hit, need, prompt_tok = (np.ascontiguousarray(x, dtype=np.int64) for x in (hit, need, prompt_tok))
+    wait = np.ascontiguousarray(wait, dtype=np.float64)
+    n = hit.shape[0]
+    score = np.zeros(n, np.float64)
+    lam, picked = ctypes.c_double(), ctypes.c_int64()
+    ptr = lambda x: _vp(x.ctypes.data) if x.size else _vp(0)
+    _check(lib().agentsched_pick(int(free_blocks), ptr(hit), ptr(need), ptr(prompt_tok), ptr(wait), n,
+                                 float(lambda_max), float(k), float(eps), float(a), float(b), float(c),
+                                 int(tokens_per_block), ctypes.byref(lam), ptr(score), ctypes.byref(picked)),
+           "agentsched_pick")
+    return lam.value, score, picked.value
 
 
 def _dtype_code(t) -> int:
