@@ -28,6 +28,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_BYTES = {
     "cfg2-b64-32k": 8.605e9,         # profiles/spec_verify_attn_cfg2_hbm_traffic.txt
     "cfg3-ragged-b128": 18.32e9,     # profiles/spec_verify_attn_cfg3_kernel_trace_and_traffic.txt
+    "cfg4-shared-prefix": 4.81e9,    # profiles/spec_verify_attn_cfg4_kernel_trace_and_traffic.txt (logical bytes: 14.19e9)
+    "cfg1-b16-8k": 0.551e9,          # profiles/spec_verify_attn_cfg1_kernel_trace_and_traffic.txt
 }
 
 
