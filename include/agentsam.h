@@ -91,7 +91,8 @@ int sam_flat_sizes(const sam_t *s, int64_t *n_states, int64_t *n_edges, int64_t 
  *                   [0] token of the state's first (smallest-token) transition, -1 if none
  *                   [1] its destination d if it is the only transition, -2-d if there are more
  *                       (the rest are found in the CSR row), -1 if none
- *                   [2] suffix link (as in link[])    [3] len of the suffix link's state (0 for the root)
+ *                   [2] suffix link (as in link[])    [3] len of the suffix link's state (0 for the root),
+ *                       stored as -1-len for a state with more than 64 transitions (see sam_wide_table)
  * Several automata can be packed back to back in one set of arrays: state ids (link,
  * edge_dst) are offset by state_base, row_ptr values by edge_base, lastpos by corpus_base,
  * and the pointers passed here address this automaton's slice (row_ptr[ns] of one slice is
@@ -99,6 +100,18 @@ int sam_flat_sizes(const sam_t *s, int64_t *n_states, int64_t *n_edges, int64_t 
 int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t corpus_base,
                 int32_t *len, int32_t *link, int32_t *row_ptr, int32_t *edge_tok,
                 int32_t *edge_dst, int32_t *lastpos, int32_t *corpus, int32_t *state_rec);
+
+/* Very wide states (the root, a few very frequent tokens) would take several dependent probes of
+ * their sorted row per lookup.  Their transitions are therefore also offered in an open-addressing
+ * table with one probe per lookup: 16-byte slots {key low, key high, destination, 0}, key =
+ * state << 32 | token, linear probing with the hash of csrc/sam_hash.h, free slots hold key ~0.
+ *   sam_wide_slots   the number of slots this automaton needs (a power of two, at most half full).
+ *   sam_wide_table   inserts the automaton's wide transitions into table[4*slots] (HOST), which the
+ *                    caller has filled with -1; automata packed in one set of arrays may share one
+ *                    table (slots = a power of two >= the sum of their needs).
+ * The table is optional for sam_draft (NULL: the sorted rows are searched). */
+int sam_wide_slots(const sam_t *s, int64_t *slots);
+int sam_wide_table(const sam_t *s, int32_t state_base, int32_t *table, int64_t slots);
 
 void sam_free(sam_t *s);
 
@@ -200,6 +213,7 @@ void sam_builder_destroy(sam_builder_t *b);
  *                 session's memory in `corpus`), recent[B,m], recent_len[B] (0..m).
  * Device outputs: draft[B,k] (-1 padded), n_draft[B], match_len[B], match_end[B] (index into
  *                 `corpus`, -1 when nothing matched).  match_len < min_match gives no draft.
+ * wide_table    : device copy of the sam_wide_table() table with wide_slots slots, or NULL.
  * Limits: 0 <= k <= 64, 1 <= m <= 64 (one wavefront holds a window), B >= 0. */
 int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
               const int32_t *edge_tok, const int32_t *edge_dst, const int32_t *lastpos,
@@ -207,7 +221,7 @@ int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
               const int32_t *recent, const int32_t *recent_len,
               int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
               int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
-              void *stream);
+              const int32_t *wide_table, int64_t wide_slots, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * spec_verify_attn (Alg. 4: "Validate with main LLM" - the attention of the pass in which the

@@ -23,7 +23,7 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 _vp = ctypes.c_void_p
 
 EXPORTS = ["agentsam_strerror", "agentsam_set_option", "sam_build", "sam_append", "sam_flat_sizes",
-           "sam_flatten", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
+           "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
            "sam_draft", "sam_draft_delta", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
            "spec_adaptive_k", "agentsched_pick"]
@@ -52,7 +52,9 @@ def lib():
         L.sam_flatten.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_i32p] * 8
         L.sam_free.argtypes = [_vp]
         L.sam_free.restype = None
-        L.sam_draft.argtypes = [_vp] * 12 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp]
+        L.sam_draft.argtypes = [_vp] * 12 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp, ctypes.c_int64, _vp]
+        L.sam_wide_slots.argtypes = [_vp, ctypes.POINTER(ctypes.c_int64)]
+        L.sam_wide_table.argtypes = [_vp, ctypes.c_int32, _i32p, ctypes.c_int64]
         L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 5
         L.spec_adaptive_k.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                       ctypes.POINTER(ctypes.c_int32)]
@@ -182,6 +184,7 @@ class FlatSam:
     corpus_begin: np.ndarray   # [n_automata]
     corpus_end: np.ndarray     # [n_automata] exclusive
     rows_end: np.ndarray = None  # [n_automata] end of the state ids that have a transition row (root + states flattened)
+    wide_table: object = None    # [4*slots] transitions of the very wide states (see sam_wide_table in the header)
 
     def to(self, device):
         import torch
@@ -190,7 +193,7 @@ class FlatSam:
         pad = lambda a: a if a.shape[0] > 0 else np.zeros(1, dtype=np.int32)
         return FlatSam(cv(self.len), cv(self.link), cv(self.row_ptr), cv(pad(self.edge_tok)),
                        cv(pad(self.edge_dst)), cv(self.lastpos), cv(pad(self.corpus)), cv(self.state_rec),
-                       self.roots, self.corpus_begin, self.corpus_end, self.rows_end)
+                       self.roots, self.corpus_begin, self.corpus_end, self.rows_end, cv(self.wide_table))
 
 
 def sam_flatten(sams: Sequence[Sam], grow_tokens: int = 0) -> FlatSam:
@@ -217,6 +220,17 @@ def sam_flatten(sams: Sequence[Sam], grow_tokens: int = 0) -> FlatSam:
         out.roots[i], out.corpus_begin[i], out.corpus_end[i], out.rows_end[i] = sb, cb, cb + c, sb + a
         out.row_ptr[sb + a:sb + scap[i] + 1] = eb + b          # states without a row (not read; kept consistent)
         sb, eb, cb = sb + scap[i], eb + b, cb + ccap[i]
+    need = []
+    for s in sams:
+        v = ctypes.c_int64()
+        _check(lib().sam_wide_slots(s._h, ctypes.byref(v)), "sam_wide_slots")
+        need.append(v.value)
+    slots = 2
+    while slots < sum(need):
+        slots *= 2
+    out.wide_table = np.full(4 * slots, -1, np.int32)
+    for i, s in enumerate(sams):
+        _check(lib().sam_wide_table(s._h, int(out.roots[i]), _npp(out.wide_table), slots), "sam_wide_table")
     return out
 
 
@@ -275,7 +289,8 @@ def _dev_i32(a, device):
     return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(device)
 
 
-def sam_draft(flat: FlatSam, root, corpus_end, recent, recent_len, k: int, sep_token: int, min_match: int = 1):
+def sam_draft(flat: FlatSam, root, corpus_end, recent, recent_len, k: int, sep_token: int, min_match: int = 1,
+              use_wide_table: bool = True):
     """Returns device tensors draft[B,k], n_draft[B], match_len[B], match_end[B]."""
     import torch
     dev = flat.len.device
@@ -290,7 +305,8 @@ def sam_draft(flat: FlatSam, root, corpus_end, recent, recent_len, k: int, sep_t
                          _dp(flat.lastpos), _dp(flat.corpus), _dp(flat.state_rec), _dp(root), _dp(corpus_end), _dp(recent),
                          _dp(recent_len), B, m, k, min_match, sep_token,
                          _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
-                         _stream_ptr())
+                         _dp(flat.wide_table) if use_wide_table else _vp(0),
+                         flat.wide_table.numel() // 4 if use_wide_table else 0, _stream_ptr())
     _check(rc, "sam_draft")
     return draft, n_draft, match_len, match_end
 

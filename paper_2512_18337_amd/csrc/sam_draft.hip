@@ -22,6 +22,27 @@ struct Overlay {
     unsigned mask;                   // capacity - 1 (capacity a power of two, at most half full)
 };
 
+// The table of the transitions of very wide states (16-byte slots {key low, key high, destination, 0}).
+struct WideTable {
+    const int4 *slot;
+    unsigned mask;                   // slots - 1; slot == nullptr: no table, search the sorted rows
+};
+
+__device__ __forceinline__ int wide_find(const WideTable &wt, int s, int c) {
+    const unsigned long long k = ((unsigned long long)(unsigned)s << 32) | (unsigned)c;
+    unsigned j = (unsigned)agentsam_hash64(k) & wt.mask;
+    for (unsigned probes = 0; probes <= wt.mask; ++probes) {
+        const int4 e = wt.slot[j];                           // one 16-byte (scalar) load per probe
+        const unsigned long long kk = ((unsigned long long)(unsigned)e.y << 32) | (unsigned)e.x;
+        if (kk == k) return e.z;
+        if (kk == AGENTSAM_HASH_EMPTY) return -1;
+        j = (j + 1) & wt.mask;
+    }
+    return -1;
+}
+
+__device__ __forceinline__ int link_len(int w) { return w < 0 ? -1 - w : w; }   // record field 3 without the wide flag
+
 __device__ __forceinline__ int overlay_find(const Overlay &ov, int s, int c) {
     const unsigned long long k = ((unsigned long long)(unsigned)s << 32) | (unsigned)c;
     unsigned j = (unsigned)agentsam_hash64(k) & ov.mask;
@@ -68,7 +89,7 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     const int32_t *__restrict__ recent, const int32_t *__restrict__ recent_len,
     int m, int k, int min_match, int sep,
     int32_t *__restrict__ draft, int32_t *__restrict__ n_draft, int32_t *__restrict__ match_len,
-    int32_t *__restrict__ match_end, Overlay ov, const int32_t *__restrict__ rows_end) {
+    int32_t *__restrict__ match_end, Overlay ov, const int32_t *__restrict__ rows_end, WideTable wt) {
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
     const int root = __builtin_amdgcn_readfirstlane(root_arr[b]);
@@ -82,19 +103,35 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     // with a single transition that matches - cost one dependent load.
     // s, l and every branch below are wave-uniform and kept in scalar registers, so the record is
     // fetched with a scalar load and the loop carries no exec-mask bookkeeping.
+    // Every mismatch sends the walk back towards the root, so the root's transition is the lookup
+    // made most often.  When the root is a wide state, all 64 of them (one per window token) are
+    // fetched up front, side by side, one per lane, and the walk takes them from a register.
+    int root_next = -2;                                        // -2: not fetched
+    const bool root_ahead = !OVERLAY && wt.slot != nullptr && __builtin_amdgcn_readfirstlane(state_rec[root].w) < 0;
+    if (root_ahead) root_next = (lane < ql) ? wide_find(wt, root, wtok) : -1;
+
     int s = __builtin_amdgcn_readfirstlane(root), l = 0;
     for (int t = 0; t < ql; ++t) {
         const int c = __builtin_amdgcn_readlane(wtok, t);
         for (;;) {
+            if (root_ahead && s == root) {
+                const int dst = __builtin_amdgcn_readlane(root_next, t);
+                if (dst >= 0) { s = dst; ++l; } else { l = 0; }
+                break;
+            }
             const int4 rec = state_rec[s];
             const int r0 = __builtin_amdgcn_readfirstlane(rec.x), r1 = __builtin_amdgcn_readfirstlane(rec.y);
             int dst = -1;
             if (r0 == c) {
                 dst = r1 >= 0 ? r1 : -2 - r1;
             } else if (!OVERLAY) {
-                if (r1 < -1 && c > r0)                     // rows are sorted: c can only be further right
-                    dst = __builtin_amdgcn_readfirstlane(
-                        find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane));
+                if (r1 < -1 && c > r0) {                   // rows are sorted: c can only be further right
+                    if (wt.slot != nullptr && __builtin_amdgcn_readfirstlane(rec.w) < 0)
+                        dst = __builtin_amdgcn_readfirstlane(wide_find(wt, s, c));
+                    else
+                        dst = __builtin_amdgcn_readfirstlane(
+                            find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane));
+                }
             } else if (r1 < -1) {
                 // Maintained automaton: the record holds any one transition; the overlay overrides the
                 // flattened row (a transition may have been redirected to a clone), and only states
@@ -107,7 +144,7 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
             if (dst >= 0) { s = dst; ++l; break; }
             if (s == root) { l = 0; break; }
             s = __builtin_amdgcn_readfirstlane(rec.z);
-            l = __builtin_amdgcn_readfirstlane(rec.w);
+            l = link_len(__builtin_amdgcn_readfirstlane(rec.w));
         }
     }
 
@@ -119,7 +156,7 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
         if (lp >= 0) { e = lp; break; }
         const int4 rec = state_rec[s];
         s = rec.z;
-        L = rec.w;
+        L = link_len(rec.w);
     }
     if (e < 0 || L < min_match) { e = -1; L = 0; }
 
@@ -149,8 +186,10 @@ extern "C" int sam_draft(const int32_t *len, const int32_t *link, const int32_t 
                          const int32_t *recent, const int32_t *recent_len,
                          int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
                          int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
-                         void *stream) {
+                         const int32_t *wide_table, int64_t wide_slots, void *stream) {
     if (B < 0 || m < 1 || m > 64 || k < 0 || k > 64 || min_match < 0) return AGENTSAM_ERR_ARG;
+    if (wide_table && (wide_slots < 2 || (wide_slots & (wide_slots - 1)) != 0 || wide_slots > (1ll << 31)))
+        return AGENTSAM_ERR_ARG;
     if (B == 0) return AGENTSAM_OK;
     (void)len; (void)link;                                   // carried by state_rec
     if (!row_ptr || !lastpos || !state_rec || !root || !corpus_end || !recent || !recent_len ||
@@ -161,7 +200,8 @@ extern "C" int sam_draft(const int32_t *len, const int32_t *link, const int32_t 
     hipLaunchKernelGGL(sam_draft_kernel<false>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
                        row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, nullptr);
+                       draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, nullptr,
+                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u});
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }
@@ -184,7 +224,7 @@ extern "C" int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, 
     hipLaunchKernelGGL(sam_draft_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
                        row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       draft, n_draft, match_len, match_end, ov, rows_end);
+                       draft, n_draft, match_len, match_end, ov, rows_end, WideTable{nullptr, 0u});
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }

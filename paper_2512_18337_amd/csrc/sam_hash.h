@@ -10,6 +10,7 @@
 #endif
 
 #define AGENTSAM_HASH_EMPTY (~0ull)
+#define AGENTSAM_WIDE_DEGREE 64          /* states with more transitions than this are also in the wide table */
 
 AGENTSAM_HD inline uint64_t agentsam_hash64(uint64_t k) {
     k ^= k >> 33; k *= 0xff51afd7ed558ccdull; k ^= k >> 33; k *= 0xc4ceb9fe1a85ec53ull; k ^= k >> 33;

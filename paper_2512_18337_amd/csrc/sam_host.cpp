@@ -262,6 +262,7 @@ int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t c
             rec[1] = tmp.empty() ? -1 : (tmp.size() == 1 ? tmp[0].second + state_base : -2 - (tmp[0].second + state_base));
             rec[2] = link[v];
             rec[3] = s->link[v] < 0 ? 0 : s->len[s->link[v]];
+            if ((int64_t)tmp.size() > AGENTSAM_WIDE_DEGREE) rec[3] = -1 - rec[3];   // its row is also in the wide table
         }
         row_ptr[ns] = (int32_t)(at + edge_base);
         if (nt > 0) std::memcpy(corpus, s->corpus.data(), (size_t)nt * sizeof(int32_t));
@@ -273,6 +274,61 @@ int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t c
         s->rec_dirty.assign((size_t)ns, 0); s->lp_dirty.assign((size_t)ns, 0);
         s->rec_list.clear(); s->lp_list.clear();
         s->ov_state.clear(); s->ov_tok.clear(); s->ov_dst.clear();
+    } catch (const std::bad_alloc &) {
+        return AGENTSAM_ERR_NOMEM;
+    }
+    return AGENTSAM_OK;
+}
+
+// States with more than AGENTSAM_WIDE_DEGREE transitions (the root, a few very frequent tokens): their
+// sorted rows would take several dependent probes to search, so their transitions are also offered in an
+// open-addressing table of 16-byte slots {key low, key high, destination, 0}, one probe per lookup.
+static int64_t wide_transitions(const sam *s, std::vector<int32_t> *states) {
+    int64_t total = 0;
+    const size_t ns = s->len.size();
+    for (size_t v = 0; v < ns; ++v) {
+        int64_t deg = 0;
+        for (int32_t x = s->head[v]; x != -1 && deg <= AGENTSAM_WIDE_DEGREE; x = s->e_next[(size_t)x]) ++deg;
+        if (deg > AGENTSAM_WIDE_DEGREE) {
+            for (int32_t x = s->head[v]; x != -1; x = s->e_next[(size_t)x]) ++total;
+            if (states) states->push_back((int32_t)v);
+        }
+    }
+    return total;
+}
+
+int sam_wide_slots(const sam_t *s, int64_t *slots) {
+    if (!s || !slots) return AGENTSAM_ERR_NULL;
+    const int64_t n = wide_transitions(s, nullptr);
+    int64_t cap = 2;
+    while (cap < 2 * n) cap *= 2;
+    *slots = cap;
+    return AGENTSAM_OK;
+}
+
+int sam_wide_table(const sam_t *s, int32_t state_base, int32_t *table, int64_t slots) {
+    if (!s || !table) return AGENTSAM_ERR_NULL;
+    if (state_base < 0 || slots < 2 || (slots & (slots - 1)) != 0) return AGENTSAM_ERR_ARG;
+    try {
+        std::vector<int32_t> states;
+        const int64_t n = wide_transitions(s, &states);
+        if (2 * n > slots) return AGENTSAM_ERR_ARG;          // at most half full (together with what is in it)
+        const uint64_t mask = (uint64_t)slots - 1;
+        for (int32_t v : states) {
+            for (int32_t x = s->head[(size_t)v]; x != -1; x = s->e_next[(size_t)x]) {
+                const uint64_t key = ((uint64_t)(uint32_t)(v + state_base) << 32) | (uint32_t)s->e_tok[(size_t)x];
+                uint64_t j = agentsam_hash64(key) & mask;
+                int64_t probes = 0;
+                while (!(table[4 * j] == -1 && table[4 * j + 1] == -1)) {           // key ~0 marks a free slot
+                    j = (j + 1) & mask;
+                    if (++probes > slots) return AGENTSAM_ERR_ARG;                  // table full
+                }
+                table[4 * j] = (int32_t)(uint32_t)key;
+                table[4 * j + 1] = (int32_t)(uint32_t)(key >> 32);
+                table[4 * j + 2] = s->e_dst[(size_t)x] + state_base;
+                table[4 * j + 3] = 0;
+            }
+        }
     } catch (const std::bad_alloc &) {
         return AGENTSAM_ERR_NOMEM;
     }

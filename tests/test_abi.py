@@ -44,9 +44,9 @@ def test_argument_errors_without_a_gpu():
         assert L.agentsam_set_option(b"attn_schedule", 0) == 0
     assert L.agentsam_set_option(b"attn_schedule", 3) == -2
     # entry points reject bad sizes before touching the device
-    assert L.sam_draft(*([None] * 12), 4, 65, 4, 1, 0, *([None] * 5)) == -2
-    assert L.sam_draft(*([None] * 12), 4, 16, 4, 1, 0, *([None] * 5)) == -1
-    assert L.sam_draft(*([None] * 12), 0, 16, 4, 1, 0, *([None] * 5)) == 0
+    assert L.sam_draft(*([None] * 12), 4, 65, 4, 1, 0, *([None] * 5), 0, None) == -2
+    assert L.sam_draft(*([None] * 12), 4, 16, 4, 1, 0, *([None] * 5), 0, None) == -1
+    assert L.sam_draft(*([None] * 12), 0, 16, 4, 1, 0, *([None] * 5), 0, None) == 0
     assert L.spec_accept(None, 0, None, None, 4, 64, 100, None, None, None, None) == -2
     assert L.spec_accept(None, 7, None, None, 4, 4, 100, None, None, None, None) == -3
     assert L.spec_accept(None, 0, None, None, 4, 4, 100, None, None, None, None) == -1

@@ -26,6 +26,10 @@ def _run_draft(cfg, min_match=1, recent_override=None):
     assert np.array_equal(me_rel, ome)
     assert np.array_equal(to_np(nd), ond)
     assert np.array_equal(to_np(d), od)
+    # the same without the table of wide states (their sorted rows are searched instead)
+    d2, nd2, ml2, me2 = A.sam_draft(fd, root, cend, recent, rlen, cfg.k, cfg.sep, min_match, use_wide_table=False)
+    torch.cuda.synchronize()
+    assert torch.equal(d2, d) and torch.equal(nd2, nd) and torch.equal(ml2, ml) and np.array_equal(to_np(me2), me)
     return to_np(d), to_np(nd), to_np(ml)
 
 

@@ -79,7 +79,8 @@ def test_size_bounds_and_substring_count(seed):
             else:
                 assert rec[v, 0] == f.edge_tok[r0]
                 assert rec[v, 1] == (f.edge_dst[r0] if r1 - r0 == 1 else -2 - f.edge_dst[r0])
-            assert rec[v, 2] == f.link[v] and rec[v, 3] == (0 if f.link[v] < 0 else f.len[f.link[v]])
+            ll = 0 if f.link[v] < 0 else f.len[f.link[v]]
+            assert rec[v, 2] == f.link[v] and rec[v, 3] == (ll if r1 - r0 <= 64 else -1 - ll)
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -98,6 +99,39 @@ def test_walk_of_flat_arrays_matches_oracle_small(seed):
             d, nd, ml, me = draft_oracle(T, q, k, sep, mm)
             wd, wl, we = _walk(f, 0, q, k, sep, mm)
             assert (wl, we, wd) == (ml, me, list(d[:nd]))
+
+
+def test_wide_table_holds_exactly_the_transitions_of_wide_states():
+    from test_sam_delta import _hash64, M64
+    rng = np.random.default_rng(11)
+    T = np.concatenate([rng.integers(0, 400, 3000), np.tile([7, 8], 200)]).astype(np.int32)
+    T[::2] = np.where(rng.random(T[::2].shape[0]) < 0.5, 7, T[::2])    # token 7 gets many different successors
+    f = A.sam_flatten([A.sam_build(T, 999), A.sam_build(T[:500], 999)])
+    tab = f.wide_table.reshape(-1, 4)
+    slots = tab.shape[0]
+    assert slots & (slots - 1) == 0
+    found = {}
+    for lo, hi, d, z in tab:
+        if lo == -1 and hi == -1:
+            continue
+        found[(int(np.uint32(hi)), int(np.uint32(lo)))] = int(d)
+    expect = {}
+    ns = f.len.shape[0]
+    rec = f.state_rec.reshape(ns, 4)
+    for v in range(ns):
+        r0, r1 = int(f.row_ptr[v]), int(f.row_ptr[v + 1])
+        assert (rec[v, 3] < 0) == (r1 - r0 > 64)
+        if r1 - r0 > 64:
+            for j in range(r0, r1):
+                expect[(v, int(f.edge_tok[j]))] = int(f.edge_dst[j])
+    assert len(expect) > 300 and found == expect and 2 * len(found) <= slots
+    assert int(f.roots[1]) in {v for v, _ in expect}                  # the second automaton's root, rebased
+    for (v, c), d in list(expect.items())[::17]:                      # reachable by linear probing from the hash
+        j = _hash64(((v << 32) | c) & M64) & (slots - 1)
+        while not (np.uint32(tab[j, 1]) == v and np.uint32(tab[j, 0]) == c):
+            assert not (tab[j, 0] == -1 and tab[j, 1] == -1)
+            j = (j + 1) & (slots - 1)
+        assert tab[j, 2] == d
 
 
 def test_append_equals_build_and_updates_eligibility():
