@@ -259,6 +259,19 @@ def main():
         t_accept = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
         accept_len = res[0].cpu().numpy()
 
+    # the rate this device delivers to a kernel that only streams (4 GiB, 5 launches)
+    probe_buf = torch.ones(1 << 30, dtype=torch.float32, device=dev)
+    probe_sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    A.agentsam_stream_read_probe(probe_buf, probe_sink)
+    pe0, pe1 = ev(), ev()
+    pe0.record()
+    for _ in range(5):
+        A.agentsam_stream_read_probe(probe_buf, probe_sink)
+    pe1.record()
+    torch.cuda.synchronize()
+    stream_gbs = probe_buf.numel() * 4 * 5 / (pe0.elapsed_time(pe1) * 1e-3) / 1e9
+    del probe_buf
+
     kv_elem = 2 if cfg.dtype == "bf16" else 4
     alg_bytes = float(lay.seq_lens.astype(np.int64).sum()) * cfg.Hkv * 2 * cfg.D * kv_elem
     achieved = alg_bytes / (t_attn * 1e-3) / 1e9
@@ -276,7 +289,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "spec_verify_attn", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "algorithmic_bytes": alg_bytes,
-                     "launch_ms": t_attn},
+                     "launch_ms": t_attn, "stream_read_GBs": stream_gbs, "frac_of_stream_read": achieved / stream_gbs},
         "detail": {"t_draft_us": t_draft * 1e3, "t_attn_us": t_attn * 1e3, "t_accept_us": t_accept * 1e3,
                    "sessions_per_s_sam_draft": (cfg.B / (t_draft * 1e-3)) if t_draft else None,
                    "accepted_tokens_per_s": float((accept_len + 1).sum()) / (ms_step * 1e-3),

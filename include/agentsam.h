@@ -46,6 +46,11 @@ extern "C" {
 
 const char *agentsam_strerror(int code);
 
+/* Measurement aid: reads buf[0 .. bytes rounded down to 16 MiB) once with 1024 workgroups of plain
+ * streaming loads and does nothing else (device pointers; sink16 = 16 writable bytes, normally left
+ * untouched).  Timing it gives the streaming-read rate of the device the benchmark runs on. */
+int agentsam_stream_read_probe(const void *buf, size_t bytes, void *sink16, void *stream);
+
 /* Tuning knobs for experiments and for tests of split invariance.
  *   "attn_kv_chunk"  KV positions handled by one workgroup of spec_verify_attn
  *                    (0 = choose automatically; otherwise a multiple of 128, >= 128).

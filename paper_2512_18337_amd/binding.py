@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _vp = ctypes.c_void_p
 
-EXPORTS = ["agentsam_strerror", "agentsam_set_option", "sam_build", "sam_append", "sam_flat_sizes",
+EXPORTS = ["agentsam_strerror", "agentsam_set_option", "agentsam_stream_read_probe", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
            "sam_draft", "sam_draft_delta", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
@@ -46,6 +46,7 @@ def lib():
         L.agentsam_strerror.restype = ctypes.c_char_p
         L.agentsam_strerror.argtypes = [ctypes.c_int]
         L.agentsam_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+        L.agentsam_stream_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
         L.sam_build.argtypes = [_i32p, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(_vp)]
         L.sam_append.argtypes = [_vp, _i32p, ctypes.c_int64]
         L.sam_flat_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 3
@@ -366,6 +367,12 @@ def agentsched_pick(free_blocks: int, hit, need, prompt_tok, wait, *, lambda_max
                                  int(tokens_per_block), ctypes.byref(lam), ptr(score), ctypes.byref(picked)),
            "agentsched_pick")
     return lam.value, score, picked.value
+
+
+def agentsam_stream_read_probe(buf, sink) -> None:
+    """One streaming read of the device tensor buf (measurement aid, see the header)."""
+    _check(lib().agentsam_stream_read_probe(_dp(buf), buf.numel() * buf.element_size(), _dp(sink), _stream_ptr()),
+           "agentsam_stream_read_probe")
 
 
 def _dtype_code(t) -> int:

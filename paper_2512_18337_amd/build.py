@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagentsam.so")
-SOURCES = ["sam_host.cpp", "sam_builder.cpp", "controllers.cpp", "options.cpp", "sam_draft.hip", "spec_accept.hip", "spec_verify_attn.hip"]
+SOURCES = ["sam_host.cpp", "sam_builder.cpp", "controllers.cpp", "options.cpp", "sam_draft.hip", "spec_accept.hip", "spec_verify_attn.hip", "stream_probe.hip"]
 
 
 def build(verbose: bool = False) -> str:
