@@ -134,6 +134,27 @@ def test_bf16_many_short_sessions_balanced(k, Hq, B):
     assert diff < 4e-3, diff
 
 
+def test_bf16_more_sessions_than_threads_balanced():
+    """More sessions than a workgroup has threads: the scan over seq_lens takes several rounds, and most
+    workgroups walk through dozens of whole streams."""
+    cfg = W.scaled(W.baseline_config(1), B=700, Hq=4, Hkv=2, D=64, k=3, kv_mode="ragged", kv_len=(4, 300),
+                   permute_pages=True, page=32)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    outs = {}
+    for schedule in (2, 1):
+        A.agentsam_set_option("attn_schedule", schedule)
+        try:
+            outs[schedule] = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+            torch.cuda.synchronize()
+        finally:
+            A.agentsam_set_option("attn_schedule", 0)
+    rng = np.random.default_rng(5)
+    pairs = [(int(b), int(h)) for b in list(rng.integers(0, cfg.B, 40)) + [0, 255, 256, 257, 511, 512, 699]
+             for h in range(cfg.Hq)]
+    _check(cfg, lay, q, kc, vc, outs[2], pairs)
+    assert float((outs[2] - outs[1]).abs().max()) < 4e-3
+
+
 def test_bf16_minimum_and_boundary_lengths():
     """seq_len == R (every row sees only the new positions), lengths around tile / page / chunk edges."""
     base = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=2, D=128, k=8)
