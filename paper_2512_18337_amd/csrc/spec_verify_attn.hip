@@ -259,7 +259,7 @@ __device__ __forceinline__ void softmax_exp(WaveState<D, MT> &w, const f32x4 (&s
     for (int rt = 0; rt < MT; ++rt) {
         const float mref = w.m_run[rt];
         float psum = w.l_part[rt];
-        bf16x8 pk;
+        u32x4 pw;                                            // the 8 weights, packed two per register
 #pragma unroll
         for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
@@ -269,12 +269,11 @@ __device__ __forceinline__ void softmax_exp(WaveState<D, MT> &w, const f32x4 (&s
                 const float e1 = MASK ? __builtin_amdgcn_exp2f(sacc[pt][rt][r + 1] - mref)
                                       : __builtin_amdgcn_exp2f(fmaf(sacc[pt][rt][r + 1], c, -mref));
                 const bf16x2 pr = {(__bf16)e0, (__bf16)e1};
-                pk[pt * 4 + r] = pr[0];
-                pk[pt * 4 + r + 1] = pr[1];
                 psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+                pw[pt * 2 + r / 2] = __builtin_bit_cast(unsigned, pr);   // the same register feeds the MFMA
             }
         w.l_part[rt] = psum;
-        pf[rt] = pk;
+        pf[rt] = __builtin_bit_cast(bf16x8, pw);
     }
 }
 
