@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--attn-only", action="store_true", help="time only spec_verify_attn (for profiling)")
     ap.add_argument("--kv-chunk", type=int, default=0)
     ap.add_argument("--schedule", type=int, default=0, help="attn_schedule option: 0 auto, 1 chunk grid, 2 balanced")
+    ap.add_argument("--cascade", type=int, default=0, help="attn_cascade option: 0 auto, 1 off, 2 on")
     ap.add_argument("--maintain", type=int, default=0, metavar="STEPS",
                     help="also time STEPS rounds of incremental automaton maintenance (append, delta export, "
                          "device update, sam_draft_delta); reported under detail.sam_maintenance")
@@ -193,6 +194,8 @@ def main():
         A.agentsam_set_option("attn_kv_chunk", args.kv_chunk)
     if args.schedule:
         A.agentsam_set_option("attn_schedule", args.schedule)
+    if args.cascade:
+        A.agentsam_set_option("attn_cascade", args.cascade)
 
     # ---- inputs (all resident in HBM before timing)
     nmem = cfg.B if cfg.sam_mode == "per_session" else 1

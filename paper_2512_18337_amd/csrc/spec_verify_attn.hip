@@ -28,6 +28,7 @@
 namespace agentsam {
 int64_t option_attn_v_mode();
 int64_t option_attn_schedule();
+int64_t option_attn_cascade();
 }
 
 namespace {
@@ -64,6 +65,18 @@ struct AttnParams {
     int balanced;            // 1: balanced partition of the whole batch over the grid, 0: chunk grid
     int32_t *plan;           // balanced only: exclusive prefix sums of the sessions' tile counts, [B+1]
     float *wsr;              // workspace records (after the plan, if any)
+    // shared-prefix ("cascade") run: the pages every session has in common are processed once per GROUP
+    // of gs sessions (phase 1, wide kernel over gs*rows1 packed rows), the rest per session (phase 0)
+    int cascade;             // 1: this launch is part of a cascade run
+    int phase;               // 1: prefix phase of a cascade run
+    int gs, ngroups;         // sessions per group, number of groups
+    int rows1;               // packed rows of ONE session (G*R); == rows except in the prefix phase
+    int pchunk_tiles;        // prefix phase: tiles per workgroup
+    int npchunks_max;        // prefix phase: grid extent over chunks
+    int rows_pad_p;          // rows per prefix record
+    int nslots;              // workgroups of the balanced (suffix) launch
+    const int32_t *lcp;      // [B] pages each session has in common with session 0 (written by attn_lcp_kernel)
+    float *wsp;              // prefix records
 };
 
 // A session of S positions is cut into ceil(S / max_chunk) chunks of EQUAL size (rounded up to 128
@@ -147,10 +160,12 @@ __device__ __forceinline__ void init_state(WaveState<D, MT> &w, const AttnParams
     for (int rt = 0; rt < MT; ++rt) {
         const int pr = row0 + rt * 16 + n;
         const bool live = pr < row_end;
-        const int hh = live ? pr / R : 0;
-        const int i = live ? pr % R : R - 1;
+        const int so = live ? pr / p.rows1 : 0;              // session within the group (0 outside the prefix phase)
+        const int r1 = live ? pr - so * p.rows1 : 0;
+        const int hh = live ? r1 / R : 0;
+        const int i = live ? r1 % R : R - 1;
         w.irow[rt] = i;
-        const __hip_bfloat16 *src = qg + (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D;
+        const __hip_bfloat16 *src = qg + (((int64_t)(b + so) * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D;
 #pragma unroll
         for (int ks = 0; ks < D / 32; ++ks) {
             s16x8 raw = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -350,6 +365,7 @@ struct Segment {
     int b, kvh, S;           // session, kv head, clamped sequence length
     int t0, nt;              // tile range [t0, t0+nt) of the stream
     int64_t rec;             // workspace record for the partial result, -1: whole stream, write the output
+    int rows;                // packed rows that are live in this segment (a short last group has fewer)
 };
 
 __device__ __forceinline__ int session_len(const AttnParams &p, int b) {
@@ -380,6 +396,29 @@ __device__ __forceinline__ int block_scan_excl(int v, int *tmp, int &total) {
     return base + incl - v;
 }
 
+// minimum of v over the 256 threads of the workgroup; `tmp` is 4 ints of LDS
+__device__ __forceinline__ int block_min(int v, int *tmp) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = min(v, __shfl_xor(v, off, 64));
+    if (lane == 0) tmp[wave] = v;
+    __syncthreads();
+    int m = tmp[0];
+#pragma unroll
+    for (int ww = 1; ww < kWaves; ++ww) m = min(m, tmp[ww]);
+    __syncthreads();
+    return m;
+}
+
+// Tiles of the prefix all sessions share (cascade runs): whole pages that every session lists at the
+// same place of its block table and that lie in front of every session's new rows.
+__device__ __forceinline__ int shared_prefix_tiles(const AttnParams &p, int *tmp) {
+    int m = 0x7fffffff;
+    for (int bb = threadIdx.x; bb < p.B; bb += 256) m = min(m, p.lcp[bb]);
+    const int pages = __builtin_amdgcn_readfirstlane(block_min(m, tmp));
+    return pages * (p.P / kTile);
+}
+
 __device__ __forceinline__ int balanced_share(int T, int nslots) {
     const int s = (T + nslots - 1) / nslots;
     return s < kMinShare ? kMinShare : s;
@@ -390,10 +429,27 @@ __device__ __forceinline__ int balanced_share(int T, int nslots) {
 template <class Body>
 __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, Body body) {
     Segment sg;
+    sg.rows = p.rows;
     int nt_b;                    // tiles of the current stream (chunk grid: end of my chunk)
     int remaining;               // tiles of my share still to do
     int64_t chunk_rec = -1;      // chunk grid: the one record
-    if (!p.balanced) {
+    int ptiles = 0;              // cascade: tiles of the shared prefix, which the streams below start after
+    if (p.cascade) ptiles = shared_prefix_tiles(p, tmp);
+    if (p.phase == 1) {
+        // prefix phase: workgroup (chunk, group, kv head); the group's sessions share these tiles, so
+        // their rows are packed side by side and the block table of the group's first session serves all
+        sg.kvh = blockIdx.x % p.Hkv;
+        const int grp = (blockIdx.x / p.Hkv) % p.ngroups;
+        const int chunk = blockIdx.x / (p.Hkv * p.ngroups);
+        sg.t0 = chunk * p.pchunk_tiles;
+        if (sg.t0 >= ptiles) return;
+        sg.b = grp * p.gs;
+        sg.rows = min(p.gs, p.B - sg.b) * p.rows1;
+        sg.S = ptiles * kTile + p.R;                         // every row sees the whole prefix: nothing is masked
+        remaining = min(p.pchunk_tiles, ptiles - sg.t0);
+        nt_b = sg.t0 + remaining;
+        chunk_rec = ((int64_t)grp * p.Hkv + sg.kvh) * p.npchunks_max + chunk;
+    } else if (!p.balanced) {
         sg.kvh = blockIdx.x % p.Hkv;
         sg.b = (blockIdx.x / p.Hkv) % p.B;
         sg.S = session_len(p, sg.b);
@@ -413,7 +469,7 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
         for (int base = 0; base < p.B; base += 256) {
             const int bb = base + tid;
             int tot;
-            block_scan_excl(bb < p.B ? tiles_of(session_len(p, bb)) : 0, tmp, tot);
+            block_scan_excl(bb < p.B ? max(0, tiles_of(session_len(p, bb)) - ptiles) : 0, tmp, tot);
             sessions_tiles += tot;
         }
         const int T = __builtin_amdgcn_readfirstlane(sessions_tiles) * p.Hkv;   // uniform: scalar registers
@@ -425,7 +481,7 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
         if (tid == 0) tmp[4] = -1;                           // ordered before the writes below by the scan's barriers
         for (int base = 0; base < p.B; base += 256) {
             const int bb = base + tid;
-            const int nt = bb < p.B ? tiles_of(session_len(p, bb)) : 0;
+            const int nt = bb < p.B ? max(0, tiles_of(session_len(p, bb)) - ptiles) : 0;
             int tot;
             const int excl = carry + block_scan_excl(nt, tmp, tot);
             if (blockIdx.x == 0 && bb < p.B) p.plan[bb] = excl;
@@ -439,7 +495,7 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
         if (sg.b < 0 || sg.b >= p.B) return;                 // cannot happen: some stream contains tile `lo`
         const int excl0 = __builtin_amdgcn_readfirstlane(tmp[5]);
         sg.S = __builtin_amdgcn_readfirstlane(session_len(p, sg.b));
-        nt_b = tiles_of(sg.S);
+        nt_b = max(0, tiles_of(sg.S) - ptiles);
         const int r = lo - excl0 * p.Hkv;
         sg.kvh = r / nt_b;
         sg.t0 = r % nt_b;
@@ -449,8 +505,16 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
     while (remaining > 0) {                                  // (one round on the chunk grid)
         sg.nt = min(remaining, nt_b - sg.t0);
         const bool whole = sg.t0 == 0 && sg.nt == nt_b;
-        sg.rec = !p.balanced ? chunk_rec : whole ? -1 : 2 * (int64_t)blockIdx.x + (first ? 0 : 1);
-        body(sg);
+        if (p.phase == 1 || !p.balanced) sg.rec = chunk_rec;
+        else if (!whole) sg.rec = 2 * (int64_t)blockIdx.x + (first ? 0 : 1);
+        else sg.rec = ptiles > 0 ? 2 * (int64_t)p.nslots + (int64_t)sg.b * p.Hkv + sg.kvh : -1;   // (the prefix part is pending)
+        if (p.phase == 0 && ptiles > 0) {                    // the stream's tiles come after the shared prefix
+            Segment abs = sg;
+            abs.t0 += ptiles;
+            body(abs);
+        } else {
+            body(sg);
+        }
         remaining -= sg.nt;
         first = false;
         sg.t0 = 0;
@@ -460,7 +524,7 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
                 ++sg.b;
                 if (sg.b >= p.B) return;                     // cannot happen while seq_lens is unchanged
                 sg.S = __builtin_amdgcn_readfirstlane(session_len(p, sg.b));
-                nt_b = tiles_of(sg.S);
+                nt_b = max(0, tiles_of(sg.S) - ptiles);
             } while (nt_b == 0);
         }
     }
@@ -814,7 +878,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     // at the end.
     const int rpw = XT ? 16 * MT : (p.rows + kWaves - 1) / kWaves;
     const int row0 = wave * rpw;
-    const int row_end = min(p.rows, row0 + rpw);
     constexpr int kXRow0 = kWaves * 16 * MT;                 // first extra row (XT only)
 
     // ---- per-lane constants of the tile loop (computed once; the loop only adds uniform bases)
@@ -837,10 +900,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     for_each_segment(p, sched_tmp, [&](const Segment &sg) __attribute__((always_inline)) {
     const int b = sg.b, kvh = sg.kvh, S = sg.S;
     const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
+    const int row_end = min(sg.rows, row0 + rpw);            // (a short last group of the prefix phase has fewer rows)
     WaveState<D, MT> w;
     init_state<D, MT>(w, p, b, kvh, row0, row_end, n, g);
     WaveState<D, 1> wx;
-    if (XT) init_state<D, 1>(wx, p, b, kvh, kXRow0, p.rows, n, g);
+    if (XT) init_state<D, 1>(wx, p, b, kvh, kXRow0, sg.rows, n, g);
 
     // attempt: 0 optimistic (fixed references), 1 exact row maxima only, 2 final pass with those
     for (int attempt = 0;; ++attempt) {
@@ -1049,9 +1113,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     const bool final_out = sg.rec < 0;
     float *wo = nullptr, *wm = nullptr, *wl = nullptr;
     if (!final_out) {
-        wo = p.wsr + sg.rec * ws_record_floats(p.rows_pad, D);
-        wm = wo + (int64_t)p.rows_pad * D;
-        wl = wm + p.rows_pad;
+        const int rpad = p.phase == 1 ? p.rows_pad_p : p.rows_pad;
+        wo = (p.phase == 1 ? p.wsp : p.wsr) + sg.rec * ws_record_floats(rpad, D);
+        wm = wo + (int64_t)rpad * D;
+        wl = wm + rpad;
     }
 #pragma unroll
     for (int rt = 0; rt < MT; ++rt) {
@@ -1115,7 +1180,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         // every wavefront computed the same M and L; wavefront 0 publishes them over its own entries
         if (wave == 0 && g_e == 0) { xm[n_e] = M; xl[n_e] = L; }
         __syncthreads();
-        const int rows_x = p.rows - kXRow0;
+        const int rows_x = max(0, sg.rows - kXRow0);
         for (int idx = tid_e; idx < rows_x * (D / 4); idx += 256) {
             const int row = idx / (D / 4), c4 = idx % (D / 4);
             const int pr = kXRow0 + row;
@@ -1199,6 +1264,89 @@ __global__ __launch_bounds__(256) void attn_merge_balanced_kernel(const AttnPara
             const float w = exp2f(rec[(int64_t)p.rows_pad * D + pr] - M);
             L += w * rec[(int64_t)p.rows_pad * D + p.rows_pad + pr];
             const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
+            acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
+        }
+        const float inv = 1.0f / L;
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+        const int hh = pr / p.R, i = pr % p.R;
+        const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
+        store_out(p.out, o, acc, p.out_bf16);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Shared-prefix ("cascade") runs.
+//
+// attn_lcp_kernel: lcp[b] = number of leading pages session b lists exactly as session 0 does, cut to
+// the pages that lie wholly in front of the session's R new rows (so no row of any session is masked
+// inside the shared prefix).  The minimum over the batch is the prefix every session shares.
+// attn_merge_cascade_kernel: per (session, kv head), the log-sum-exp merge of the prefix records of the
+// session's group (its rows are a slice of the group's packed rows) with the records of its own part.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_lcp_kernel(const AttnParams p, int32_t *lcp) {
+    __shared__ int tmp[4];
+    const int b = blockIdx.x;
+    const int usable_b = max(0, session_len(p, b) - p.R) / p.P;
+    const int usable_0 = max(0, session_len(p, 0) - p.R) / p.P;
+    const int n = min(usable_b, usable_0);
+    const int32_t *rb = p.bt + (int64_t)b * p.max_pages, *r0 = p.bt;
+    int first_bad = n;
+    for (int j = threadIdx.x; j < n; j += 256) {
+        const int pg = rb[j];
+        if (pg != r0[j] || pg < 0 || (int64_t)pg >= p.num_pages) { first_bad = j; break; }   // j only grows
+    }
+    const int m = block_min(first_bad, tmp);
+    if (threadIdx.x == 0) lcp[b] = m;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_cascade_kernel(const AttnParams p) {
+    __shared__ int tmp[4];
+    const int kvh = blockIdx.x, b = blockIdx.y;
+    const int ptiles = shared_prefix_tiles(p, tmp);
+    const int nt_b = max(0, tiles_of(session_len(p, b)) - ptiles);
+    if (nt_b == 0) return;                                   // (cannot happen for a valid session: its new rows follow the prefix)
+    const int T = p.plan[p.B] * p.Hkv;
+    const int share = balanced_share(T, p.nslots);
+    const int g0 = p.plan[b] * p.Hkv + kvh * nt_b, g1 = g0 + nt_b;
+    const int i0 = g0 / share, i1 = (g1 - 1) / share;
+    if (ptiles == 0 && i0 == i1) return;                     // no prefix part, one workgroup had the stream: output written
+    const int64_t recf = ws_record_floats(p.rows_pad, D);
+    const int64_t recfp = ws_record_floats(p.rows_pad_p, D);
+    const int first_slot = (i0 * share < g0) ? 1 : 0;
+    // the session's own part: one record if a single workgroup had it (slot after the per-workgroup ones), else
+    // one per workgroup
+    const int n_own = (i0 == i1) ? 1 : i1 - i0 + 1;
+    auto own = [&](int j) {
+        if (i0 == i1) return p.wsr + (2 * (int64_t)p.nslots + (int64_t)b * p.Hkv + kvh) * recf;
+        const int i = i0 + j;
+        return p.wsr + (2 * (int64_t)i + (i == i0 ? first_slot : 0)) * recf;
+    };
+    // the prefix part: the chunks of the session's group, rows [so*rows1, (so+1)*rows1) of each record
+    const int grp = b / p.gs, so = b % p.gs;
+    const int n_pre = (ptiles + p.pchunk_tiles - 1) / p.pchunk_tiles;
+    auto pre = [&](int c) { return p.wsp + (((int64_t)grp * p.Hkv + kvh) * p.npchunks_max + c) * recfp; };
+    const int rows1 = p.rows1;
+    for (int idx = threadIdx.x; idx < rows1 * (D / 4); idx += 256) {
+        const int pr = idx / (D / 4), c4 = idx % (D / 4);
+        const int prp = so * rows1 + pr;
+        float M = kNegBig;
+        for (int j = 0; j < n_own; ++j) M = fmaxf(M, own(j)[(int64_t)p.rows_pad * D + pr]);
+        for (int c = 0; c < n_pre; ++c) M = fmaxf(M, pre(c)[(int64_t)p.rows_pad_p * D + prp]);
+        float L = 0.f;
+        float4 acc{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < n_own; ++j) {
+            const float *rec = own(j);
+            const float w = exp2f(rec[(int64_t)p.rows_pad * D + pr] - M);
+            L += w * rec[(int64_t)p.rows_pad * D + p.rows_pad + pr];
+            const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
+            acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
+        }
+        for (int c = 0; c < n_pre; ++c) {
+            const float *rec = pre(c);
+            const float w = exp2f(rec[(int64_t)p.rows_pad_p * D + prp] - M);
+            L += w * rec[(int64_t)p.rows_pad_p * D + p.rows_pad_p + prp];
+            const float4 o = *(const float4 *)(rec + (int64_t)prp * D + c4 * 4);
             acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
         }
         const float inv = 1.0f / L;
@@ -1319,6 +1467,10 @@ struct Plan {
     int nslots;
     size_t plan_bytes;       // balanced: the prefix sums in front of the records
     size_t ws_bytes;
+    // shared-prefix run
+    bool cascade;
+    int gs, ngroups, rows_group, rows_pad_p, pchunk_tiles, npchunks_max;
+    size_t lcp_bytes, own_bytes; // workspace: [lcp][plan][own records][prefix records]
 };
 
 // Workgroups an MI355X keeps resident at once: 256 compute units x 2 (wide kernel, 64 KB of LDS and
@@ -1335,6 +1487,7 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
     const int G = Hq / Hkv;
     const int64_t opt = agentsam::option_attn_kv_chunk();
     pl->wide = false;
+    pl->cascade = false;
     pl->balanced = false;
     pl->nslots = 0;
     pl->plan_bytes = 0;
@@ -1381,7 +1534,39 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
     }
     pl->nchunks_max = (int)((smax + pl->chunk - 1) / pl->chunk);
     const size_t rec_bytes = (size_t)pl->rows_pad * (D + 2) * sizeof(float);
-    if (pl->balanced) {
+    if (dtype == AGENTSAM_BF16) {
+        // Shared-prefix run: groups of gs sessions (as many as fit the wide kernel's 192 packed rows) take
+        // the common prefix together.  Looked for by default only when the detection (two small launches,
+        // about 10 us) is below half a percent of the time the K/V stream itself takes.
+        const int rows1 = G * R;
+        const int gs = std::min<int>(B, (kWaves * kRowsPerGroup) / rows1);
+        const int64_t casc = agentsam::option_attn_cascade();
+        const double kv_bytes = (double)smax * B * Hkv * 2.0 * D * 2.0;
+        const int64_t tiles_max = (int64_t)B * Hkv * ((smax + kTile - 1) / kTile);
+        if (gs >= 2 && gs * rows1 > kRowsPerGroup && tiles_max <= 0x7fffffffll && agentsam::option_attn_kv_chunk() == 0 &&
+            agentsam::option_attn_schedule() != 1 && (casc == 2 || (casc == 0 && kv_bytes >= 11.0e9))) {
+            pl->cascade = true;
+            pl->balanced = true;                             // the sessions' own parts: balanced shares
+            pl->gs = gs;
+            pl->ngroups = (B + gs - 1) / gs;
+            pl->rows_group = gs * rows1;
+            pl->rows_pad_p = (pl->rows_group + 3) & ~3;
+            const int64_t max_tiles = (smax + kTile - 1) / kTile;
+            int64_t pc = (max_tiles * pl->ngroups * Hkv + 1023) / 1024;      // about 1024 prefix workgroups
+            if (pc < 64) pc = 64;
+            if (pc > kMaxChunk / kTile) pc = kMaxChunk / kTile;
+            pl->pchunk_tiles = (int)pc;
+            pl->npchunks_max = (int)((max_tiles + pc - 1) / pc);
+            if ((int64_t)pl->npchunks_max * pl->ngroups * Hkv > 0x7fffffffll) pl->cascade = false;
+        }
+    }
+    if (pl->cascade) {
+        pl->lcp_bytes = ((size_t)B * sizeof(int32_t) + 255) & ~(size_t)255;
+        pl->plan_bytes = (((size_t)B + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+        pl->own_bytes = (2 * (size_t)pl->nslots + (size_t)B * Hkv) * rec_bytes;
+        pl->ws_bytes = pl->lcp_bytes + pl->plan_bytes + pl->own_bytes +
+                       (size_t)pl->ngroups * Hkv * pl->npchunks_max * (size_t)pl->rows_pad_p * (D + 2) * sizeof(float);
+    } else if (pl->balanced) {
         pl->plan_bytes = (((size_t)B + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
         pl->ws_bytes = pl->plan_bytes + 2 * (size_t)pl->nslots * rec_bytes;
     } else {
@@ -1461,7 +1646,43 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     p.balanced = pl.balanced ? 1 : 0;
     p.plan = (int32_t *)workspace;
     p.wsr = (float *)((char *)workspace + pl.plan_bytes);
+    p.cascade = 0; p.phase = 0; p.gs = 1; p.ngroups = B; p.rows1 = p.rows; p.pchunk_tiles = 1; p.npchunks_max = 0;
+    p.rows_pad_p = pl.rows_pad; p.nslots = pl.nslots; p.lcp = nullptr; p.wsp = nullptr;
     hipStream_t st = (hipStream_t)stream;
+
+    if (pl.cascade) {
+        // [lcp][plan][own records][prefix records]
+        char *wsb = (char *)workspace;
+        int32_t *lcp = (int32_t *)wsb;
+        p.cascade = 1;
+        p.lcp = lcp;
+        p.plan = (int32_t *)(wsb + pl.lcp_bytes);
+        p.wsr = (float *)(wsb + pl.lcp_bytes + pl.plan_bytes);
+        p.wsp = (float *)(wsb + pl.lcp_bytes + pl.plan_bytes + pl.own_bytes);
+        p.gs = pl.gs; p.ngroups = pl.ngroups; p.pchunk_tiles = pl.pchunk_tiles; p.npchunks_max = pl.npchunks_max;
+        p.rows_pad_p = pl.rows_pad_p;
+        hipLaunchKernelGGL(attn_lcp_kernel, dim3((unsigned)B), dim3(256), 0, st, p, lcp);
+        AGENTSAM_LAUNCH_CHECK();
+        const bool tr = agentsam::option_attn_v_mode() == 1;
+        // prefix phase: the wide kernel over the packed rows of a whole group
+        AttnParams pp = p;
+        pp.phase = 1;
+        pp.rows = pl.rows_group;                             // rows1 stays the rows of one session
+        pp.balanced = 0;
+        dim3 pgrid((unsigned)((int64_t)pl.npchunks_max * pl.ngroups * Hkv));
+        if (D == 64) launch_bf16<64, 1>(pp, true, pgrid, st); else launch_bf16<128, 1>(pp, true, pgrid, st);
+        AGENTSAM_LAUNCH_CHECK();
+        // the sessions' own parts, balanced
+        dim3 sgrid((unsigned)pl.nslots);
+        if (D == 64) { if (tr) launch_bf16<64, 1>(p, pl.wide, sgrid, st); else launch_bf16<64, 0>(p, pl.wide, sgrid, st); }
+        else { if (tr) launch_bf16<128, 1>(p, pl.wide, sgrid, st); else launch_bf16<128, 0>(p, pl.wide, sgrid, st); }
+        AGENTSAM_LAUNCH_CHECK();
+        dim3 mg((unsigned)Hkv, (unsigned)B);
+        if (D == 64) hipLaunchKernelGGL(attn_merge_cascade_kernel<64>, mg, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL(attn_merge_cascade_kernel<128>, mg, dim3(256), 0, st, p);
+        AGENTSAM_LAUNCH_CHECK();
+        return AGENTSAM_OK;
+    }
 
     if (dtype == AGENTSAM_F32) {
         dim3 grid((unsigned)pl.nchunks_max, (unsigned)Hq, (unsigned)B);

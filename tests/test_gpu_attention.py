@@ -155,6 +155,63 @@ def test_bf16_more_sessions_than_threads_balanced():
     assert float((outs[2] - outs[1]).abs().max()) < 4e-3
 
 
+CASCADE = [
+    # B, Hq, Hkv, k, kv_mode, kv_len, prefix_len: groups of 4 / 5 / 2 sessions, a short last group, no sharing at all
+    dict(B=6, Hq=10, Hkv=2, k=8, kv_mode="shared_prefix", kv_len=(40, 700), prefix_len=2048),     # 45 rows, groups 4 + 2
+    dict(B=11, Hq=8, Hkv=2, k=8, kv_mode="shared_prefix", kv_len=(9, 300), prefix_len=1024),      # 36 rows, groups 5 + 5 + 1
+    dict(B=5, Hq=16, Hkv=4, k=16, kv_mode="shared_prefix", kv_len=(17, 900), prefix_len=1536),    # 68 rows, groups of 2, wide own parts
+    dict(B=7, Hq=8, Hkv=2, k=8, kv_mode="ragged", kv_len=(9, 2000), permute_pages=True),          # nothing shared
+    dict(B=4, Hq=8, Hkv=2, k=8, kv_mode="shared_prefix", kv_len=(9, 60), prefix_len=64),          # one shared page
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASCADE)))
+def test_bf16_shared_prefix_cascade(case):
+    """The shared-prefix run: the common pages are processed once per group of sessions, each session's
+    own part separately, and the two are merged.  Checked against the oracle on every output."""
+    cfg = W.scaled(W.baseline_config(1), D=128, **CASCADE[case])
+    print(f"attn cascade case {case}: {CASCADE[case]}", flush=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    A.agentsam_set_option("attn_cascade", 2)
+    try:
+        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+        torch.cuda.synchronize()
+    finally:
+        A.agentsam_set_option("attn_cascade", 0)
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
+def test_bf16_cascade_partial_sharing_and_short_session():
+    """Sharing that stops early for one session (its third page differs), and a session shorter than the
+    others' common prefix: the shared prefix is the minimum over the batch and the result is unchanged."""
+    cfg = W.scaled(W.baseline_config(1), B=5, Hq=10, Hkv=2, D=128, k=8, kv_mode="shared_prefix", kv_len=(100, 600),
+                   prefix_len=1024)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    scale = 1.0 / np.sqrt(cfg.D)
+    ref = A.spec_verify_attn(q, kc, vc, bt, seq, scale)                   # plain run
+    for variant in ("third page differs", "short session"):
+        bt2, seq2, kc2, vc2 = bt.clone(), seq.clone(), kc, vc
+        if variant == "third page differs":
+            # session 3 gets a private copy of its third page: same contents, another page id
+            kc2 = torch.cat([kc, kc[bt[3, 2]][None]]); vc2 = torch.cat([vc, vc[bt[3, 2]][None]])
+            bt2[3, 2] = kc.shape[0]
+        else:
+            seq2[1] = 200                                                  # ends inside the others' prefix
+        A.agentsam_set_option("attn_cascade", 2)
+        try:
+            out = A.spec_verify_attn(q, kc2, vc2, bt2, seq2, scale)
+            torch.cuda.synchronize()
+        finally:
+            A.agentsam_set_option("attn_cascade", 0)
+        plain = A.spec_verify_attn(q, kc2, vc2, bt2, seq2, scale)
+        torch.cuda.synchronize()
+        diff = float((out - plain).abs().max())
+        print(f"  {variant}: cascade vs plain {diff:.2e}", flush=True)
+        assert diff < 4e-3                                   # (the split decides what each weight is rounded against)
+        if variant == "third page differs":
+            assert float((out - ref).abs().max()) < 4e-3
+
+
 def test_bf16_minimum_and_boundary_lengths():
     """seq_len == R (every row sees only the new positions), lengths around tile / page / chunk edges."""
     base = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=2, D=128, k=8)
