@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_BYTES = {
     "cfg2-b64-32k": 8.605e9,         # profiles/spec_verify_attn_cfg2_hbm_traffic.txt
     "cfg3-ragged-b128": 18.32e9,     # profiles/spec_verify_attn_cfg3_kernel_trace_and_traffic.txt
-    "cfg4-shared-prefix": 4.81e9,    # profiles/spec_verify_attn_cfg4_kernel_trace_and_traffic.txt (logical bytes: 14.19e9)
+    "cfg4-shared-prefix": 2.25e9,    # profiles/spec_verify_attn_cfg4_kernel_trace_and_traffic.txt (logical bytes: 14.19e9)
     "cfg1-b16-8k": 0.551e9,          # profiles/spec_verify_attn_cfg1_kernel_trace_and_traffic.txt
 }
 
@@ -277,6 +277,10 @@ def main():
 
     kv_elem = 2 if cfg.dtype == "bf16" else 4
     alg_bytes = float(lay.seq_lens.astype(np.int64).sum()) * cfg.Hkv * 2 * cfg.D * kv_elem
+    # distinct pages only (smaller than alg_bytes when sessions share pages), and the matrix work
+    used_pages = np.unique(lay.block_table[lay.block_table >= 0]).size
+    unique_bytes = float(used_pages) * cfg.page * cfg.Hkv * 2 * cfg.D * kv_elem
+    attn_flops = 4.0 * cfg.D * cfg.G * cfg.R * float(lay.seq_lens.astype(np.int64).sum()) * cfg.Hkv
     achieved = alg_bytes / (t_attn * 1e-3) / 1e9
     result = {
         "metric": "verified tokens/s/GPU (B=64, 32k ctx, k=8); verify-attn HBM GB/s % of peak",
@@ -292,7 +296,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "spec_verify_attn", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "algorithmic_bytes": alg_bytes,
-                     "launch_ms": t_attn, "stream_read_GBs": stream_gbs, "frac_of_stream_read": achieved / stream_gbs},
+                     "launch_ms": t_attn, "stream_read_GBs": stream_gbs, "frac_of_stream_read": achieved / stream_gbs,
+                     "unique_bytes": unique_bytes, "unique_GBs": unique_bytes / (t_attn * 1e-3) / 1e9,
+                     "mfma_TFLOPs": attn_flops / (t_attn * 1e-3) / 1e12, "mfma_frac_of_2500": attn_flops / (t_attn * 1e-3) / 2.5e15},
         "detail": {"t_draft_us": t_draft * 1e3, "t_attn_us": t_attn * 1e3, "t_accept_us": t_accept * 1e3,
                    "sessions_per_s_sam_draft": (cfg.B / (t_draft * 1e-3)) if t_draft else None,
                    "accepted_tokens_per_s": float((accept_len + 1).sum()) / (ms_step * 1e-3),
