@@ -58,6 +58,10 @@ int agentsam_stream_read_probe(const void *buf, size_t bytes, void *sink16, void
  *                    (session, kv head) stream cut into chunks, one workgroup per chunk;
  *                    2 = all streams laid end to end and cut into one equal share per resident
  *                    workgroup; 0 = choose (2 for large batches unless a chunk size is set).
+ *   "attn_cascade"   shared-prefix run of spec_verify_attn (bf16): 2 = look for pages that all sessions
+ *                    list at the same place of their block tables and process them once per group of
+ *                    sessions instead of once per session; 1 = never; 0 = look when the K/V stream
+ *                    is large enough (>= 11 GB) for the detection to cost nothing.  Same results.
  *   "attn_v_mode"    0/1: how the bf16 kernels transpose V out of LDS (same results).
  * Returns AGENTSAM_ERR_ARG for an unknown key or a bad value. */
 int agentsam_set_option(const char *key, int64_t value);
@@ -242,6 +246,8 @@ int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
  * Device output : out[B,R,Hq,D] in out_dtype.
  * workspace     : device scratch of at least spec_verify_attn_workspace() bytes (partial
  *                 results of the KV splits); contents need no initialisation.
+ * Sessions may list the same pages (a shared prefix): results are those of the definition above
+ * whatever is shared; see "attn_cascade" for how sharing is used.
  * A page id outside [0,num_pages) is treated as a page of zeros (never dereferenced).
  * Supported: D in {64,128}; Hq % Hkv == 0; bf16 needs page_size % 32 == 0; scale > 0;
  * (Hq/Hkv)*R <= 192 for bf16, R <= 32 for f32. */
