@@ -1330,25 +1330,22 @@ __global__ __launch_bounds__(256) void attn_merge_cascade_kernel(const AttnParam
     for (int idx = threadIdx.x; idx < rows1 * (D / 4); idx += 256) {
         const int pr = idx / (D / 4), c4 = idx % (D / 4);
         const int prp = so * rows1 + pr;
-        float M = kNegBig;
-        for (int j = 0; j < n_own; ++j) M = fmaxf(M, own(j)[(int64_t)p.rows_pad * D + pr]);
-        for (int c = 0; c < n_pre; ++c) M = fmaxf(M, pre(c)[(int64_t)p.rows_pad_p * D + prp]);
-        float L = 0.f;
+        // one pass over the records with a running maximum (every record is read once)
+        float M = kNegBig, L = 0.f;
         float4 acc{0.f, 0.f, 0.f, 0.f};
-        for (int j = 0; j < n_own; ++j) {
-            const float *rec = own(j);
-            const float w = exp2f(rec[(int64_t)p.rows_pad * D + pr] - M);
-            L += w * rec[(int64_t)p.rows_pad * D + p.rows_pad + pr];
-            const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
-            acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
-        }
-        for (int c = 0; c < n_pre; ++c) {
-            const float *rec = pre(c);
-            const float w = exp2f(rec[(int64_t)p.rows_pad_p * D + prp] - M);
-            L += w * rec[(int64_t)p.rows_pad_p * D + p.rows_pad_p + prp];
-            const float4 o = *(const float4 *)(rec + (int64_t)prp * D + c4 * 4);
-            acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
-        }
+        auto add = [&](const float *rec, int rpad, int row) {
+            const float m = rec[(int64_t)rpad * D + row];
+            const float l = rec[(int64_t)rpad * D + rpad + row];
+            const float4 o = *(const float4 *)(rec + (int64_t)row * D + c4 * 4);
+            const float Mn = fmaxf(M, m);
+            const float sa = exp2f(M - Mn), sb = exp2f(m - Mn);
+            M = Mn;
+            L = L * sa + l * sb;
+            acc.x = acc.x * sa + o.x * sb; acc.y = acc.y * sa + o.y * sb;
+            acc.z = acc.z * sa + o.z * sb; acc.w = acc.w * sa + o.w * sb;
+        };
+        for (int j = 0; j < n_own; ++j) add(own(j), p.rows_pad, pr);
+        for (int c = 0; c < n_pre; ++c) add(pre(c), p.rows_pad_p, prp);
         const float inv = 1.0f / L;
         acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
         const int hh = pr / p.R, i = pr % p.R;
