@@ -233,6 +233,27 @@ int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
               const int32_t *wide_table, int64_t wide_slots, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * sam_draft_merged (Alg. 4: S_merged = MergeSAM(S_session, S_cross, weights); Sec. 5.4.2: the
+ * session's own context and the top-K retrieved contexts, "the similarity scores determine the
+ * weights of each SAM during the merge").
+ *
+ * Every session queries M automata with the same window: root[B,M], corpus_end[B,M], weight[B,M]
+ * (all automata live in the one set of flattened arrays).  The automata are not physically merged;
+ * the paper gives no merge rule, so this library's reading is: each automaton proposes as in
+ * sam_draft, and the proposal with the largest weight * match_len is taken (among automata with
+ * weight > 0 that propose at least one token; on equal scores the longer match, then the lower
+ * index).  source[b] = index of the automaton taken, -1 when none proposes (then n_draft = 0).
+ * workspace: device scratch of B*M*(k+3) int32.  Other arguments, outputs and limits as sam_draft. */
+int sam_draft_merged(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
+                     const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,
+                     const int32_t *root, const int32_t *corpus_end, const float *weight, int32_t M,
+                     const int32_t *recent, const int32_t *recent_len,
+                     int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
+                     int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+                     int32_t *source, void *workspace, size_t workspace_bytes,
+                     const int32_t *wide_table, int64_t wide_slots, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * spec_verify_attn (Alg. 4: "Validate with main LLM" - the attention of the pass in which the
  * target model scores the base token and the k drafts of every session at once).
  *

@@ -43,3 +43,24 @@ def draft_oracle_batch(T, mem_begin, mem_end, recent, recent_len, k: int, sep: i
                            _p(draft, ctypes.c_int32), _p(nd, ctypes.c_int32), _p(ml, ctypes.c_int32),
                            _p(mend, ctypes.c_int64))
     return draft[:, :k], nd, ml, mend
+
+
+def merged_draft_oracle(memories, weights, q, k, sep, min_match=1):
+    """Several memories queried with one window (Alg. 4: MergeSAM with weights).  The paper prints no merge
+    rule; the reading checked here: every memory proposes as draft_oracle does, and the proposal with the
+    largest weight * match_len is taken among memories with a positive weight that propose at least one
+    token (equal scores: the longer match, then the earlier memory).  Scores are compared in float32, the
+    precision the weights are given in.  Returns (draft, n_draft, match_len, match_end, source)."""
+    import numpy as np
+    best = None
+    for j, (T, w) in enumerate(zip(memories, weights)):
+        d, nd, ml, me = draft_oracle(np.asarray(T, np.int32), np.asarray(q, np.int32), k, sep, min_match)
+        w = np.float32(w)
+        if nd <= 0 or not (w > 0):
+            continue
+        score = np.float32(w * np.float32(ml))
+        if best is None or score > best[0] or (score == best[0] and ml > best[3]):
+            best = (score, d, nd, ml, me, j)
+    if best is None:
+        return np.full(k, -1, np.int32), 0, 0, -1, -1
+    return best[1], best[2], best[3], best[4], best[5]

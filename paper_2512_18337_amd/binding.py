@@ -25,7 +25,7 @@ _vp = ctypes.c_void_p
 EXPORTS = ["agentsam_strerror", "agentsam_set_option", "agentsam_stream_read_probe", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
-           "sam_draft", "sam_draft_delta", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
+           "sam_draft", "sam_draft_delta", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
            "spec_adaptive_k", "agentsched_pick"]
 
 
@@ -54,6 +54,8 @@ def lib():
         L.sam_free.argtypes = [_vp]
         L.sam_free.restype = None
         L.sam_draft.argtypes = [_vp] * 12 + [ctypes.c_int32] * 5 + [_vp] * 4 + [_vp, ctypes.c_int64, _vp]
+        L.sam_draft_merged.argtypes = ([_vp] * 9 + [ctypes.c_int32] + [_vp] * 2 + [ctypes.c_int32] * 5 + [_vp] * 5 +
+                                       [_vp, ctypes.c_size_t, _vp, ctypes.c_int64, _vp])
         L.sam_wide_slots.argtypes = [_vp, ctypes.POINTER(ctypes.c_int64)]
         L.sam_wide_table.argtypes = [_vp, ctypes.c_int32, _i32p, ctypes.c_int64]
         L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 5
@@ -310,6 +312,30 @@ def sam_draft(flat: FlatSam, root, corpus_end, recent, recent_len, k: int, sep_t
                          flat.wide_table.numel() // 4 if use_wide_table else 0, _stream_ptr())
     _check(rc, "sam_draft")
     return draft, n_draft, match_len, match_end
+
+
+def sam_draft_merged(flat: FlatSam, root, corpus_end, weight, recent, recent_len, k: int, sep_token: int,
+                     min_match: int = 1):
+    """root, corpus_end, weight: [B, M].  Returns draft[B,k], n_draft[B], match_len[B], match_end[B], source[B]."""
+    import torch
+    dev = flat.state_rec.device
+    root, corpus_end = _dev_i32(root, dev), _dev_i32(corpus_end, dev)
+    recent, recent_len = _dev_i32(recent, dev), _dev_i32(recent_len, dev)
+    weight = torch.as_tensor(np.ascontiguousarray(weight, dtype=np.float32)).to(dev)
+    B, m = recent.shape
+    M = root.shape[1]
+    assert root.shape == (B, M) and corpus_end.shape == (B, M) and weight.shape == (B, M)
+    out = [torch.empty((B, k), dtype=torch.int32, device=dev)] + [torch.empty((B,), dtype=torch.int32, device=dev)
+                                                                  for _ in range(4)]
+    ws = torch.empty(max(1, B * M * (k + 3)), dtype=torch.int32, device=dev)
+    rc = lib().sam_draft_merged(_dp(flat.row_ptr), _dp(flat.edge_tok), _dp(flat.edge_dst), _dp(flat.lastpos),
+                                _dp(flat.corpus), _dp(flat.state_rec), _dp(root), _dp(corpus_end), _dp(weight), M,
+                                _dp(recent), _dp(recent_len), B, m, k, min_match, sep_token,
+                                _dp(out[0]) if k > 0 else _vp(0), _dp(out[1]), _dp(out[2]), _dp(out[3]), _dp(out[4]),
+                                _dp(ws), ws.numel() * 4, _dp(flat.wide_table), flat.wide_table.numel() // 4,
+                                _stream_ptr())
+    _check(rc, "sam_draft_merged")
+    return tuple(out)
 
 
 def sam_apply_delta(delta: SamDelta, state_rec, lastpos) -> None:

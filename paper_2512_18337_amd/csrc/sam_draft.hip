@@ -89,13 +89,16 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     const int32_t *__restrict__ recent, const int32_t *__restrict__ recent_len,
     int m, int k, int min_match, int sep,
     int32_t *__restrict__ draft, int32_t *__restrict__ n_draft, int32_t *__restrict__ match_len,
-    int32_t *__restrict__ match_end, Overlay ov, const int32_t *__restrict__ rows_end, WideTable wt) {
+    int32_t *__restrict__ match_end, Overlay ov, const int32_t *__restrict__ rows_end, WideTable wt,
+    int lookups_per_session) {
+    // one wavefront per lookup; a session may query several automata with the same window
     const int b = blockIdx.x;
+    const int wb = b / lookups_per_session;
     const int lane = threadIdx.x;
     const int root = __builtin_amdgcn_readfirstlane(root_arr[b]);
-    const int ql = __builtin_amdgcn_readfirstlane(max(0, min(m, recent_len[b])));
+    const int ql = __builtin_amdgcn_readfirstlane(max(0, min(m, recent_len[wb])));
     // lane i holds the i-th token of the (right-aligned) window
-    const int wtok = (lane < ql) ? recent[(int64_t)b * m + (m - ql) + lane] : -1;
+    const int wtok = (lane < ql) ? recent[(int64_t)wb * m + (m - ql) + lane] : -1;
 
     // longest suffix of the window that occurs in the memory: state s, matched length l.
     // One 16-byte record per state {first token, its destination (or -2-d when the state has
@@ -201,7 +204,7 @@ extern "C" int sam_draft(const int32_t *len, const int32_t *link, const int32_t 
                        row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
                        draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, nullptr,
-                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u});
+                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, 1);
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }
@@ -224,7 +227,7 @@ extern "C" int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, 
     hipLaunchKernelGGL(sam_draft_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
                        row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       draft, n_draft, match_len, match_end, ov, rows_end, WideTable{nullptr, 0u});
+                       draft, n_draft, match_len, match_end, ov, rows_end, WideTable{nullptr, 0u}, 1);
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }
@@ -252,6 +255,77 @@ extern "C" int sam_apply_delta(const int32_t *rec_idx, const int32_t *rec_val, i
     hipLaunchKernelGGL(sam_apply_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                        rec_idx, (const int4 *)rec_val, n_rec, lastpos_idx, lastpos_val, n_lastpos,
                        (int4 *)state_rec, lastpos);
+    AGENTSAM_LAUNCH_CHECK();
+    return AGENTSAM_OK;
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Several automata per session (Alg. 4: S_merged = MergeSAM(S_session, S_cross, weights); Sec. 5.4.2:
+// the session's own context and the top-K retrieved contexts, weighted by their similarity scores).
+// The automata are not physically merged: every (session, automaton) pair is one lookup of the kernel
+// above, and the proposal of the automaton with the largest weight x matched length is taken.
+// ------------------------------------------------------------------------------------------
+namespace {
+__global__ __launch_bounds__(64) void sam_select_kernel(const float *__restrict__ weight, const int32_t *__restrict__ c_draft,
+                                                        const int32_t *__restrict__ c_n, const int32_t *__restrict__ c_len,
+                                                        const int32_t *__restrict__ c_end, int B, int M, int k,
+                                                        int32_t *__restrict__ draft, int32_t *__restrict__ n_draft,
+                                                        int32_t *__restrict__ match_len, int32_t *__restrict__ match_end,
+                                                        int32_t *__restrict__ source) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    int best = -1;
+    float best_score = 0.f;
+    int best_len = 0;
+    for (int j = 0; j < M; ++j) {                            // uniform over the wavefront
+        const int x = b * M + j;
+        const int len = c_len[x];
+        const float w = weight[x];
+        if (c_n[x] <= 0 || !(w > 0.f)) continue;             // no proposal from this automaton (or it is switched off)
+        const float score = w * (float)len;
+        if (best < 0 || score > best_score || (score == best_score && len > best_len)) {
+            best = j; best_score = score; best_len = len;
+        }
+    }
+    const int x = b * M + (best < 0 ? 0 : best);
+    if (lane < k) draft[(int64_t)b * k + lane] = best < 0 ? -1 : c_draft[(int64_t)x * k + lane];
+    if (lane == 0) {
+        n_draft[b] = best < 0 ? 0 : c_n[x];
+        match_len[b] = best < 0 ? 0 : c_len[x];
+        match_end[b] = best < 0 ? -1 : c_end[x];
+        source[b] = best;
+    }
+}
+}  // namespace
+
+extern "C" int sam_draft_merged(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
+                                const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,
+                                const int32_t *root, const int32_t *corpus_end, const float *weight, int32_t M,
+                                const int32_t *recent, const int32_t *recent_len,
+                                int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
+                                int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+                                int32_t *source, void *workspace, size_t workspace_bytes,
+                                const int32_t *wide_table, int64_t wide_slots, void *stream) {
+    if (B < 0 || M < 1 || m < 1 || m > 64 || k < 0 || k > 64 || min_match < 0) return AGENTSAM_ERR_ARG;
+    if ((int64_t)B * M > 0x7fffffffll) return AGENTSAM_ERR_ARG;
+    if (wide_table && (wide_slots < 2 || (wide_slots & (wide_slots - 1)) != 0 || wide_slots > (1ll << 31)))
+        return AGENTSAM_ERR_ARG;
+    if (B == 0) return AGENTSAM_OK;
+    if (!row_ptr || !lastpos || !state_rec || !root || !corpus_end || !weight || !recent || !recent_len ||
+        !n_draft || !match_len || !match_end || !source || (k > 0 && !draft) || !workspace)
+        return AGENTSAM_ERR_NULL;
+    const size_t n = (size_t)B * M;
+    if (workspace_bytes < n * (size_t)(k + 3) * sizeof(int32_t)) return AGENTSAM_ERR_WORKSPACE;
+    int32_t *c_draft = (int32_t *)workspace, *c_n = c_draft + n * k, *c_len = c_n + n, *c_end = c_len + n;
+    hipLaunchKernelGGL(sam_draft_kernel<false>, dim3((unsigned)n), dim3(64), 0, (hipStream_t)stream,
+                       row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
+                       recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
+                       c_draft, c_n, c_len, c_end, Overlay{nullptr, nullptr, 0u}, nullptr,
+                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, (int)M);
+    AGENTSAM_LAUNCH_CHECK();
+    hipLaunchKernelGGL(sam_select_kernel, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
+                       weight, c_draft, c_n, c_len, c_end, (int)B, (int)M, (int)k, draft, n_draft, match_len, match_end,
+                       source);
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }
