@@ -796,6 +796,7 @@ struct WideCfg {
     static constexpr int kCPR = D / 8;                       // 16-byte chunks per row
     static constexpr int kRPI = 64 / kCPR;                   // rows per 1 KB load instruction
     static constexpr int kPieces = kTile / kRPI;             // 1 KB load instructions per K (or V) tile
+    static constexpr int kG = kCPR > kRPI ? kCPR / kRPI : 1; // the swizzle pattern of a piece repeats every kG pieces
 };
 
 // 16 bytes per lane from global memory straight into LDS: lane i's data lands at lds_base + 16*i.
@@ -825,39 +826,47 @@ __device__ __forceinline__ const void *uniform_ptr(const void *ptr) {
     return (const void *)(((uint64_t)hi << 32) | lo);
 }
 
-// A whole tile (all 1 KB pieces of K, then of V at +kKT) in one block; M0 is saved once.
-#define AGENTSAM_DMA_PIECE(J, G)                       \
-    "s_add_u32 m0, %1, " #J "*1024\n\ts_nop 0\n\t"     \
-    "global_load_lds_dwordx4 " G ", %2 nt\n\t"         \
-    "s_add_u32 m0, %1, %c4+" #J "*1024\n\ts_nop 0\n\t" \
-    "global_load_lds_dwordx4 " G ", %3 nt\n\t"
+// A whole tile (all 1 KB pieces of K, then of V at +kKT) in one block.  The instruction's immediate
+// offset is added to the global AND to the LDS address, so four consecutive pieces share one M0
+// value and one base register pair: M0 is written once per 4 KB, not once per piece.  goffp[i] is
+// the lane's byte offset inside piece i of a group, without the piece's own i*1024 (the swizzle
+// repeats every kG pieces, so kG offsets serve all pieces).
+#define AGENTSAM_DMA_GROUP(MOFF, SB, G0, G1, G2, G3)                 \
+    "s_add_u32 m0, %1, " MOFF "\n\ts_nop 0\n\t"                     \
+    "global_load_lds_dwordx4 " G0 ", " SB " nt\n\t"                  \
+    "global_load_lds_dwordx4 " G1 ", " SB " offset:1024 nt\n\t"      \
+    "global_load_lds_dwordx4 " G2 ", " SB " offset:2048 nt\n\t"      \
+    "global_load_lds_dwordx4 " G3 ", " SB " offset:3072 nt\n\t"
 template <int D>
-__device__ __forceinline__ void lds_dma_tile(const void *kb, const void *vb, const unsigned (&goff)[WideCfg<D>::kPieces],
+__device__ __forceinline__ void lds_dma_tile(const char *kb, const char *vb, const unsigned (&goffp)[WideCfg<D>::kG],
                                              unsigned slot_addr /* uniform LDS byte address */) {
     const unsigned m = __builtin_amdgcn_readfirstlane(slot_addr);
     unsigned saved;
     if constexpr (D == 128) {
+        static_assert(WideCfg<D>::kPieces == 8 && WideCfg<D>::kG == 4, "two groups of four pieces");
+        const char *kb1 = kb + 4096, *vb1 = vb + 4096;
         asm volatile("s_mov_b32 %0, m0\n\t"
-                     AGENTSAM_DMA_PIECE(0, "%5") AGENTSAM_DMA_PIECE(1, "%6") AGENTSAM_DMA_PIECE(2, "%7")
-                     AGENTSAM_DMA_PIECE(3, "%8") AGENTSAM_DMA_PIECE(4, "%9") AGENTSAM_DMA_PIECE(5, "%10")
-                     AGENTSAM_DMA_PIECE(6, "%11") AGENTSAM_DMA_PIECE(7, "%12")
+                     AGENTSAM_DMA_GROUP("0", "%2", "%7", "%8", "%9", "%10")
+                     AGENTSAM_DMA_GROUP("4096", "%4", "%7", "%8", "%9", "%10")
+                     AGENTSAM_DMA_GROUP("%c6", "%3", "%7", "%8", "%9", "%10")
+                     AGENTSAM_DMA_GROUP("%c6+4096", "%5", "%7", "%8", "%9", "%10")
                      "s_mov_b32 m0, %0"
                      : "=&s"(saved)
-                     : "s"(m), "s"(kb), "s"(vb), "n"(WideCfg<D>::kKT), "v"(goff[0]), "v"(goff[1]), "v"(goff[2]),
-                       "v"(goff[3]), "v"(goff[4]), "v"(goff[5]), "v"(goff[6]), "v"(goff[7])
+                     : "s"(m), "s"(kb), "s"(vb), "s"(kb1), "s"(vb1), "n"(WideCfg<D>::kKT), "v"(goffp[0]), "v"(goffp[1]),
+                       "v"(goffp[2]), "v"(goffp[3])
                      : "memory", "scc");
     } else {
+        static_assert(WideCfg<D>::kPieces == 4 && WideCfg<D>::kG == 1, "one group of four pieces");
         asm volatile("s_mov_b32 %0, m0\n\t"
-                     AGENTSAM_DMA_PIECE(0, "%5") AGENTSAM_DMA_PIECE(1, "%6") AGENTSAM_DMA_PIECE(2, "%7")
-                     AGENTSAM_DMA_PIECE(3, "%8")
+                     AGENTSAM_DMA_GROUP("0", "%2", "%5", "%5", "%5", "%5")
+                     AGENTSAM_DMA_GROUP("%c4", "%3", "%5", "%5", "%5", "%5")
                      "s_mov_b32 m0, %0"
                      : "=&s"(saved)
-                     : "s"(m), "s"(kb), "s"(vb), "n"(WideCfg<D>::kKT), "v"(goff[0]), "v"(goff[1]), "v"(goff[2]),
-                       "v"(goff[3])
+                     : "s"(m), "s"(kb), "s"(vb), "n"(WideCfg<D>::kKT), "v"(goffp[0])
                      : "memory", "scc");
     }
 }
-#undef AGENTSAM_DMA_PIECE
+#undef AGENTSAM_DMA_GROUP
 
 template <int D, int MT, int NS, bool XT>
 __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
@@ -884,6 +893,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     // piece j of a tile (1 KB = kRPI rows): my 16 bytes are row j*kRPI + lrow, and I fetch the global
     // chunk that belongs in my LDS chunk under the XOR swizzle
     const int lrow = lane / W::kCPR, lslot = lane % W::kCPR;
+    unsigned goffp[W::kG];                                   // byte offset inside piece i (mod kG), minus the piece's i*1024
+#pragma unroll
+    for (int i = 0; i < W::kG; ++i)
+        goffp[i] = (unsigned)(lrow * W::kRowBytes + (lslot ^ ((i * W::kRPI + lrow) & (W::kCPR - 1))) * 16);
     // fragment reads: K rows n and n+16 (the swizzle only sees row & 15), V rows 4g+jq and +16.
     // Under the XOR swizzle the offset for k-step ks is koff0 ^ (ks << 6) and for d-tile dt it is
     // voff0 ^ (dt << 5); since slot offsets are multiples of 16 KB the XOR can be applied after the
@@ -931,21 +944,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         const char *vb = (const char *)uniform_ptr((const char *)p.vc + base);
         const int slot_off = slot_idx * W::kSlot;
         const int rows_left = S - pos0;                      // rows >= rows_left lie past the sequence
-        unsigned ld_goff[W::kPieces];                        // my byte offsets inside the tile in global memory
-#pragma unroll                                               // (recomputed here: only every 4th tile is mine)
-        for (int j = 0; j < W::kPieces; ++j) {
-            const int row = j * W::kRPI + lrow;
-            ld_goff[j] = (unsigned)(row * D + (lslot ^ (row & (W::kCPR - 1))) * 8) * 2u;
-        }
         if (page_ok && rows_left >= kTile) {                 // the usual case: a full tile, all lanes load
-            lds_dma_tile<D>(kb, vb, ld_goff, smem_addr + slot_off);
+            lds_dma_tile<D>(kb, vb, goffp, smem_addr + slot_off);
         } else {
 #pragma unroll
             for (int j = 0; j < W::kPieces; ++j) {
                 char *lk = smem + slot_off + j * 1024;
+                const unsigned goff = goffp[j % W::kG] + j * 1024;   // my byte offset inside the tile in global memory
                 if (page_ok && j * W::kRPI + lrow < rows_left) {
-                    lds_dma16(kb, ld_goff[j], smem_addr + slot_off + j * 1024);
-                    lds_dma16(vb, ld_goff[j], smem_addr + slot_off + j * 1024 + W::kKT);
+                    lds_dma16(kb, goff, smem_addr + slot_off + j * 1024);
+                    lds_dma16(vb, goff, smem_addr + slot_off + j * 1024 + W::kKT);
                 } else {
                     // past the end of the sequence (or a bad page id): the slot must not keep stale
                     // bits, since 0 * NaN would poison the row sums
