@@ -73,6 +73,9 @@ BF16_SMALL = [
     dict(B=2, Hq=16, Hkv=2, D=128, k=16, kv_mode="ragged", kv_len=(17, 2500), permute_pages=True),  # 136 rows
     dict(B=2, Hq=10, Hkv=2, D=128, k=8, kv_mode="shared_prefix", kv_len=(40, 500), prefix_len=1024),  # 45 rows
     dict(B=2, Hq=8, Hkv=2, D=64, k=8, kv_mode="ragged", kv_len=(9, 2000), permute_pages=True, page=32),
+    # head dim 64 with more than 48 packed rows: the wide kernel's ring of 8 slots, one 4 KB group per part
+    dict(B=2, Hq=16, Hkv=2, D=64, k=8, kv_mode="ragged", kv_len=(33, 1800), permute_pages=True, page=32),   # 72 rows
+    dict(B=2, Hq=16, Hkv=2, D=64, k=16, kv_mode="ragged", kv_len=(17, 2300), permute_pages=True),           # 136 rows
 ]
 
 
