@@ -179,6 +179,42 @@ int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32
                     void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * sam_draft_step: sam_draft with the matched state carried from call to call (Alg. 4, the decoding
+ * loop: x_t is the current verified suffix and the decoder follows transitions from where it stands;
+ * Sec. 5.4.2: "given the current verified suffix, the decoder follows SAM transitions").  A call
+ * consumes only the tokens committed since the previous call, so its cost does not depend on how
+ * long the match is, and the match is not cut to a window.
+ *
+ *   cur_state[B], cur_len[B]   device, in and out: the state and length of the carried match.  A
+ *                              session starts with cur_len = 0 (cur_state then ignored; any negative
+ *                              cur_state also means a fresh session).  Otherwise the pair must be
+ *                              what this entry point wrote for the same automaton, which may have
+ *                              grown since (sam_append + sam_apply_delta): a state that was split
+ *                              meanwhile is followed to the clone that now holds the string.
+ *   new_tok[B,max_new], n_new[B]   device: the tokens to consume, oldest first (n_new clipped to
+ *                              [0,max_new]; no limit on max_new).
+ * Definition of the carried length after token t_n, with the memory as it is at the call:
+ *   L_n = max { l+1 : 0 <= l <= L_(n-1), the last l+1 tokens (t_(n-l) .. t_n) occur in the memory },
+ *   0 if t_n does not occur.  On a memory that does not change this is the longest suffix of
+ *   everything consumed so far; after the memory has grown it can be shorter than that (a longer
+ *   match that only the new text makes possible is not looked for).
+ * The proposal is the one sam_draft makes for a window of exactly those L_n tokens; outputs as
+ * sam_draft.  Automaton arrays as sam_draft (overlay_key NULL: a flattened automaton, wide_table
+ * optional) or as sam_draft_delta (overlay_key, overlay_dst, overlay_cap, rows_end given: a
+ * maintained copy; wide_table must then be NULL).
+ * ---------------------------------------------------------------------------------------- */
+int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
+                   const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,
+                   const uint64_t *overlay_key, const int32_t *overlay_dst, int64_t overlay_cap,
+                   const int32_t *rows_end, const int32_t *wide_table, int64_t wide_slots,
+                   const int32_t *root, const int32_t *corpus_end,
+                   const int32_t *new_tok, const int32_t *n_new, int32_t B, int32_t max_new,
+                   int32_t k, int32_t min_match, int32_t sep_token,
+                   int32_t *cur_state, int32_t *cur_len,
+                   int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+                   void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Asynchronous construction (Sec. 5.4.2, "Asynchronous SAM construction"; Alg. 4 step 2: a
  * background thread extends the automaton with streamed tokens).  A builder owns one child thread, a
  * waiting queue and the automata of the requests submitted to it.

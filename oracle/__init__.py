@@ -20,7 +20,9 @@ Every function is pinned by tests that run without a GPU (worked examples,
 closed forms, invariants, an independent brute force, library special cases);
 none is "parity unpinned".
 """
-from .draft import draft_oracle, draft_oracle_batch, build_oracle_lib, merged_draft_oracle  # noqa: F401
+from .draft import (  # noqa: F401
+    draft_oracle, draft_oracle_batch, build_oracle_lib, merged_draft_oracle, carried_match_len_oracle, draft_step_oracle,
+)
 from .attention import attention_oracle, attention_oracle_head          # noqa: F401
 from .accept import accept_oracle                                        # noqa: F401
 from .sched import adaptive_k_oracle, agentsched_oracle                   # noqa: F401

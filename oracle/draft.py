@@ -64,3 +64,50 @@ def merged_draft_oracle(memories, weights, q, k, sep, min_match=1):
     if best is None:
         return np.full(k, -1, np.int32), 0, 0, -1, -1
     return best[1], best[2], best[3], best[4], best[5]
+
+
+def _occurs(T: np.ndarray, pat: np.ndarray) -> bool:
+    """Does pat occur in T as a contiguous run?  Plain scan."""
+    n, m = T.shape[0], pat.shape[0]
+    if m == 0:
+        return True
+    if m > n:
+        return False
+    cand = np.flatnonzero(T[: n - m + 1] == pat[0])
+    for j in range(1, m):
+        if cand.size == 0:
+            return False
+        cand = cand[T[cand + j] == pat[j]]
+    return cand.size > 0
+
+
+def carried_match_len_oracle(T, ctx, L_prev: int, n_new: int) -> int:
+    """Length of the match carried from call to call (Alg. 4, the decoding loop: the decoder follows
+    transitions from the current verified suffix).  ctx = every token of the session so far, the last n_new
+    of them not yet consumed; L_prev = the carried length before them; T = the memory as it is NOW.
+    For each new token t_n, in order:
+        L_n = max { l+1 : 0 <= l <= L_(n-1), ctx[n-l .. n] occurs in T },  0 if t_n does not occur in T.
+    (A match is extended by one token or cut from the left; a longer one is never looked for.)"""
+    T = np.ascontiguousarray(T, dtype=np.int32)
+    ctx = np.ascontiguousarray(ctx, dtype=np.int32)
+    L = int(L_prev)
+    for n in range(ctx.shape[0] - n_new, ctx.shape[0]):
+        new_L = 0
+        for l in range(min(L, n), -1, -1):
+            if _occurs(T, ctx[n - l: n + 1]):
+                new_L = l + 1
+                break
+        L = new_L
+    return L
+
+
+def draft_step_oracle(T, ctx, L_prev: int, n_new: int, k: int, sep: int, min_match: int = 1):
+    """One call of the stateful lookup: the carried length after the new tokens, then the proposal that
+    draft_oracle makes for a window of exactly that many tokens.
+    Returns (L, draft[k], n_draft, match_len, match_end)."""
+    L = carried_match_len_oracle(T, ctx, L_prev, n_new)
+    ctx = np.ascontiguousarray(ctx, dtype=np.int32)
+    if L == 0:
+        return 0, np.full(k, -1, np.int32), 0, 0, -1
+    d, nd, ml, me = draft_oracle(T, ctx[ctx.shape[0] - L:], k, sep, min_match)
+    return L, d, nd, ml, me

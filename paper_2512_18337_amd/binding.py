@@ -25,7 +25,7 @@ _vp = ctypes.c_void_p
 EXPORTS = ["agentsam_strerror", "agentsam_set_option", "agentsam_stream_read_probe", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
-           "sam_draft", "sam_draft_delta", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
+           "sam_draft", "sam_draft_delta", "sam_draft_step", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
            "spec_adaptive_k", "agentsched_pick"]
 
 
@@ -75,6 +75,8 @@ def lib():
         L.sam_apply_delta.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
         L.sam_draft_delta.argtypes = ([_vp] * 8 + [ctypes.c_int64] + [_vp] * 5 + [ctypes.c_int32] * 5 +
                                       [_vp] * 4 + [_vp])
+        L.sam_draft_step.argtypes = ([_vp] * 8 + [ctypes.c_int64, _vp, _vp, ctypes.c_int64] + [_vp] * 4 +
+                                     [ctypes.c_int32] * 5 + [_vp] * 6 + [_vp])
         L.spec_verify_attn_workspace.argtypes = [ctypes.c_int32] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
         L.spec_verify_attn.argtypes = ([_vp, _vp, _vp, _vp, ctypes.c_int32, _vp] + [ctypes.c_int32] * 6 +
                                        [ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
@@ -369,6 +371,40 @@ def sam_draft_delta(flat: FlatSam, overlay_key, overlay_dst, rows_end, root, cor
                                _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
                                _stream_ptr())
     _check(rc, "sam_draft_delta")
+    return draft, n_draft, match_len, match_end
+
+
+def sam_draft_step(flat: FlatSam, root, corpus_end, new_tok, n_new, cur_state, cur_len, k: int, sep_token: int,
+                   min_match: int = 1, overlay_key=None, overlay_dst=None, rows_end=None, use_wide_table: bool = True):
+    """sam_draft with the matched state carried from call to call.  cur_state / cur_len are device int32
+    tensors updated in place (start a session with cur_len = 0).  With overlay_key / overlay_dst /
+    rows_end the arrays are a maintained device copy (as for sam_draft_delta)."""
+    import torch
+    dev = flat.state_rec.device
+    root, corpus_end = _dev_i32(root, dev), _dev_i32(corpus_end, dev)
+    new_tok, n_new = _dev_i32(new_tok, dev), _dev_i32(n_new, dev)
+    B, max_new = new_tok.shape
+    for t in (cur_state, cur_len):
+        if t.dtype != torch.int32 or t.device != dev or not t.is_contiguous() or t.numel() != B:
+            raise ValueError("cur_state / cur_len must be contiguous int32 device tensors of B elements")
+    maintained = overlay_key is not None
+    if maintained:
+        rows_end = _dev_i32(rows_end, dev)
+    wt = None if maintained or not use_wide_table else flat.wide_table
+    draft = torch.empty((B, k), dtype=torch.int32, device=dev)
+    n_draft = torch.empty((B,), dtype=torch.int32, device=dev)
+    match_len = torch.empty((B,), dtype=torch.int32, device=dev)
+    match_end = torch.empty((B,), dtype=torch.int32, device=dev)
+    rc = lib().sam_draft_step(_dp(flat.row_ptr), _dp(flat.edge_tok), _dp(flat.edge_dst), _dp(flat.lastpos),
+                              _dp(flat.corpus), _dp(flat.state_rec),
+                              _dp(overlay_key) if maintained else _vp(0), _dp(overlay_dst) if maintained else _vp(0),
+                              overlay_key.numel() if maintained else 0, _dp(rows_end) if maintained else _vp(0),
+                              _dp(wt) if wt is not None else _vp(0), (wt.numel() // 4) if wt is not None else 0,
+                              _dp(root), _dp(corpus_end), _dp(new_tok) if max_new > 0 else _vp(0), _dp(n_new), B, max_new,
+                              k, min_match, sep_token, _dp(cur_state), _dp(cur_len),
+                              _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
+                              _stream_ptr())
+    _check(rc, "sam_draft_step")
     return draft, n_draft, match_len, match_end
 
 

@@ -80,6 +80,91 @@ __device__ __forceinline__ int find_edge(const int32_t *__restrict__ edge_tok,
     return wave_bcast(ds, __ffsll((long long)eq) - 1);
 }
 
+// The flat automaton as the kernels see it.
+struct FlatSam {
+    const int32_t *row_ptr, *edge_tok, *edge_dst, *lastpos, *corpus;
+    const int4 *state_rec;
+    const int32_t *rows_end;         // maintained automaton only: states below rows_end[b] have a flattened row
+};
+
+// One step of the walk: consume token c from (state s, matched length l).  Afterwards s is the state
+// of the longest suffix of (old match + c) that occurs in the memory and l its length.
+// One 16-byte record per state {first token, its destination (or -2-d when the state has more
+// transitions), suffix link, len of the link's state} makes the common step - a state with a single
+// transition that matches - cost one dependent load.  s, l and every branch are wave-uniform and kept
+// in scalar registers, so the record is fetched with a scalar load and the loop carries no exec-mask
+// bookkeeping.  root_pref: the root's transition on c if the caller fetched it ahead, -2 if not.
+template <bool OVERLAY>
+__device__ __forceinline__ void consume_token(const FlatSam &A, const Overlay &ov, const WideTable &wt, int b, int root,
+                                              int root_pref, int c, int lane, int &s, int &l) {
+    for (;;) {
+        if (root_pref != -2 && s == root) {
+            if (root_pref >= 0) { s = root_pref; ++l; } else { l = 0; }
+            return;
+        }
+        const int4 rec = A.state_rec[s];
+        const int r0 = __builtin_amdgcn_readfirstlane(rec.x), r1 = __builtin_amdgcn_readfirstlane(rec.y);
+        int dst = -1;
+        if (r0 == c) {
+            dst = r1 >= 0 ? r1 : -2 - r1;
+        } else if (!OVERLAY) {
+            if (r1 < -1 && c > r0) {                   // rows are sorted: c can only be further right
+                if (wt.slot != nullptr && __builtin_amdgcn_readfirstlane(rec.w) < 0)
+                    dst = __builtin_amdgcn_readfirstlane(wide_find(wt, s, c));
+                else
+                    dst = __builtin_amdgcn_readfirstlane(
+                        find_edge(A.edge_tok, A.edge_dst, A.row_ptr[s] + 1, A.row_ptr[s + 1], c, lane));
+            }
+        } else if (r1 < -1) {
+            // Maintained automaton: the record holds any one transition; the overlay overrides the
+            // flattened row (a transition may have been redirected to a clone), and only states
+            // that existed at the last flatten have a row at all.
+            dst = __builtin_amdgcn_readfirstlane(overlay_find(ov, s, c));
+            if (dst < 0 && s < __builtin_amdgcn_readfirstlane(A.rows_end[b]))
+                dst = __builtin_amdgcn_readfirstlane(
+                    find_edge(A.edge_tok, A.edge_dst, A.row_ptr[s], A.row_ptr[s + 1], c, lane));
+        }
+        if (dst >= 0) { s = dst; ++l; return; }
+        if (s == root) { l = 0; return; }
+        s = __builtin_amdgcn_readfirstlane(rec.z);
+        l = link_len(__builtin_amdgcn_readfirstlane(rec.w));
+    }
+}
+
+// The proposal of (state s, matched length l): the tokens that followed the most recent occurrence
+// that still has a continuation; all strings of one state share their end positions, so if this state
+// has none, the next candidate is the suffix link's longest string.
+__device__ __forceinline__ void emit_draft(const FlatSam &A, int b, int root, int s, int l, int k, int min_match, int sep,
+                                           int corpus_end_b, int lane, int32_t *__restrict__ draft,
+                                           int32_t *__restrict__ n_draft, int32_t *__restrict__ match_len,
+                                           int32_t *__restrict__ match_end) {
+    int L = l, e = -1;
+    while (s != root) {
+        const int lp = A.lastpos[s];
+        if (lp >= 0) { e = lp; break; }
+        const int4 rec = A.state_rec[s];
+        s = rec.z;
+        L = link_len(rec.w);
+    }
+    if (e < 0 || L < min_match) { e = -1; L = 0; }
+
+    int n = 0;
+    int tk = -1;
+    if (e >= 0 && k > 0) {
+        const int idx = e + 1 + lane;
+        const bool in = (lane < k) && (idx < corpus_end_b);
+        tk = in ? A.corpus[idx] : sep;
+        const unsigned long long stop = __ballot(!(in && tk != sep));
+        n = stop ? (__ffsll((long long)stop) - 1) : 64;
+    }
+    if (lane < k) draft[(int64_t)b * k + lane] = (lane < n) ? tk : -1;
+    if (lane == 0) {
+        n_draft[b] = n;
+        match_len[b] = L;
+        match_end[b] = e;
+    }
+}
+
 template <bool OVERLAY>
 __global__ __launch_bounds__(64) void sam_draft_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_tok,
@@ -95,17 +180,13 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     const int b = blockIdx.x;
     const int wb = b / lookups_per_session;
     const int lane = threadIdx.x;
+    const FlatSam A{row_ptr, edge_tok, edge_dst, lastpos, corpus, state_rec, rows_end};
     const int root = __builtin_amdgcn_readfirstlane(root_arr[b]);
     const int ql = __builtin_amdgcn_readfirstlane(max(0, min(m, recent_len[wb])));
     // lane i holds the i-th token of the (right-aligned) window
     const int wtok = (lane < ql) ? recent[(int64_t)wb * m + (m - ql) + lane] : -1;
 
     // longest suffix of the window that occurs in the memory: state s, matched length l.
-    // One 16-byte record per state {first token, its destination (or -2-d when the state has
-    // more transitions), suffix link, len of the link's state} makes the common step - a state
-    // with a single transition that matches - cost one dependent load.
-    // s, l and every branch below are wave-uniform and kept in scalar registers, so the record is
-    // fetched with a scalar load and the loop carries no exec-mask bookkeeping.
     // Every mismatch sends the walk back towards the root, so the root's transition is the lookup
     // made most often.  When the root is a wide state, all 64 of them (one per window token) are
     // fetched up front, side by side, one per lane, and the walk takes them from a register.
@@ -116,68 +197,51 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     int s = __builtin_amdgcn_readfirstlane(root), l = 0;
     for (int t = 0; t < ql; ++t) {
         const int c = __builtin_amdgcn_readlane(wtok, t);
-        for (;;) {
-            if (root_ahead && s == root) {
-                const int dst = __builtin_amdgcn_readlane(root_next, t);
-                if (dst >= 0) { s = dst; ++l; } else { l = 0; }
-                break;
-            }
-            const int4 rec = state_rec[s];
-            const int r0 = __builtin_amdgcn_readfirstlane(rec.x), r1 = __builtin_amdgcn_readfirstlane(rec.y);
-            int dst = -1;
-            if (r0 == c) {
-                dst = r1 >= 0 ? r1 : -2 - r1;
-            } else if (!OVERLAY) {
-                if (r1 < -1 && c > r0) {                   // rows are sorted: c can only be further right
-                    if (wt.slot != nullptr && __builtin_amdgcn_readfirstlane(rec.w) < 0)
-                        dst = __builtin_amdgcn_readfirstlane(wide_find(wt, s, c));
-                    else
-                        dst = __builtin_amdgcn_readfirstlane(
-                            find_edge(edge_tok, edge_dst, row_ptr[s] + 1, row_ptr[s + 1], c, lane));
-                }
-            } else if (r1 < -1) {
-                // Maintained automaton: the record holds any one transition; the overlay overrides the
-                // flattened row (a transition may have been redirected to a clone), and only states
-                // that existed at the last flatten have a row at all.
-                dst = __builtin_amdgcn_readfirstlane(overlay_find(ov, s, c));
-                if (dst < 0 && s < __builtin_amdgcn_readfirstlane(rows_end[b]))
-                    dst = __builtin_amdgcn_readfirstlane(
-                        find_edge(edge_tok, edge_dst, row_ptr[s], row_ptr[s + 1], c, lane));
-            }
-            if (dst >= 0) { s = dst; ++l; break; }
-            if (s == root) { l = 0; break; }
-            s = __builtin_amdgcn_readfirstlane(rec.z);
-            l = link_len(__builtin_amdgcn_readfirstlane(rec.w));
+        const int pref = root_ahead ? __builtin_amdgcn_readlane(root_next, t) : -2;
+        consume_token<OVERLAY>(A, ov, wt, b, root, pref, c, lane, s, l);
+    }
+    emit_draft(A, b, root, s, l, k, min_match, sep, corpus_end[b], lane, draft, n_draft, match_len, match_end);
+}
+
+// Stateful form: the matched state of every session is carried from call to call, so a call consumes
+// only the tokens committed since the previous one (Alg. 4: x_t is the current verified suffix; the
+// decoder follows transitions from where it stands).  cur_state/cur_len: in and out.
+template <bool OVERLAY>
+__global__ __launch_bounds__(64) void sam_draft_step_kernel(
+    FlatSam A, const int32_t *__restrict__ root_arr, const int32_t *__restrict__ corpus_end,
+    const int32_t *__restrict__ new_tok, const int32_t *__restrict__ n_new, int max_new,
+    int k, int min_match, int sep, int32_t *__restrict__ cur_state, int32_t *__restrict__ cur_len,
+    int32_t *__restrict__ draft, int32_t *__restrict__ n_draft, int32_t *__restrict__ match_len,
+    int32_t *__restrict__ match_end, Overlay ov, WideTable wt) {
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int root = __builtin_amdgcn_readfirstlane(root_arr[b]);
+    int s = __builtin_amdgcn_readfirstlane(cur_state[b]);
+    int l = __builtin_amdgcn_readfirstlane(cur_len[b]);
+    if (s < 0 || l <= 0) { s = root; l = 0; }                // a fresh session
+    // The memory may have grown since the state was stored: a state can have been split, its shorter
+    // strings now living in a clone that became its suffix link.  The string of length l belongs to
+    // the state r on the link path with len(link(r)) < l <= len(r).
+    while (s != root) {
+        const int4 rec = A.state_rec[s];
+        if (link_len(__builtin_amdgcn_readfirstlane(rec.w)) < l) break;
+        s = __builtin_amdgcn_readfirstlane(rec.z);
+    }
+    const int nn = __builtin_amdgcn_readfirstlane(max(0, min(max_new, n_new[b])));
+    const bool root_wide = !OVERLAY && wt.slot != nullptr && __builtin_amdgcn_readfirstlane(A.state_rec[root].w) < 0;
+    for (int t0 = 0; t0 < nn; t0 += 64) {                    // 64 tokens at a time, one per lane
+        const int cnt = min(64, nn - t0);
+        const int wtok = (lane < cnt) ? new_tok[(int64_t)b * max_new + t0 + lane] : -1;
+        int root_next = -2;
+        if (root_wide) root_next = (lane < cnt) ? wide_find(wt, root, wtok) : -1;
+        for (int t = 0; t < cnt; ++t) {
+            const int c = __builtin_amdgcn_readlane(wtok, t);
+            const int pref = root_wide ? __builtin_amdgcn_readlane(root_next, t) : -2;
+            consume_token<OVERLAY>(A, ov, wt, b, root, pref, c, lane, s, l);
         }
     }
-
-    // most recent occurrence that still has a continuation; all strings of one state share their
-    // end positions, so if this state has none, the next candidate is the suffix link's longest string
-    int L = l, e = -1;
-    while (s != root) {
-        const int lp = lastpos[s];
-        if (lp >= 0) { e = lp; break; }
-        const int4 rec = state_rec[s];
-        s = rec.z;
-        L = link_len(rec.w);
-    }
-    if (e < 0 || L < min_match) { e = -1; L = 0; }
-
-    int n = 0;
-    int tk = -1;
-    if (e >= 0 && k > 0) {
-        const int idx = e + 1 + lane;
-        const bool in = (lane < k) && (idx < corpus_end[b]);
-        tk = in ? corpus[idx] : sep;
-        const unsigned long long stop = __ballot(!(in && tk != sep));
-        n = stop ? (__ffsll((long long)stop) - 1) : 64;
-    }
-    if (lane < k) draft[(int64_t)b * k + lane] = (lane < n) ? tk : -1;
-    if (lane == 0) {
-        n_draft[b] = n;
-        match_len[b] = L;
-        match_end[b] = e;
-    }
+    if (lane == 0) { cur_state[b] = s; cur_len[b] = l; }
+    emit_draft(A, b, root, s, l, k, min_match, sep, corpus_end[b], lane, draft, n_draft, match_len, match_end);
 }
 
 }  // namespace
@@ -228,6 +292,44 @@ extern "C" int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, 
                        row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
                        draft, n_draft, match_len, match_end, ov, rows_end, WideTable{nullptr, 0u}, 1);
+    AGENTSAM_LAUNCH_CHECK();
+    return AGENTSAM_OK;
+}
+
+extern "C" int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
+                              const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,
+                              const uint64_t *overlay_key, const int32_t *overlay_dst, int64_t overlay_cap,
+                              const int32_t *rows_end, const int32_t *wide_table, int64_t wide_slots,
+                              const int32_t *root, const int32_t *corpus_end,
+                              const int32_t *new_tok, const int32_t *n_new, int32_t B, int32_t max_new,
+                              int32_t k, int32_t min_match, int32_t sep_token,
+                              int32_t *cur_state, int32_t *cur_len,
+                              int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
+                              void *stream) {
+    if (B < 0 || max_new < 0 || k < 0 || k > 64 || min_match < 0) return AGENTSAM_ERR_ARG;
+    const bool maintained = overlay_key != nullptr;
+    if (maintained && (overlay_cap < 2 || (overlay_cap & (overlay_cap - 1)) != 0 || overlay_cap > (1ll << 31)))
+        return AGENTSAM_ERR_ARG;
+    if (wide_table && (wide_slots < 2 || (wide_slots & (wide_slots - 1)) != 0 || wide_slots > (1ll << 31)))
+        return AGENTSAM_ERR_ARG;
+    if (maintained && wide_table) return AGENTSAM_ERR_ARG;   // the table is a snapshot of the last flatten
+    if (B == 0) return AGENTSAM_OK;
+    if (!row_ptr || !lastpos || !state_rec || !root || !corpus_end || !n_new || (max_new > 0 && !new_tok) ||
+        !cur_state || !cur_len || !n_draft || !match_len || !match_end || (k > 0 && !draft))
+        return AGENTSAM_ERR_NULL;
+    if (maintained && (!overlay_dst || !rows_end)) return AGENTSAM_ERR_NULL;
+    const FlatSam A{row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, rows_end};
+    if (maintained) {
+        const Overlay ov{(const unsigned long long *)overlay_key, overlay_dst, (unsigned)(overlay_cap - 1)};
+        hipLaunchKernelGGL(sam_draft_step_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream, A, root,
+                           corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state,
+                           cur_len, draft, n_draft, match_len, match_end, ov, WideTable{nullptr, 0u});
+    } else {
+        hipLaunchKernelGGL(sam_draft_step_kernel<false>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream, A, root,
+                           corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state,
+                           cur_len, draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u},
+                           WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u});
+    }
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }

@@ -1,0 +1,144 @@
+"""GPU parity of sam_draft_step (matched state carried from call to call) against the carried-match oracle,
+bit-exact, through the C ABI: on a flattened automaton (with and without the wide-state table) and on a
+maintained device copy whose memory grows between the calls."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_18337_amd as A
+from oracle import draft_step_oracle
+from paper_2512_18337_amd import workloads as W
+from _util import to_np
+from test_gpu_sam_delta import _sync
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _next_tokens(rng, T, ctx, vocab, lo, hi):
+    """What a session produces next: mostly text that continues a span of the memory, sometimes noise."""
+    n = int(rng.integers(lo, hi + 1))
+    out = []
+    while len(out) < n:
+        r = rng.random()
+        if r < 0.75 and len(T) > 40:
+            p = int(rng.integers(0, len(T) - 30)); out += [int(x) for x in T[p:p + int(rng.integers(3, 30))]]
+        else:
+            out += [int(x) for x in rng.integers(0, vocab, int(rng.integers(1, 4)))]
+    return out[:n]
+
+
+def _check_step(tag, mems, owner, ctxs, L_prev, n_new, got, cur_len, corpus_begin, k, sep):
+    d, nd, ml, me = (to_np(x) for x in got)
+    cl = to_np(cur_len)
+    for b in range(len(owner)):
+        T = np.asarray(mems[owner[b]], np.int32)
+        L, od, ond, oml, ome = draft_step_oracle(T, np.asarray(ctxs[b], np.int32), L_prev[b], n_new[b], k, sep, 1)
+        got_end = int(me[b]) - int(corpus_begin[owner[b]]) if me[b] >= 0 else -1
+        assert int(cl[b]) == L, (tag, b, int(cl[b]), L)
+        assert (int(ml[b]), got_end, int(nd[b])) == (oml, ome, ond), (tag, b)
+        assert list(d[b, :ond]) == list(od[:ond]) and (d[b, ond:] == -1).all(), (tag, b)
+        L_prev[b] = L
+    return max(L_prev)
+
+
+@pytest.mark.parametrize("wide", [True, False])
+def test_carried_state_on_a_flattened_automaton(wide):
+    cfg = W.scaled(W.baseline_config(2), B=20, sam_sessions=6, sam_session_len=1500, vocab=2000, m=32, k=8)
+    rng = np.random.default_rng(31 + int(wide))
+    mems = [list(W.token_memory(cfg))]
+    # filter separators out of what sessions "say": a context never holds the separator
+    owner = [0] * cfg.B
+    sams = [A.sam_build(np.asarray(T, np.int32), cfg.sep) for T in mems]
+    flat = A.sam_flatten(sams)
+    fd = flat.to(DEV)
+    root = np.array([flat.roots[o] for o in owner], np.int32)
+    cend = np.array([flat.corpus_end[o] for o in owner], np.int32)
+    cur_state = torch.full((cfg.B,), -1, dtype=torch.int32, device=DEV)
+    cur_len = torch.zeros((cfg.B,), dtype=torch.int32, device=DEV)
+    ctxs = [[] for _ in range(cfg.B)]
+    L_prev = [0] * cfg.B
+    sizes = [(100, 150), (0, 9), (1, 9), (1, 9), (0, 3), (60, 70), (1, 9), (1, 2)]   # first call: the prompt; one call > 64
+    longest = 0
+    for step, (lo, hi) in enumerate(sizes):
+        new = [[t for t in _next_tokens(rng, mems[0], ctxs[b], cfg.vocab, lo, hi) if t != cfg.sep] for b in range(cfg.B)]
+        if step == 3:
+            new[0] = []                                       # a session with nothing new this call
+        max_new = max(1, max(len(x) for x in new))
+        tok = np.full((cfg.B, max_new), -7, np.int32)
+        n_new = np.array([len(x) for x in new], np.int32)
+        for b in range(cfg.B):
+            tok[b, :len(new[b])] = new[b]
+            ctxs[b] += new[b]
+        print(f"draft step {step}: max_new {max_new} wide {wide}", flush=True)
+        got = A.sam_draft_step(fd, root, cend, tok, n_new, cur_state, cur_len, cfg.k, cfg.sep, use_wide_table=wide)
+        torch.cuda.synchronize()
+        longest = max(longest, _check_step((wide, step), mems, owner, ctxs, L_prev, n_new, got, cur_len,
+                                           flat.corpus_begin, cfg.k, cfg.sep))
+    assert longest > 8                                        # the stream really carried long matches
+
+
+def test_carried_state_on_a_growing_memory():
+    cfg = W.scaled(W.baseline_config(2), B=18, sam_sessions=1, sam_session_len=2500, vocab=1500, m=32, k=8,
+                   sam_mode="per_session")
+    rng = np.random.default_rng(303)
+    mems = [list(W.token_memory(cfg, i)) for i in range(3)]
+    owner = [b % 3 for b in range(cfg.B)]
+    sams = [A.sam_build(np.asarray(T, np.int32), cfg.sep) for T in mems]
+    grow = 1500
+    flat = A.sam_flatten(sams, grow_tokens=grow)
+    fd = flat.to(DEV)
+    mem_len = [len(T) for T in mems]
+    root = np.array([flat.roots[o] for o in owner], np.int32)
+    rows_end = np.array([flat.rows_end[o] for o in owner], np.int32)
+    cur_state = torch.full((cfg.B,), -1, dtype=torch.int32, device=DEV)
+    cur_len = torch.zeros((cfg.B,), dtype=torch.int32, device=DEV)
+    ctxs = [[] for _ in range(cfg.B)]
+    L_prev = [0] * cfg.B
+    for step in range(10):
+        # the memories grow: mostly by what their own sessions said last (their contexts' tails), which is
+        # what splits the very states the sessions stand in
+        for i, T in enumerate(mems):
+            add = []
+            for b in range(cfg.B):
+                if owner[b] == i and ctxs[b] and rng.random() < 0.6:
+                    add += ctxs[b][-int(rng.integers(2, 12)):] + [int(rng.integers(0, cfg.vocab))]
+            add += [int(x) for x in rng.integers(0, cfg.vocab, int(rng.integers(1, 6)))]
+            if step % 4 == 2:
+                add.append(cfg.sep)
+            add = add[:grow // 10 - 1]
+            A.sam_append(sams[i], np.asarray(add, np.int32))
+            T += add
+        keys, dsts = _sync(sams, fd, flat, mem_len)
+        cend = np.array([int(flat.corpus_begin[owner[b]]) + mem_len[owner[b]] for b in range(cfg.B)], np.int32)
+        lo, hi = ((40, 80) if step == 0 else (0, 9))
+        new = [[t for t in _next_tokens(rng, mems[owner[b]], ctxs[b], cfg.vocab, lo, hi) if t != cfg.sep]
+               for b in range(cfg.B)]
+        max_new = max(1, max(len(x) for x in new))
+        tok = np.full((cfg.B, max_new), -7, np.int32)
+        n_new = np.array([len(x) for x in new], np.int32)
+        for b in range(cfg.B):
+            tok[b, :len(new[b])] = new[b]
+            ctxs[b] += new[b]
+        print(f"draft step on growing memory {step}: overlay capacity {keys.numel()}", flush=True)
+        got = A.sam_draft_step(fd, root, cend, tok, n_new, cur_state, cur_len, cfg.k, cfg.sep,
+                               overlay_key=keys, overlay_dst=dsts, rows_end=rows_end)
+        torch.cuda.synchronize()
+        _check_step(step, mems, owner, ctxs, L_prev, n_new, got, cur_len, flat.corpus_begin, cfg.k, cfg.sep)
+
+
+def test_draft_step_argument_errors():
+    z = torch.zeros(4, dtype=torch.int32, device=DEV)
+    L = A.binding.lib()
+    p = A.binding._dp
+    n = A.binding._vp(0)
+
+    def call(B=1, k=8, cur=p(z), arrays=p(z)):
+        return L.sam_draft_step(arrays, arrays, arrays, arrays, arrays, arrays, n, n, 0, n, n, 0, arrays, arrays,
+                                arrays, arrays, B, 1, k, 1, 9, cur, cur, arrays, arrays, arrays, arrays, n)
+
+    assert call(k=65) != 0                                    # k out of range
+    assert call(B=-1) != 0
+    assert call(cur=n) != 0                                   # missing carried-state arrays
+    assert call(B=0, cur=n, arrays=n) == 0                    # an empty batch is a no-op
+    torch.cuda.synchronize()
