@@ -164,6 +164,29 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev):
             "overlay_transitions_at_end": int(n_ov), "full_flatten_ms": t_flatten * 1e3}
 
 
+def measure_build(A, cfg):
+    """Host cost of making a prompt's automaton available (Sec. 5.4.2, asynchronous construction): building
+    and flattening 30k- and 128k-token prompts on the calling thread, against what the calling thread pays
+    when the child thread builds (the submit call)."""
+    out = {}
+    rng = np.random.default_rng(cfg.seed)
+    for name, n in (("30k", 30000), ("128k", 131072)):
+        # a repetitive prompt: spans of an 8k-token base text repeated with small edits
+        base = rng.integers(0, cfg.vocab, 8192).astype(np.int32)
+        toks = np.concatenate([base[int(rng.integers(0, 4096)):][:int(rng.integers(256, 2048))] for _ in range(n // 256)])[:n]
+        toks = np.ascontiguousarray(np.where(rng.random(toks.shape[0]) < 0.02, rng.integers(0, cfg.vocab, toks.shape[0]), toks),
+                                    dtype=np.int32)
+        t0 = time.perf_counter(); sm = A.sam_build(toks, cfg.sep); t1 = time.perf_counter()
+        A.sam_flatten([sm]); t2 = time.perf_counter()
+        bld = A.SamBuilder()
+        t3 = time.perf_counter(); bld.submit(1, toks, cfg.sep); t4 = time.perf_counter()
+        bld.wait(1); t5 = time.perf_counter()
+        bld.close()
+        out[name] = {"tokens": int(toks.shape[0]), "build_ms": (t1 - t0) * 1e3, "flatten_ms": (t2 - t1) * 1e3,
+                     "async_submit_ms": (t4 - t3) * 1e3, "async_ready_ms": (t5 - t3) * 1e3}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -332,6 +355,8 @@ def main():
         torch.cuda.synchronize()
         result["detail"]["t_draft_step_us"] = se0.elapsed_time(se1) / 20 * 1e3
         result["detail"]["draft_step_tokens_per_call"] = n_commit
+    if not args.attn_only:
+        result["detail"]["sam_prompt_build"] = measure_build(A, cfg)
     if args.maintain > 0:
         result["detail"]["sam_maintenance"] = measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx,
                                                                   args.maintain, dev)
