@@ -326,7 +326,7 @@ def main():
                    "sessions_per_s_sam_draft": (cfg.B / (t_draft * 1e-3)) if t_draft else None,
                    "accepted_tokens_per_s": float((accept_len + 1).sum()) / (ms_step * 1e-3),
                    "synthetic_OTE": float((accept_len + 1).mean()),
-                   "synthetic_SHR": (float(accept_len[nd_h > 0].sum()) / float(cfg.k * max(1, (nd_h > 0).sum()))),
+                   "synthetic_SHR": (float(accept_len[nd_h > 0].sum()) / float(max(1, cfg.k) * max(1, (nd_h > 0).sum()))),
                    "accept_hbm_GBs": (logits.numel() * logits.element_size() / (t_accept * 1e-3) / 1e9)
                    if t_accept else None,
                    "sam_build_tokens_per_s": sum(len(m) for m in mems) / t_build,
