@@ -142,3 +142,56 @@ def test_draft_step_argument_errors():
     assert call(cur=n) != 0                                   # missing carried-state arrays
     assert call(B=0, cur=n, arrays=n) == 0                    # an empty batch is a no-op
     torch.cuda.synchronize()
+
+
+def test_draft_step_edges_min_match_no_drafts_reset_and_empty_call():
+    """min_match above the carried length suppresses the proposal but not the state; k = 0 keeps only the
+    state; setting cur_len to 0 starts a session afresh; a call with no new tokens repeats the proposal."""
+    cfg = W.scaled(W.baseline_config(2), B=6, sam_sessions=4, sam_session_len=800, vocab=500, m=32, k=5)
+    rng = np.random.default_rng(8)
+    T = list(W.token_memory(cfg))
+    sams = [A.sam_build(np.asarray(T, np.int32), cfg.sep)]
+    flat = A.sam_flatten(sams)
+    fd = flat.to(DEV)
+    root = np.full(cfg.B, flat.roots[0], np.int32)
+    cend = np.full(cfg.B, flat.corpus_end[0], np.int32)
+    cur_state = torch.full((cfg.B,), -1, dtype=torch.int32, device=DEV)
+    cur_len = torch.zeros((cfg.B,), dtype=torch.int32, device=DEV)
+    # every session consumes a span of the memory of a different length (1 .. 6 tokens, no separator inside)
+    ctxs, tok = [], np.zeros((cfg.B, 8), np.int32)
+    for b in range(cfg.B):
+        while True:
+            p = int(rng.integers(0, len(T) - 40))
+            span = T[p:p + b + 1]
+            if cfg.sep not in T[p:p + 20]:
+                break
+        ctxs.append(list(span)); tok[b, :b + 1] = span
+    n_new = np.arange(1, cfg.B + 1, dtype=np.int32)
+    min_match = 4
+    d, nd, ml, me = (to_np(x) for x in A.sam_draft_step(fd, root, cend, tok, n_new, cur_state, cur_len, cfg.k, cfg.sep,
+                                                         min_match=min_match))
+    torch.cuda.synchronize()
+    cl = to_np(cur_len)
+    for b in range(cfg.B):
+        L, od, ond, oml, ome = draft_step_oracle(np.asarray(T, np.int32), np.asarray(ctxs[b], np.int32), 0, b + 1, cfg.k,
+                                                 cfg.sep, min_match)
+        assert int(cl[b]) == L == b + 1                       # the whole span matches
+        assert (int(nd[b]), int(ml[b]), int(me[b])) == (ond, oml, ome) and list(d[b, :ond]) == list(od[:ond])
+        if b + 1 < min_match:
+            assert nd[b] == 0 and ml[b] == 0 and me[b] == -1   # too short a match proposes nothing
+    # no new tokens, no drafts asked for: the state stays, the outputs are those of k = 0
+    zero = np.zeros(cfg.B, np.int32)
+    before = (to_np(cur_state).copy(), to_np(cur_len).copy())
+    d0, nd0, ml0, me0 = A.sam_draft_step(fd, root, cend, tok, zero, cur_state, cur_len, 0, cfg.sep)
+    torch.cuda.synchronize()
+    assert d0.shape == (cfg.B, 0) and (to_np(nd0) == 0).all()
+    assert np.array_equal(to_np(cur_state), before[0]) and np.array_equal(to_np(cur_len), before[1])
+    assert np.array_equal(to_np(ml0), np.arange(1, cfg.B + 1))    # min_match 1: every carried match counts
+    # session 2 starts afresh: its next token is matched from the root
+    cur_len[2] = 0
+    one = np.zeros(cfg.B, np.int32); one[2] = 1
+    tok2 = np.zeros((cfg.B, 1), np.int32); tok2[2, 0] = ctxs[2][0]
+    A.sam_draft_step(fd, root, cend, tok2, one, cur_state, cur_len, cfg.k, cfg.sep)
+    torch.cuda.synchronize()
+    cl = to_np(cur_len)
+    assert cl[2] == 1 and np.array_equal(np.delete(cl, 2), np.delete(before[1], 2))
