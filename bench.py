@@ -355,6 +355,20 @@ def main():
         torch.cuda.synchronize()
         result["detail"]["t_draft_step_us"] = se0.elapsed_time(se1) / 20 * 1e3
         result["detail"]["draft_step_tokens_per_call"] = n_commit
+        # the whole step with the stateful lookup in place of the window lookup (not the headline: the hot
+        # path is defined with the stateless one)
+        def step_stateful():
+            d, nd, _, _ = A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
+            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)
+            return A.spec_accept(logits, d, nd)
+        for _ in range(3):
+            step_stateful()
+        torch.cuda.synchronize()
+        t0s = time.perf_counter()
+        for _ in range(args.steps):
+            step_stateful()
+        torch.cuda.synchronize()
+        result["detail"]["ms_per_step_with_draft_step"] = (time.perf_counter() - t0s) / args.steps * 1e3
     if not args.attn_only:
         result["detail"]["sam_prompt_build"] = measure_build(A, cfg)
     if args.maintain > 0:

@@ -190,7 +190,9 @@ int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32
  *                              cur_state also means a fresh session).  Otherwise the pair must be
  *                              what this entry point wrote for the same automaton, which may have
  *                              grown since (sam_append + sam_apply_delta): a state that was split
- *                              meanwhile is followed to the clone that now holds the string.
+ *                              meanwhile is followed to the clone that now holds the string.  State
+ *                              ids are creation order + state_base, so the pair stays valid across a
+ *                              new sam_flatten as long as the automaton keeps its state_base.
  *   new_tok[B,max_new], n_new[B]   device: the tokens to consume, oldest first (n_new clipped to
  *                              [0,max_new]; no limit on max_new).
  * Definition of the carried length after token t_n, with the memory as it is at the call:
