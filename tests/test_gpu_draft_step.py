@@ -195,3 +195,56 @@ def test_draft_step_edges_min_match_no_drafts_reset_and_empty_call():
     torch.cuda.synchronize()
     cl = to_np(cur_len)
     assert cl[2] == 1 and np.array_equal(np.delete(cl, 2), np.delete(before[1], 2))
+
+
+@pytest.mark.parametrize("i", [2, 4])
+def test_draft_step_full_size_memory(i):
+    """The baseline workloads' full-size memories (workload 2: one 256k-token automaton for all sessions;
+    workload 4: 1M tokens, long repeats): the window as the first call, then what a step commits."""
+    from _util import draft_inputs, make_memories
+    cfg = W.baseline_config(i)
+    mems = make_memories(cfg)
+    flat, root, cbeg, cend, recent, rlen = draft_inputs(cfg, mems)
+    fd = flat.to(DEV)
+    B = cfg.B
+    sample = list(range(0, B, max(1, B // 12)))               # the oracle scans the whole memory per candidate length
+    T = [np.asarray(mems[b if cfg.sam_mode == "per_session" else 0], np.int32) for b in range(B)]
+    cur_state = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+    cur_len = torch.zeros((B,), dtype=torch.int32, device=DEV)
+    tok = np.zeros((B, cfg.m), np.int32)
+    for b in range(B):
+        tok[b, :rlen[b]] = recent[b, cfg.m - rlen[b]:]
+    ctxs = [list(tok[b, :rlen[b]]) for b in range(B)]
+    L_prev = [0] * B
+    print(f"draft step full size {cfg.name}: first call", flush=True)
+    got = A.sam_draft_step(fd, root, cend, tok, rlen, cur_state, cur_len, cfg.k, cfg.sep)
+    torch.cuda.synchronize()
+    # on an unchanging memory the carried match of the window is what the window lookup finds
+    ref = A.sam_draft(fd, root, cend, recent, rlen, cfg.k, cfg.sep)
+    torch.cuda.synchronize()
+    for x, y in zip(got, ref):
+        assert torch.equal(x, y)
+    d, nd = to_np(got[0]), to_np(got[1])
+    cl, ml, me = to_np(cur_len), to_np(got[2]), to_np(got[3])
+    for b in sample:
+        L, od, ond, oml, ome = draft_step_oracle(T[b], np.asarray(ctxs[b], np.int32), 0, len(ctxs[b]), cfg.k, cfg.sep, 1)
+        assert (int(cl[b]), int(ml[b]), int(nd[b])) == (L, oml, ond), b
+        assert (int(me[b]) - int(cbeg[b]) if me[b] >= 0 else -1) == ome and list(d[b, :ond]) == list(od[:ond])
+        L_prev[b] = L
+    # second call: the first drafts are accepted, then a token that breaks the match
+    rng = np.random.default_rng(cfg.seed + 17)
+    new = [[int(t) for t in d[b, :min(int(nd[b]), 3)]] + [int(rng.integers(0, cfg.vocab))] for b in range(B)]
+    tok2 = np.zeros((B, 4), np.int32)
+    n2 = np.array([len(x) for x in new], np.int32)
+    for b in range(B):
+        tok2[b, :len(new[b])] = new[b]
+        ctxs[b] += new[b]
+    print(f"draft step full size {cfg.name}: second call", flush=True)
+    got = A.sam_draft_step(fd, root, cend, tok2, n2, cur_state, cur_len, cfg.k, cfg.sep)
+    torch.cuda.synchronize()
+    d, nd, ml, me = (to_np(x) for x in got)
+    cl = to_np(cur_len)
+    for b in sample:
+        L, od, ond, oml, ome = draft_step_oracle(T[b], np.asarray(ctxs[b], np.int32), L_prev[b], int(n2[b]), cfg.k, cfg.sep, 1)
+        assert (int(cl[b]), int(ml[b]), int(nd[b])) == (L, oml, ond), b
+        assert (int(me[b]) - int(cbeg[b]) if me[b] >= 0 else -1) == ome and list(d[b, :ond]) == list(od[:ond])
