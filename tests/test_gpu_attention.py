@@ -110,6 +110,29 @@ def test_bf16_small_balanced_schedule(case):
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
+# (G, k): the packed-row counts at which the kernel variant changes (narrow <= 48 < wide: 16 / 16+extra / 32 /
+# 32+extra / 48 rows per wavefront) and the largest supported, 192
+ROW_BOUNDARIES = [(7, 6), (8, 7), (13, 4), (8, 9), (9, 8), (8, 15), (43, 2), (16, 8), (29, 4), (16, 11)]
+
+
+@pytest.mark.parametrize("G,k", ROW_BOUNDARIES)
+def test_bf16_row_count_boundaries(G, k):
+    cfg = W.scaled(W.baseline_config(1), B=2, Hq=G, Hkv=1, D=128, k=k, kv_mode="ragged", kv_len=(k + 2, 1500),
+                   permute_pages=True)
+    print(f"attn bf16 rows {G * (k + 1)} (G={G}, k={k})", flush=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
+def test_bf16_more_than_192_rows_is_refused():
+    cfg = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=1, D=128, k=24, kv_mode="fixed", kv_len=(256, 256))
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    with pytest.raises(A.AgentSamError):
+        A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+
+
 @pytest.mark.parametrize("k,Hq,B", [(8, 32, 70), (16, 64, 130)])
 def test_bf16_many_short_sessions_balanced(k, Hq, B):
     """Enough (session, kv head) streams that the balanced schedule is chosen by itself, with streams
