@@ -110,9 +110,10 @@ def test_bf16_small_balanced_schedule(case):
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
-# (G, k): the packed-row counts at which the kernel variant changes (narrow <= 48 < wide: 16 / 16+extra / 32 /
-# 32+extra / 48 rows per wavefront) and the largest supported, 192
-ROW_BOUNDARIES = [(7, 6), (8, 7), (13, 4), (8, 9), (9, 8), (8, 15), (43, 2), (16, 8), (29, 4), (16, 11)]
+# (G, k): the packed-row counts at which the kernel variant changes (narrow: 16 / 32 / 48 rows; wide: 16 / 16+extra /
+# 32 / 32+extra / 48 rows per wavefront) and the largest supported, 192
+ROW_BOUNDARIES = [(4, 3), (17, 0), (8, 3), (11, 2), (8, 5),                                    # 16, 17, 32, 33, 48
+                  (7, 6), (8, 7), (13, 4), (8, 9), (9, 8), (8, 15), (43, 2), (16, 8), (29, 4), (16, 11)]
 
 
 @pytest.mark.parametrize("G,k", ROW_BOUNDARIES)
