@@ -65,6 +65,24 @@ def test_fp32_ragged_multi_chunk_and_d128():
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
+@pytest.mark.parametrize("k,D", [(0, 64), (31, 64), (31, 128)])
+def test_fp32_fewest_and_most_query_rows(k, D):
+    """fp32 storage: one query row (plain decoding) and the largest supported number, 32."""
+    cfg = W.scaled(W.baseline_config(0), B=2, Hq=2, Hkv=1, D=D, page=16, k=k, kv_mode="ragged", kv_len=(k + 2, 700),
+                   permute_pages=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
+def test_fp32_more_than_32_query_rows_is_refused():
+    cfg = W.scaled(W.baseline_config(0), B=1, Hq=1, Hkv=1, D=64, page=16, k=32, kv_mode="fixed", kv_len=(128, 128))
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    with pytest.raises(A.AgentSamError):
+        A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+
+
 BF16_SMALL = [
     # several tiles per wavefront, ragged tails, every packed-row tile count, both head dims
     dict(B=3, Hq=8, Hkv=2, D=128, k=8, kv_mode="ragged", kv_len=(9, 3000), permute_pages=True),     # 36 rows
