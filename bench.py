@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (5 times): a kernel of known HBM traffic "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with")
+    ap.add_argument("--cold", action="store_true",
+                    help="write a 512 MiB scratch buffer before every step (outside the timed events), so that nothing of "
+                         "the previous step is left in the caches; ms_per_step is then the sum of the kernels' event times")
     ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
                     help="override a workload field (experiments only), e.g. --set permute_pages=False")
     return ap.parse_args()
@@ -252,7 +255,11 @@ def main():
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
+    flush = torch.zeros(128 << 20, dtype=torch.float32, device=dev) if args.cold else None
+
     def step(events=None):
+        if flush is not None:
+            flush.add_(1.0)
         if not args.attn_only:
             if events: events[0].record()
             d, nd, ml, me = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
@@ -275,6 +282,9 @@ def main():
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_step = t_total / args.steps * 1e3
+    if args.cold:                                             # the flush kernel is not part of the step
+        first, last = (1, 2) if args.attn_only else (0, 3)
+        ms_step = float(np.mean([e[first].elapsed_time(e[last]) for e in evs]))
 
     t_attn = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))             # ms, whole call
     if args.attn_only:
@@ -315,7 +325,8 @@ def main():
         "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "head_dim": cfg.D,
                    "kv_len": [int(lay.seq_lens.min()), int(lay.seq_lens.max())], "page": cfg.page, "k": cfg.k,
                    "sam_tokens": int(sum(len(m) for m in mems)), "vocab": cfg.vocab,
-                   "step": "sam_draft + spec_verify_attn + spec_accept", "attn_only": bool(args.attn_only)},
+                   "step": "sam_draft + spec_verify_attn + spec_accept", "attn_only": bool(args.attn_only),
+                   "cold_caches": bool(args.cold)},
         "roofline": {"bound": "hbm", "kernel": "spec_verify_attn", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "algorithmic_bytes": alg_bytes,
