@@ -788,6 +788,9 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
 //     references to the exact row maxima, then a final pass;
 //   - registers stay under 256 so that two workgroups share a compute unit and one's wavefront
 //     fills the other's stalls; one workgroup barrier per tile publishes the tile.
+// AGENTSAM_EXP_NO_DMA / AGENTSAM_EXP_NO_COMPUTE / AGENTSAM_EXP_NS (never defined by the build script) cut the
+// tile requests or the arithmetic out of the loop, or change the ring depth, to time the two halves
+// apart; results are then meaningless.
 template <int D>
 struct WideCfg {
     static constexpr int kRowBytes = D * 2;
