@@ -145,6 +145,24 @@ def test_bf16_row_count_boundaries(G, k):
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
+@pytest.mark.parametrize("G,k,sched", [(4, 8, 0), (8, 16, 2), (8, 23, 1), (4, 8, 2)])
+def test_bf16_results_repeat_bit_for_bit(G, k, sched):
+    """The same call twenty times: every launch gives the same bits (no race in the tile rings, no
+    order-dependent merge)."""
+    cfg = W.scaled(W.baseline_config(1), B=24, Hq=2 * G, Hkv=2, D=128, k=k, kv_mode="ragged", kv_len=(k + 2, 6000),
+                   permute_pages=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    A.agentsam_set_option("attn_schedule", sched)
+    try:
+        first = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D)).clone()
+        for _ in range(20):
+            again = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+            assert torch.equal(again, first)
+        torch.cuda.synchronize()
+    finally:
+        A.agentsam_set_option("attn_schedule", 0)
+
+
 def test_bf16_more_than_192_rows_is_refused():
     cfg = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=1, D=128, k=24, kv_mode="fixed", kv_len=(256, 256))
     lay, q, kc, vc, bt, seq = _inputs(cfg)
