@@ -380,6 +380,24 @@ def main():
             step_stateful()
         torch.cuda.synchronize()
         result["detail"]["ms_per_step_with_draft_step"] = (time.perf_counter() - t0s) / args.steps * 1e3
+    if not args.cold:
+        # the same step recorded once into a HIP graph and replayed (no host work between its kernels)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        result["detail"]["ms_per_step_graph"] = (time.perf_counter() - tg0) / args.steps * 1e3
     if not args.attn_only:
         result["detail"]["sam_prompt_build"] = measure_build(A, cfg)
     if args.maintain > 0:
