@@ -13,11 +13,23 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("shape", [dict(B=8, Hq=8, Hkv=2, k=8, kv_len=(64, 5000)),            # narrow kernel, chunk grid + merge
-                                   dict(B=40, Hq=16, Hkv=2, k=16, kv_len=(40, 3000))])       # wide kernel, balanced
+@pytest.mark.parametrize("shape", [
+    dict(B=8, Hq=8, Hkv=2, k=8, kv_len=(64, 5000), kv_mode="ragged", permute_pages=True),       # narrow kernel, chunk grid + merge
+    dict(B=40, Hq=16, Hkv=2, k=16, kv_len=(40, 3000), kv_mode="ragged", permute_pages=True),    # wide kernel, balanced
+    dict(B=6, Hq=10, Hkv=2, k=8, kv_len=(40, 700), kv_mode="shared_prefix", prefix_len=2048, cascade=2),   # shared-prefix run
+])
 def test_captured_step_replays_like_the_eager_step(shape):
-    cfg = W.scaled(W.baseline_config(1), D=128, kv_mode="ragged", permute_pages=True, sam_session_len=4096, vocab=4000,
-                   **shape)
+    shape = dict(shape)
+    cascade = shape.pop("cascade", 0)
+    cfg = W.scaled(W.baseline_config(1), D=128, sam_session_len=4096, vocab=4000, **shape)
+    A.agentsam_set_option("attn_cascade", cascade)
+    try:
+        _captured_step_case(cfg)
+    finally:
+        A.agentsam_set_option("attn_cascade", 0)
+
+
+def _captured_step_case(cfg):
     mems = make_memories(cfg)
     flat, root, cbeg, cend, recent, rlen = draft_inputs(cfg, mems)
     fd = flat.to(DEV)
