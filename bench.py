@@ -113,7 +113,7 @@ def cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h,
     }
 
 
-def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev):
+def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest=None):
     """Incremental maintenance of the device automaton: every round appends 2 tokens per session (about
     what a verified step commits) to the memories, exports the delta, updates the device copy and drafts
     from it.  Host times are wall clock, device times HIP events."""
@@ -123,7 +123,7 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev):
     sams = [A.sam_build(np.asarray(m, np.int32), cfg.sep) for m in mems]
     per_mem = 2 * cfg.B // len(mems)
     t0 = time.perf_counter()
-    flat = A.sam_flatten(sams, grow_tokens=per_mem * (steps + 1))
+    flat = A.sam_flatten(sams, grow_tokens=per_mem * (3 * steps + 1))
     t_flatten = time.perf_counter() - t0
     fd = flat.to(dev)
     mem_len = [len(m) for m in mems]
@@ -160,7 +160,67 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev):
         e2.record()
         torch.cuda.synchronize()
         t_dev.append(e0.elapsed_time(e1)); t_draft.append(e1.elapsed_time(e2))
-    return {"rounds": steps, "tokens_appended_per_round": per_mem * len(mems),
+    res_rounds = {}
+    if rest is not None:
+        # Whole rounds, wall clock: (a) one thing after the other; (b) the step is launched first, the host
+        # appends and exports while the GPU runs it, and the device copy is updated on a second stream as soon
+        # as the step's lookup has finished, next to the attention (Sec. 5.4.2: maintenance off the decoding path).
+        def host_part():
+            for i, T in enumerate(mems):
+                p = int(rng.integers(0, max(1, len(T) - per_mem)))
+                add = [x for x in T[p:p + per_mem] if x != cfg.sep] or [0]
+                A.sam_append(sams[i], np.asarray(add, np.int32))
+                T += add
+            n = sum(A.sam_delta_sizes(s)[2] for s in sams)
+            cap = 2
+            while cap < 2 * n:
+                cap *= 2
+            keys, dsts = A.overlay_table(cap)
+            return keys, dsts, [A.sam_delta_export(s, keys, dsts, int(flat.roots[i]), int(flat.corpus_begin[i]))
+                                for i, s in enumerate(sams)]
+
+        def up(a):                                            # pinned staging: the copy is a DMA on the current stream
+            return torch.from_numpy(np.ascontiguousarray(a)).pin_memory().to(dev, non_blocking=True)
+
+        def device_part(keys, dsts, deltas):
+            import dataclasses
+            for i, d in enumerate(deltas):
+                dd = dataclasses.replace(d, rec_idx=up(d.rec_idx), rec_val=up(d.rec_val), lastpos_idx=up(d.lastpos_idx),
+                                         lastpos_val=up(d.lastpos_val))
+                A.sam_apply_delta(dd, fd.state_rec, fd.lastpos)
+                n = d.new_tokens.shape[0]
+                at = int(flat.corpus_begin[i]) + mem_len[i]
+                fd.corpus[at:at + n] = up(d.new_tokens)
+                mem_len[i] += n
+            return (up(keys.view(np.int64)), up(dsts),
+                    up((flat.corpus_begin + np.asarray(mem_len))[idx].astype(np.int32)))
+
+        state = [keys_d, dsts_d, cend_d]
+        main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        for mode in ("sequential", "overlapped"):
+            torch.cuda.synchronize()
+            tr0 = time.perf_counter()
+            for _ in range(steps):
+                if mode == "sequential":
+                    state = list(device_part(*host_part()))
+                    d, nd, _, _ = A.sam_draft_delta(fd, state[0], state[1], rows_end_d, root_d, state[2], recent_d, rlen_d,
+                                                    cfg.k, cfg.sep)
+                    rest(d, nd)
+                    torch.cuda.synchronize()
+                else:
+                    d, nd, _, _ = A.sam_draft_delta(fd, state[0], state[1], rows_end_d, root_d, state[2], recent_d, rlen_d,
+                                                    cfg.k, cfg.sep)
+                    looked_up = torch.cuda.Event()
+                    looked_up.record(main)
+                    rest(d, nd)                               # attention + accept, queued behind the lookup
+                    hp = host_part()                          # the GPU is busy with the step meanwhile
+                    with torch.cuda.stream(side):
+                        side.wait_event(looked_up)            # the lookup must not see a half-updated copy
+                        state = list(device_part(*hp))
+                    main.wait_stream(side)                    # the next lookup sees the whole update
+            torch.cuda.synchronize()
+            res_rounds["round_ms_" + mode] = (time.perf_counter() - tr0) / steps * 1e3
+    return {"rounds": steps, "tokens_appended_per_round": per_mem * len(mems), **res_rounds,
             "host_append_and_export_us": float(np.median(t_host)) * 1e6,
             "device_update_us_incl_uploads": float(np.median(t_dev)) * 1e3,
             "t_draft_delta_us": float(np.median(t_draft)) * 1e3,
@@ -401,8 +461,11 @@ def main():
     if not args.attn_only:
         result["detail"]["sam_prompt_build"] = measure_build(A, cfg)
     if args.maintain > 0:
+        def rest(d, nd):
+            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)
+            A.spec_accept(logits, d, nd)
         result["detail"]["sam_maintenance"] = measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx,
-                                                                  args.maintain, dev)
+                                                                  args.maintain, dev, rest)
     if not args.no_cpu_baseline and not args.attn_only:
         result["cpu_baseline"] = cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h)
     else:
