@@ -99,3 +99,51 @@ def test_maintained_copy_on_device_matches_oracle(shared):
                                     recent, rlen, cfg.k, cfg.sep)
     torch.cuda.synchronize()
     assert np.array_equal(to_np(d2), d) and np.array_equal(to_np(ml2), ml) and np.array_equal(to_np(nd2), nd)
+
+
+def test_update_on_a_second_stream_next_to_other_work():
+    """The device copy is updated on a second stream while the first is busy: ordered by one event (the
+    round's lookup has finished) and one stream wait (the next lookup sees the whole update)."""
+    cfg = W.scaled(W.baseline_config(2), B=16, sam_sessions=4, sam_session_len=1200, vocab=1500, m=32, k=8)
+    rng = np.random.default_rng(99)
+    mems = [list(W.token_memory(cfg))]
+    owner = [0] * cfg.B
+    sams = [A.sam_build(np.asarray(T, np.int32), cfg.sep) for T in mems]
+    flat = A.sam_flatten(sams, grow_tokens=2000)
+    fd = flat.to(DEV)
+    mem_len = [len(T) for T in mems]
+    root = torch.as_tensor(np.array([flat.roots[0]] * cfg.B, np.int32), device=DEV)
+    rows_end = torch.as_tensor(np.array([flat.rows_end[0]] * cfg.B, np.int32), device=DEV)
+    keys, dsts = _sync(sams, fd, flat, mem_len)
+    cend = torch.as_tensor(np.array([int(flat.corpus_begin[0]) + mem_len[0]] * cfg.B, np.int32), device=DEV)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    busy_a = torch.randn(2048, 2048, device=DEV)
+    pending = []
+    for rnd in range(8):
+        recent, rlen = _windows(rng, mems, owner, cfg.m, cfg.vocab)
+        got = A.sam_draft_delta(fd, keys, dsts, rows_end, root, cend, torch.as_tensor(recent, device=DEV),
+                                torch.as_tensor(rlen, device=DEV), cfg.k, cfg.sep)
+        looked_up = torch.cuda.Event()
+        looked_up.record(main)
+        for _ in range(6):                                    # stands in for the attention of the step
+            busy_a = torch.tanh(busy_a @ busy_a * 1e-3)
+        pending.append((got, recent, rlen, [list(T) for T in mems]))
+        add = []
+        for _ in range(3):
+            p = int(rng.integers(0, len(mems[0]) - 30)); add += mems[0][p:p + int(rng.integers(2, 25))]
+        add += [int(x) for x in rng.integers(0, cfg.vocab, 3)]
+        A.sam_append(sams[0], np.asarray(add, np.int32))
+        mems[0] += add
+        with torch.cuda.stream(side):
+            side.wait_event(looked_up)
+            keys, dsts = _sync(sams, fd, flat, mem_len)
+            cend = torch.as_tensor(np.array([int(flat.corpus_begin[0]) + mem_len[0]] * cfg.B, np.int32), device=DEV)
+        main.wait_stream(side)
+    torch.cuda.synchronize()
+    for (d, nd, ml, me), recent, rlen, snap in pending:       # every round's lookup saw exactly its own memory
+        d, nd, ml, me = to_np(d), to_np(nd), to_np(ml), to_np(me)
+        for b in range(cfg.B):
+            od, ond, oml, ome = draft_oracle(np.asarray(snap[0], np.int32), recent[b, cfg.m - rlen[b]:], cfg.k, cfg.sep, 1)
+            got_end = int(me[b]) - int(flat.corpus_begin[0]) if me[b] >= 0 else -1
+            assert (int(ml[b]), got_end, int(nd[b])) == (oml, ome, ond)
+            assert list(d[b, :ond]) == list(od[:ond])
