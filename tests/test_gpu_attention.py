@@ -163,6 +163,42 @@ def test_bf16_results_repeat_bit_for_bit(G, k, sched):
         A.agentsam_set_option("attn_schedule", 0)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_bf16_seeded_random_shapes(seed):
+    """Shapes, lengths, page sizes and schedules drawn from a seeded generator: every output against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    D = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 5, 8, 12]))
+    k = int(rng.integers(0, min(24, 192 // G - 1) + 1))
+    B = int(rng.choice([1, 2, 5, 9, 33]))
+    page = int(rng.choice([32, 64, 128]))
+    lo = k + 1 + int(rng.integers(0, 40))
+    hi = lo + int(rng.choice([0, 31, 200, 1500, 4000]))
+    mode = str(rng.choice(["ragged", "fixed", "shared_prefix"]))
+    kw = dict(B=B, Hq=G * Hkv, Hkv=Hkv, D=D, k=k, page=page, kv_mode=mode, kv_len=(lo, hi), permute_pages=bool(rng.integers(0, 2)))
+    if mode == "shared_prefix":
+        kw["prefix_len"] = page * int(rng.integers(1, 12))
+    if mode == "fixed":
+        kw["kv_len"] = (hi, hi)
+    cfg = W.scaled(W.baseline_config(1), **kw)
+    sched, casc = int(rng.integers(0, 3)), int(rng.choice([0, 1, 2]))
+    print(f"attn random shape {seed}: {kw} schedule {sched} cascade {casc}", flush=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    A.agentsam_set_option("attn_schedule", sched)
+    A.agentsam_set_option("attn_cascade", casc)
+    try:
+        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+        torch.cuda.synchronize()
+    finally:
+        A.agentsam_set_option("attn_schedule", 0)
+        A.agentsam_set_option("attn_cascade", 0)
+    pairs = _all_pairs(cfg)
+    if len(pairs) > 60:
+        pairs = [pairs[i] for i in rng.choice(len(pairs), 60, replace=False)]
+    _check(cfg, lay, q, kc, vc, out, pairs, dominated=True)
+
+
 def test_bf16_more_than_192_rows_is_refused():
     cfg = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=1, D=128, k=24, kv_mode="fixed", kv_len=(256, 256))
     lay, q, kc, vc, bt, seq = _inputs(cfg)
