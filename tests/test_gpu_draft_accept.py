@@ -63,6 +63,20 @@ def test_sam_draft_edge_cases():
     # a root wider than 64 transitions per probe round is covered by the full-size cases (vocab 32000+)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_sam_draft_seeded_random_memories(seed):
+    """Memory shape, vocabulary, repetitiveness, window and draft lengths drawn from a seeded generator."""
+    rng = np.random.default_rng(500 + seed)
+    kw = dict(B=int(rng.choice([1, 3, 17, 40])), vocab=int(rng.choice([2, 5, 70, 3000, 60000])),
+              zipf_s=float(rng.choice([0.0, 1.1])), copy_frac=float(rng.choice([0.0, 0.3, 0.8])),
+              span=(int(rng.integers(2, 9)), int(rng.integers(9, 200))),
+              sam_mode=str(rng.choice(["per_session", "shared"])), sam_sessions=int(rng.integers(1, 6)),
+              sam_session_len=int(rng.choice([40, 700, 6000])), m=int(rng.choice([1, 7, 32, 64])),
+              k=int(rng.choice([0, 1, 8, 33, 64])))
+    print(f"sam_draft random memory {seed}: {kw}", flush=True)
+    _run_draft(W.scaled(W.baseline_config(1), **kw), min_match=int(rng.choice([1, 1, 3])))
+
+
 def test_sam_draft_empty_memory():
     s = A.sam_build([], sep_token=5)
     fd = A.sam_flatten([s]).to(DEV)
