@@ -371,7 +371,7 @@ extern "C" int sam_apply_delta(const int32_t *rec_idx, const int32_t *rec_val, i
 namespace {
 __global__ __launch_bounds__(64) void sam_select_kernel(const float *__restrict__ weight, const int32_t *__restrict__ c_draft,
                                                         const int32_t *__restrict__ c_n, const int32_t *__restrict__ c_len,
-                                                        const int32_t *__restrict__ c_end, int B, int M, int k,
+                                                        const int32_t *__restrict__ c_end, int /*B*/, int M, int k,
                                                         int32_t *__restrict__ draft, int32_t *__restrict__ n_draft,
                                                         int32_t *__restrict__ match_len, int32_t *__restrict__ match_end,
                                                         int32_t *__restrict__ source) {
