@@ -17,8 +17,11 @@ code.
                speculation switch                            [Alg. 3; Alg. 4 step 4]
 
 Every function is pinned by tests that run without a GPU (worked examples,
-closed forms, invariants, an independent brute force, library special cases);
-none is "parity unpinned".
+closed forms, invariants, an independent brute force, library special cases),
+with one exception: the choice among several weighted memories in
+merged_draft_oracle follows a rule of this build (the paper names the merge
+and its weights but prints no rule), so that rule is "parity unpinned"; the
+per-memory drafts it chooses among are draft_oracle's and pinned as above.
 """
 from .draft import (  # noqa: F401
     draft_oracle, draft_oracle_batch, build_oracle_lib, merged_draft_oracle, carried_match_len_oracle, draft_step_oracle,

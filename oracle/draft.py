@@ -46,8 +46,8 @@ def draft_oracle_batch(T, mem_begin, mem_end, recent, recent_len, k: int, sep: i
 
 
 def merged_draft_oracle(memories, weights, q, k, sep, min_match=1):
-    """Several memories queried with one window (Alg. 4: MergeSAM with weights).  The paper prints no merge
-    rule; the reading checked here: every memory proposes as draft_oracle does, and the proposal with the
+    """Several memories queried with one window (Alg. 4: MergeSAM with weights).  PARITY UNPINNED as to the
+    rule: the paper prints no merge rule.  The reading checked here: every memory proposes as draft_oracle does, and the proposal with the
     largest weight * match_len is taken among memories with a positive weight that propose at least one
     token (equal scores: the longer match, then the earlier memory).  Scores are compared in float32, the
     precision the weights are given in.  Returns (draft, n_draft, match_len, match_end, source)."""
