@@ -156,7 +156,11 @@ void sam_free(sam_t *s);
  *   sam_draft_delta   device: sam_draft on a maintained copy.  A transition is looked up in the
  *                     state's record, then in the overlay, then - for states below rows_end[b], the
  *                     end of the state-id range that has flattened rows in session b's automaton -
- *                     in the flattened row.  Same outputs and limits as sam_draft.
+ *                     in the flattened row.  Same outputs and limits as sam_draft.  wide_table /
+ *                     wide_slots (optional, NULL / 0: none): what sam_wide_table wrote at or after
+ *                     the last sam_flatten; the flattened rows with more than 64 transitions (as
+ *                     row_ptr tells) are then looked up there instead of being searched.  It need
+ *                     not follow later appends: the overlay is asked first.
  * ---------------------------------------------------------------------------------------- */
 int sam_delta_sizes(const sam_t *s, int64_t *n_rec, int64_t *n_lastpos, int64_t *n_overlay,
                     int64_t *n_new_tokens, int64_t *flat_states);
@@ -176,7 +180,7 @@ int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32
                     const int32_t *recent, const int32_t *recent_len,
                     int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
                     int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
-                    void *stream);
+                    const int32_t *wide_table, int64_t wide_slots, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * sam_draft_step: sam_draft with the matched state carried from call to call (Alg. 4, the decoding
@@ -203,7 +207,7 @@ int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32
  * The proposal is the one sam_draft makes for a window of exactly those L_n tokens; outputs as
  * sam_draft.  Automaton arrays as sam_draft (overlay_key NULL: a flattened automaton, wide_table
  * optional) or as sam_draft_delta (overlay_key, overlay_dst, overlay_cap, rows_end given: a
- * maintained copy; wide_table must then be NULL).
+ * maintained copy; wide_table optional, as there).
  * ---------------------------------------------------------------------------------------- */
 int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
                    const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,

@@ -74,7 +74,7 @@ def lib():
         L.sam_delta_export.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32] + [_vp] * 6 + [ctypes.c_int64, _vp]
         L.sam_apply_delta.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
         L.sam_draft_delta.argtypes = ([_vp] * 8 + [ctypes.c_int64] + [_vp] * 5 + [ctypes.c_int32] * 5 +
-                                      [_vp] * 4 + [_vp])
+                                      [_vp] * 4 + [_vp, ctypes.c_int64, _vp])
         L.sam_draft_step.argtypes = ([_vp] * 8 + [ctypes.c_int64, _vp, _vp, ctypes.c_int64] + [_vp] * 4 +
                                      [ctypes.c_int32] * 5 + [_vp] * 6 + [_vp])
         L.spec_verify_attn_workspace.argtypes = [ctypes.c_int32] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
@@ -353,13 +353,15 @@ def sam_apply_delta(delta: SamDelta, state_rec, lastpos) -> None:
 
 
 def sam_draft_delta(flat: FlatSam, overlay_key, overlay_dst, rows_end, root, corpus_end, recent, recent_len, k: int,
-                    sep_token: int, min_match: int = 1):
-    """sam_draft on a maintained device copy; overlay_key is a device int64/uint64 tensor, overlay_dst int32."""
+                    sep_token: int, min_match: int = 1, use_wide_table: bool = True):
+    """sam_draft on a maintained device copy; overlay_key is a device int64/uint64 tensor, overlay_dst int32.
+    flat.wide_table (written when the automaton was flattened) serves the long flattened rows."""
     import torch
     dev = flat.state_rec.device
     root, corpus_end, rows_end = _dev_i32(root, dev), _dev_i32(corpus_end, dev), _dev_i32(rows_end, dev)
     recent, recent_len = _dev_i32(recent, dev), _dev_i32(recent_len, dev)
     B, m = recent.shape
+    wt = flat.wide_table if use_wide_table else None
     draft = torch.empty((B, k), dtype=torch.int32, device=dev)
     n_draft = torch.empty((B,), dtype=torch.int32, device=dev)
     match_len = torch.empty((B,), dtype=torch.int32, device=dev)
@@ -369,6 +371,7 @@ def sam_draft_delta(flat: FlatSam, overlay_key, overlay_dst, rows_end, root, cor
                                overlay_key.numel(), _dp(rows_end), _dp(root), _dp(corpus_end), _dp(recent),
                                _dp(recent_len), B, m, k, min_match, sep_token,
                                _dp(draft) if k > 0 else _vp(0), _dp(n_draft), _dp(match_len), _dp(match_end),
+                               _dp(wt) if wt is not None else _vp(0), (wt.numel() // 4) if wt is not None else 0,
                                _stream_ptr())
     _check(rc, "sam_draft_delta")
     return draft, n_draft, match_len, match_end
@@ -390,7 +393,7 @@ def sam_draft_step(flat: FlatSam, root, corpus_end, new_tok, n_new, cur_state, c
     maintained = overlay_key is not None
     if maintained:
         rows_end = _dev_i32(rows_end, dev)
-    wt = None if maintained or not use_wide_table else flat.wide_table
+    wt = flat.wide_table if use_wide_table else None
     draft = torch.empty((B, k), dtype=torch.int32, device=dev)
     n_draft = torch.empty((B,), dtype=torch.int32, device=dev)
     match_len = torch.empty((B,), dtype=torch.int32, device=dev)

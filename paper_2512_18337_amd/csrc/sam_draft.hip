@@ -120,15 +120,45 @@ __device__ __forceinline__ void consume_token(const FlatSam &A, const Overlay &o
             // flattened row (a transition may have been redirected to a clone), and only states
             // that existed at the last flatten have a row at all.
             dst = __builtin_amdgcn_readfirstlane(overlay_find(ov, s, c));
-            if (dst < 0 && s < __builtin_amdgcn_readfirstlane(A.rows_end[b]))
-                dst = __builtin_amdgcn_readfirstlane(
-                    find_edge(A.edge_tok, A.edge_dst, A.row_ptr[s], A.row_ptr[s + 1], c, lane));
+            if (dst < 0 && s < __builtin_amdgcn_readfirstlane(A.rows_end[b])) {
+                // The wide table mirrors the flattened rows of states that had more than
+                // AGENTSAM_WIDE_DEGREE transitions at the last flatten; a maintained record no longer
+                // carries that flag, the row's length still tells.
+                const int e0 = __builtin_amdgcn_readfirstlane(A.row_ptr[s]);
+                const int e1 = __builtin_amdgcn_readfirstlane(A.row_ptr[s + 1]);
+                if (wt.slot != nullptr && e1 - e0 > AGENTSAM_WIDE_DEGREE)
+                    dst = __builtin_amdgcn_readfirstlane(wide_find(wt, s, c));
+                else
+                    dst = __builtin_amdgcn_readfirstlane(find_edge(A.edge_tok, A.edge_dst, e0, e1, c, lane));
+            }
         }
         if (dst >= 0) { s = dst; ++l; return; }
         if (s == root) { l = 0; return; }
         s = __builtin_amdgcn_readfirstlane(rec.z);
         l = link_len(__builtin_amdgcn_readfirstlane(rec.w));
     }
+}
+
+// Is the root a state whose transitions are in the wide table?  (Then they are fetched ahead, one
+// window token per lane.)  Flattened automaton: the flag in its record; maintained copy: the
+// length of its flattened row.
+template <bool OVERLAY>
+__device__ __forceinline__ bool root_in_wide_table(const FlatSam &A, const WideTable &wt, int b, int root) {
+    if (wt.slot == nullptr) return false;
+    if (!OVERLAY) return __builtin_amdgcn_readfirstlane(A.state_rec[root].w) < 0;
+    if (root >= __builtin_amdgcn_readfirstlane(A.rows_end[b])) return false;
+    return __builtin_amdgcn_readfirstlane(A.row_ptr[root + 1]) - __builtin_amdgcn_readfirstlane(A.row_ptr[root]) >
+           AGENTSAM_WIDE_DEGREE;
+}
+
+// The root's transition on token c (per lane), for a root that root_in_wide_table() accepted.
+template <bool OVERLAY>
+__device__ __forceinline__ int root_transition(const Overlay &ov, const WideTable &wt, int root, int c) {
+    if (OVERLAY) {
+        const int d = overlay_find(ov, root, c);             // added or redirected since the last flatten
+        if (d >= 0) return d;
+    }
+    return wide_find(wt, root, c);
 }
 
 // The proposal of (state s, matched length l): the tokens that followed the most recent occurrence
@@ -191,8 +221,8 @@ __global__ __launch_bounds__(64) void sam_draft_kernel(
     // made most often.  When the root is a wide state, all 64 of them (one per window token) are
     // fetched up front, side by side, one per lane, and the walk takes them from a register.
     int root_next = -2;                                        // -2: not fetched
-    const bool root_ahead = !OVERLAY && wt.slot != nullptr && __builtin_amdgcn_readfirstlane(state_rec[root].w) < 0;
-    if (root_ahead) root_next = (lane < ql) ? wide_find(wt, root, wtok) : -1;
+    const bool root_ahead = root_in_wide_table<OVERLAY>(A, wt, b, root);
+    if (root_ahead) root_next = (lane < ql) ? root_transition<OVERLAY>(ov, wt, root, wtok) : -1;
 
     int s = __builtin_amdgcn_readfirstlane(root), l = 0;
     for (int t = 0; t < ql; ++t) {
@@ -228,12 +258,12 @@ __global__ __launch_bounds__(64) void sam_draft_step_kernel(
         s = __builtin_amdgcn_readfirstlane(rec.z);
     }
     const int nn = __builtin_amdgcn_readfirstlane(max(0, min(max_new, n_new[b])));
-    const bool root_wide = !OVERLAY && wt.slot != nullptr && __builtin_amdgcn_readfirstlane(A.state_rec[root].w) < 0;
+    const bool root_wide = root_in_wide_table<OVERLAY>(A, wt, b, root);
     for (int t0 = 0; t0 < nn; t0 += 64) {                    // 64 tokens at a time, one per lane
         const int cnt = min(64, nn - t0);
         const int wtok = (lane < cnt) ? new_tok[(int64_t)b * max_new + t0 + lane] : -1;
         int root_next = -2;
-        if (root_wide) root_next = (lane < cnt) ? wide_find(wt, root, wtok) : -1;
+        if (root_wide) root_next = (lane < cnt) ? root_transition<OVERLAY>(ov, wt, root, wtok) : -1;
         for (int t = 0; t < cnt; ++t) {
             const int c = __builtin_amdgcn_readlane(wtok, t);
             const int pref = root_wide ? __builtin_amdgcn_readlane(root_next, t) : -2;
@@ -280,9 +310,11 @@ extern "C" int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, 
                                const int32_t *recent, const int32_t *recent_len,
                                int32_t B, int32_t m, int32_t k, int32_t min_match, int32_t sep_token,
                                int32_t *draft, int32_t *n_draft, int32_t *match_len, int32_t *match_end,
-                               void *stream) {
+                               const int32_t *wide_table, int64_t wide_slots, void *stream) {
     if (B < 0 || m < 1 || m > 64 || k < 0 || k > 64 || min_match < 0) return AGENTSAM_ERR_ARG;
     if (overlay_cap < 2 || (overlay_cap & (overlay_cap - 1)) != 0 || overlay_cap > (1ll << 31)) return AGENTSAM_ERR_ARG;
+    if (wide_table && (wide_slots < 2 || (wide_slots & (wide_slots - 1)) != 0 || wide_slots > (1ll << 31)))
+        return AGENTSAM_ERR_ARG;
     if (B == 0) return AGENTSAM_OK;
     if (!row_ptr || !lastpos || !state_rec || !overlay_key || !overlay_dst || !rows_end || !root || !corpus_end ||
         !recent || !recent_len || !n_draft || !match_len || !match_end || (k > 0 && !draft))
@@ -291,7 +323,8 @@ extern "C" int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, 
     hipLaunchKernelGGL(sam_draft_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
                        row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
                        recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       draft, n_draft, match_len, match_end, ov, rows_end, WideTable{nullptr, 0u}, 1);
+                       draft, n_draft, match_len, match_end, ov, rows_end,
+                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, 1);
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }
@@ -312,23 +345,22 @@ extern "C" int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, c
         return AGENTSAM_ERR_ARG;
     if (wide_table && (wide_slots < 2 || (wide_slots & (wide_slots - 1)) != 0 || wide_slots > (1ll << 31)))
         return AGENTSAM_ERR_ARG;
-    if (maintained && wide_table) return AGENTSAM_ERR_ARG;   // the table is a snapshot of the last flatten
     if (B == 0) return AGENTSAM_OK;
     if (!row_ptr || !lastpos || !state_rec || !root || !corpus_end || !n_new || (max_new > 0 && !new_tok) ||
         !cur_state || !cur_len || !n_draft || !match_len || !match_end || (k > 0 && !draft))
         return AGENTSAM_ERR_NULL;
     if (maintained && (!overlay_dst || !rows_end)) return AGENTSAM_ERR_NULL;
     const FlatSam A{row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, rows_end};
+    const WideTable wt{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u};
     if (maintained) {
         const Overlay ov{(const unsigned long long *)overlay_key, overlay_dst, (unsigned)(overlay_cap - 1)};
         hipLaunchKernelGGL(sam_draft_step_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream, A, root,
                            corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state,
-                           cur_len, draft, n_draft, match_len, match_end, ov, WideTable{nullptr, 0u});
+                           cur_len, draft, n_draft, match_len, match_end, ov, wt);
     } else {
         hipLaunchKernelGGL(sam_draft_step_kernel<false>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream, A, root,
                            corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state,
-                           cur_len, draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u},
-                           WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u});
+                           cur_len, draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, wt);
     }
     AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;

@@ -78,7 +78,8 @@ def test_carried_state_on_a_flattened_automaton(wide):
     assert longest > 8                                        # the stream really carried long matches
 
 
-def test_carried_state_on_a_growing_memory():
+@pytest.mark.parametrize("wide", [True, False])      # long flattened rows through the hash table / searched
+def test_carried_state_on_a_growing_memory(wide):
     cfg = W.scaled(W.baseline_config(2), B=18, sam_sessions=1, sam_session_len=2500, vocab=1500, m=32, k=8,
                    sam_mode="per_session")
     rng = np.random.default_rng(303)
@@ -122,7 +123,7 @@ def test_carried_state_on_a_growing_memory():
             ctxs[b] += new[b]
         print(f"draft step on growing memory {step}: overlay capacity {keys.numel()}", flush=True)
         got = A.sam_draft_step(fd, root, cend, tok, n_new, cur_state, cur_len, cfg.k, cfg.sep,
-                               overlay_key=keys, overlay_dst=dsts, rows_end=rows_end)
+                               overlay_key=keys, overlay_dst=dsts, rows_end=rows_end, use_wide_table=wide)
         torch.cuda.synchronize()
         _check_step(step, mems, owner, ctxs, L_prev, n_new, got, cur_len, flat.corpus_begin, cfg.k, cfg.sep)
 

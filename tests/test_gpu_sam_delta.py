@@ -47,8 +47,9 @@ def _windows(rng, mems, owner, m, vocab):
     return recent, rlen
 
 
+@pytest.mark.parametrize("wide", [True, False])      # long flattened rows through the hash table / searched
 @pytest.mark.parametrize("shared", [True, False])
-def test_maintained_copy_on_device_matches_oracle(shared):
+def test_maintained_copy_on_device_matches_oracle(shared, wide):
     cfg = W.scaled(W.baseline_config(2), B=24, sam_sessions=6, sam_session_len=1500, vocab=2000, m=32, k=8)
     rng = np.random.default_rng(77 + int(shared))
     if shared:
@@ -83,7 +84,8 @@ def test_maintained_copy_on_device_matches_oracle(shared):
         rows_end = np.array([flat.rows_end[owner[b]] for b in range(cfg.B)], np.int32)
         recent, rlen = _windows(rng, mems, owner, cfg.m, cfg.vocab)
         print(f"maintained copy round {rnd}: overlay capacity {keys.numel()}", flush=True)
-        d, nd, ml, me = A.sam_draft_delta(fd, keys, dsts, rows_end, root, cend, recent, rlen, cfg.k, cfg.sep)
+        d, nd, ml, me = A.sam_draft_delta(fd, keys, dsts, rows_end, root, cend, recent, rlen, cfg.k, cfg.sep,
+                                          use_wide_table=wide)
         torch.cuda.synchronize()
         d, nd, ml, me = to_np(d), to_np(nd), to_np(ml), to_np(me)
         for b in range(cfg.B):
