@@ -149,3 +149,24 @@ def test_update_on_a_second_stream_next_to_other_work():
             got_end = int(me[b]) - int(flat.corpus_begin[0]) if me[b] >= 0 else -1
             assert (int(ml[b]), got_end, int(nd[b])) == (oml, ome, ond)
             assert list(d[b, :ond]) == list(od[:ond])
+
+
+def test_draft_delta_argument_errors():
+    """Bad sizes and missing arrays are refused on the host; nothing is launched."""
+    z = torch.zeros(8, dtype=torch.int32, device=DEV)
+    L = A.binding.lib()
+    p, n = A.binding._dp(z), A.binding._vp(0)
+
+    def call(B=1, m=4, k=2, cap=8, ov=p, wide=n, wide_slots=0, arrays=p):
+        return L.sam_draft_delta(arrays, arrays, arrays, arrays, arrays, arrays, ov, ov, cap, arrays, arrays, arrays,
+                                 arrays, arrays, B, m, k, 1, 9, arrays, arrays, arrays, arrays, wide, wide_slots, n)
+
+    assert call(cap=6) != 0                                   # overlay capacity not a power of two
+    assert call(cap=0) != 0
+    assert call(ov=n) != 0                                    # no overlay table
+    assert call(wide=p, wide_slots=6) != 0                    # wide table size not a power of two
+    assert call(wide=p, wide_slots=0) != 0
+    assert call(m=65) != 0 and call(k=65) != 0 and call(B=-1) != 0
+    assert call(arrays=n) != 0                                # missing automaton arrays
+    assert call(B=0, arrays=n) == 0                           # an empty batch is a no-op
+    torch.cuda.synchronize()
