@@ -123,7 +123,7 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
     sams = [A.sam_build(np.asarray(m, np.int32), cfg.sep) for m in mems]
     per_mem = 2 * cfg.B // len(mems)
     t0 = time.perf_counter()
-    flat = A.sam_flatten(sams, grow_tokens=per_mem * (3 * steps + 1))
+    flat = A.sam_flatten(sams, grow_tokens=per_mem * (4 * steps + 1))
     t_flatten = time.perf_counter() - t0
     fd = flat.to(dev)
     mem_len = [len(m) for m in mems]
@@ -197,7 +197,12 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
 
         state = [keys_d, dsts_d, cend_d]
         main, side = torch.cuda.current_stream(), torch.cuda.Stream()
-        for mode in ("sequential", "overlapped"):
+        # third mode: as "overlapped", with the lookup carrying its matched state (three tokens consumed per call)
+        new_tok_d = recent_d[:, -3:].contiguous()
+        n_new_d = torch.full((recent_d.shape[0],), 3, dtype=torch.int32, device=dev)
+        cur_state = torch.full((recent_d.shape[0],), -1, dtype=torch.int32, device=dev)
+        cur_len = torch.zeros((recent_d.shape[0],), dtype=torch.int32, device=dev)
+        for mode in ("sequential", "overlapped", "overlapped_carried_state"):
             torch.cuda.synchronize()
             tr0 = time.perf_counter()
             for _ in range(steps):
@@ -208,8 +213,13 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
                     rest(d, nd)
                     torch.cuda.synchronize()
                 else:
-                    d, nd, _, _ = A.sam_draft_delta(fd, state[0], state[1], rows_end_d, root_d, state[2], recent_d, rlen_d,
-                                                    cfg.k, cfg.sep)
+                    if mode == "overlapped":
+                        d, nd, _, _ = A.sam_draft_delta(fd, state[0], state[1], rows_end_d, root_d, state[2], recent_d,
+                                                        rlen_d, cfg.k, cfg.sep)
+                    else:
+                        d, nd, _, _ = A.sam_draft_step(fd, root_d, state[2], new_tok_d, n_new_d, cur_state, cur_len,
+                                                       cfg.k, cfg.sep, overlay_key=state[0], overlay_dst=state[1],
+                                                       rows_end=rows_end_d)
                     looked_up = torch.cuda.Event()
                     looked_up.record(main)
                     rest(d, nd)                               # attention + accept, queued behind the lookup
