@@ -199,6 +199,42 @@ def test_bf16_seeded_random_shapes(seed):
     _check(cfg, lay, q, kc, vc, out, pairs, dominated=True)
 
 
+ODD_PAGES = [
+    dict(dtype="bf16", page=96, Hq=8, Hkv=2, D=128, k=8, B=3, kv_len=(9, 2500)),       # 36 rows, narrow kernel
+    dict(dtype="bf16", page=160, Hq=16, Hkv=2, D=128, k=16, B=2, kv_len=(17, 2300)),   # 136 rows, wide kernel
+    dict(dtype="bf16", page=96, Hq=16, Hkv=2, D=64, k=8, B=2, kv_len=(33, 1800)),      # 72 rows, head dim 64
+    dict(dtype="f32", page=24, Hq=4, Hkv=2, D=64, k=6, B=3, kv_len=(7, 900)),
+    dict(dtype="f32", page=7, Hq=2, Hkv=1, D=128, k=4, B=2, kv_len=(5, 300)),
+]
+
+
+@pytest.mark.parametrize("schedule", [1, 2])
+@pytest.mark.parametrize("case", range(len(ODD_PAGES)))
+def test_page_sizes_that_are_not_powers_of_two(case, schedule):
+    """Positions are mapped to pages with a division instead of a shift (bf16: any multiple of the 32-position
+    tile; fp32: any size)."""
+    kw = dict(ODD_PAGES[case])
+    base = W.baseline_config(0 if kw.pop("dtype") == "f32" else 1)
+    cfg = W.scaled(base, kv_mode="ragged", permute_pages=True, **kw)
+    print(f"attn odd page case {case} schedule {schedule}: {ODD_PAGES[case]}", flush=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    A.agentsam_set_option("attn_schedule", schedule)
+    try:
+        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+        torch.cuda.synchronize()
+    finally:
+        A.agentsam_set_option("attn_schedule", 0)
+    _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
+
+
+def test_bf16_page_size_that_cuts_a_tile_is_refused():
+    cfg = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=2, D=128, k=8, page=48, kv_mode="fixed", kv_len=(480, 480))
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    with pytest.raises(Exception):
+        A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
+
+
 def test_bf16_more_than_192_rows_is_refused():
     cfg = W.scaled(W.baseline_config(1), B=1, Hq=8, Hkv=1, D=128, k=24, kv_mode="fixed", kv_len=(256, 256))
     lay, q, kc, vc, bt, seq = _inputs(cfg)
