@@ -80,36 +80,56 @@ def cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h,
     accept_oracle(lg, draft_h, nd_h)
     t_accept = time.perf_counter() - t0
     # attention: seeded sample of (session, head) pairs, every row of each; extrapolated linearly
-    rng = np.random.default_rng(cfg.seed)
     scale = 1.0 / np.sqrt(cfg.D)
     P = cfg.page
-    done, t_attn, pos_done = 0, 0.0, 0
     total_pos = int(lay.seq_lens.astype(np.int64).sum()) * cfg.Hq
-    while t_attn < budget_s and done < cfg.B * cfg.Hq:
-        b = int(rng.integers(0, cfg.B)); h = int(rng.integers(0, cfg.Hq))
-        S = int(lay.seq_lens[b]); npg = (S + P - 1) // P
-        pages = torch.as_tensor(lay.block_table[b, :npg].astype(np.int64), device=kc.device)
-        g = h // cfg.G
-        Kp = kc[pages, g].float().cpu().numpy()[:, None]          # [npg,1,P,D] page-shaped host copy
-        Vp = vc[pages, g].float().cpu().numpy()[:, None]
-        qh = q[b, :, h].float().cpu().numpy()
-        ident = np.arange(npg)
-        t0 = time.perf_counter()
-        K = gather_kv(Kp, ident, S, 0); V = gather_kv(Vp, ident, S, 0)
-        attention_oracle_head(qh, K, V, scale)
-        t_attn += time.perf_counter() - t0
-        done += 1; pos_done += S
-    t_attn_full = t_attn * total_pos / max(1, pos_done)
+
+    def sample_attention(budget):
+        rng = np.random.default_rng(cfg.seed)
+        done, t_attn, pos_done = 0, 0.0, 0
+        while t_attn < budget and done < cfg.B * cfg.Hq:
+            b = int(rng.integers(0, cfg.B)); h = int(rng.integers(0, cfg.Hq))
+            S = int(lay.seq_lens[b]); npg = (S + P - 1) // P
+            pages = torch.as_tensor(lay.block_table[b, :npg].astype(np.int64), device=kc.device)
+            g = h // cfg.G
+            Kp = kc[pages, g].float().cpu().numpy()[:, None]          # [npg,1,P,D] page-shaped host copy
+            Vp = vc[pages, g].float().cpu().numpy()[:, None]
+            qh = q[b, :, h].float().cpu().numpy()
+            ident = np.arange(npg)
+            t0 = time.perf_counter()
+            K = gather_kv(Kp, ident, S, 0); V = gather_kv(Vp, ident, S, 0)
+            attention_oracle_head(qh, K, V, scale)
+            t_attn += time.perf_counter() - t0
+            done += 1; pos_done += S
+        return done, t_attn, t_attn * total_pos / max(1, pos_done)
+
+    done, t_attn, t_attn_full = sample_attention(budget_s)
     cpu1, wall1 = time.process_time(), time.perf_counter()
     t_step = t_draft + t_attn_full + t_accept
     cores = max(1, int(round((cpu1 - cpu0) / max(1e-9, wall1 - wall0))))
+    # the same oracle held to one thread (its library routines otherwise use every core), on a shorter sample
+    single = None
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            done1, t_attn1, t_attn_full1 = sample_attention(budget_s / 4)
+        single = {"value": cfg.B * cfg.k / (t_draft + t_attn_full1 + t_accept), "unit": "tokens/s",
+                  "sample": f"attention oracle on {done1} pairs ({t_attn1:.1f} s, extrapolated to {t_attn_full1:.1f} s)"}
+    except ImportError:
+        pass
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+    except OSError:
+        pass
     return {
         "value": cfg.B * cfg.k / t_step, "unit": "tokens/s", "cores": cores, "kind": "oracle",
         "sample": (f"draft oracle on all {cfg.B} sessions ({t_draft:.3f} s) + accept oracle on all "
                    f"{cfg.B * cfg.R} rows ({t_accept:.3f} s) + fp64 attention oracle on {done} seeded "
                    f"(session, head) pairs of {cfg.B * cfg.Hq} ({t_attn:.1f} s, extrapolated linearly by "
                    f"KV positions to {t_attn_full:.1f} s)"),
-        "host_cpus": os.cpu_count(),
+        "host_cpus": os.cpu_count(), "cpu_model": model, "single_thread": single,
     }
 
 
