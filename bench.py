@@ -425,6 +425,8 @@ def main():
                      "mfma_TFLOPs": attn_flops / (t_attn * 1e-3) / 1e12, "mfma_frac_of_2500": attn_flops / (t_attn * 1e-3) / 2.5e15},
         "detail": {"t_draft_us": t_draft * 1e3, "t_attn_us": t_attn * 1e3, "t_accept_us": t_accept * 1e3,
                    "sessions_per_s_sam_draft": (cfg.B / (t_draft * 1e-3)) if t_draft else None,
+                   # the walk makes at least one dependent 16-byte record load per window token
+                   "sam_draft_dependent_loads_per_s": (float(np.asarray(rlen).sum()) / (t_draft * 1e-3)) if t_draft else None,
                    "accepted_tokens_per_s": float((accept_len + 1).sum()) / (ms_step * 1e-3),
                    "synthetic_OTE": float((accept_len + 1).mean()),
                    "synthetic_SHR": (float(accept_len[nd_h > 0].sum()) / float(max(1, cfg.k) * max(1, (nd_h > 0).sum()))),
