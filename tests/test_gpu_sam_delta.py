@@ -170,3 +170,50 @@ def test_draft_delta_argument_errors():
     assert call(arrays=n) != 0                                # missing automaton arrays
     assert call(B=0, arrays=n) == 0                           # an empty batch is a no-op
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("i", [2, 3])
+def test_maintained_copy_full_size(i):
+    """The shared automata of workloads 2 and 3 at their full size (262 k / 2 M tokens, vocabularies of 32 k
+    / 152 k, so the root's row is tens of thousands of transitions wide): three rounds of appended text,
+    every session's lookup on the maintained copy against the oracle on the grown memory."""
+    from _util import make_memories
+    from oracle import draft_oracle_batch
+    cfg = W.baseline_config(i)
+    rng = np.random.default_rng(500 + i)
+    mems = [list(m) for m in make_memories(cfg)]
+    assert len(mems) == 1
+    owner = [0] * cfg.B
+    sams = [A.sam_build(np.asarray(mems[0], np.int32), cfg.sep)]
+    grow = 4096
+    flat = A.sam_flatten(sams, grow_tokens=grow)
+    fd = flat.to(DEV)
+    mem_len = [len(mems[0])]
+    root = np.array([flat.roots[0]] * cfg.B, np.int32)
+    rows_end = np.array([flat.rows_end[0]] * cfg.B, np.int32)
+    for rnd in range(3):
+        T = mems[0]
+        add = []
+        for _ in range(40):                                   # copies of earlier text and fresh tokens
+            if rng.random() < 0.7:
+                p = int(rng.integers(0, len(T) - 40)); add += T[p:p + int(rng.integers(2, 40))]
+            else:
+                add += [int(x) for x in rng.integers(0, cfg.vocab, int(rng.integers(1, 9)))]
+        add = add[:grow // 3 - 2] + ([cfg.sep] if rnd == 1 else [])
+        A.sam_append(sams[0], np.asarray(add, np.int32))
+        T += add
+        keys, dsts = _sync(sams, fd, flat, mem_len)
+        cend = np.array([int(flat.corpus_begin[0]) + mem_len[0]] * cfg.B, np.int32)
+        recent, rlen = _windows(rng, mems, owner, cfg.m, cfg.vocab)
+        print(f"maintained copy, workload {i}, round {rnd}: overlay capacity {keys.numel()}", flush=True)
+        d, nd, ml, me = A.sam_draft_delta(fd, keys, dsts, rows_end, root, cend, recent, rlen, cfg.k, cfg.sep)
+        torch.cuda.synchronize()
+        Tn = np.asarray(T, np.int32)
+        od, ond, oml, ome = draft_oracle_batch(Tn, np.zeros(cfg.B, np.int64), np.full(cfg.B, len(Tn), np.int64),
+                                               recent, rlen, cfg.k, cfg.sep)
+        d, nd, ml, me = to_np(d), to_np(nd), to_np(ml), to_np(me)
+        assert np.array_equal(nd, ond) and np.array_equal(ml, oml)
+        assert np.array_equal(np.where(me >= 0, me - int(flat.corpus_begin[0]), -1), ome)
+        for b in range(cfg.B):
+            assert list(d[b, :ond[b]]) == list(od[b, :ond[b]]) and (d[b, ond[b]:] == -1).all()
+        assert ml.max() > 8                                   # the windows really matched
