@@ -306,12 +306,7 @@ def main():
         import ast
         cfg = W.scaled(cfg, name=cfg.name + "+" + ",".join(args.set),
                        **{kv.split("=")[0]: ast.literal_eval(kv.split("=", 1)[1]) for kv in args.set})
-    if args.kv_chunk:
-        A.agentsam_set_option("attn_kv_chunk", args.kv_chunk)
-    if args.schedule:
-        A.agentsam_set_option("attn_schedule", args.schedule)
-    if args.cascade:
-        A.agentsam_set_option("attn_cascade", args.cascade)
+    tuning = A.attn_tuning(schedule=args.schedule, cascade=args.cascade, kv_chunk=args.kv_chunk)
 
     # ---- inputs (all resident in HBM before timing)
     nmem = cfg.B if cfg.sam_mode == "per_session" else 1
@@ -333,7 +328,7 @@ def main():
     seq = torch.as_tensor(lay.seq_lens, device=dev)
     scale = 1.0 / float(np.sqrt(cfg.D))
     ws_bytes = A.spec_verify_attn_workspace(cfg.B, cfg.R, cfg.Hq, cfg.Hkv, cfg.D, cfg.page, bt.shape[1],
-                                            A.BF16 if cfg.dtype == "bf16" else A.F32)
+                                            A.BF16 if cfg.dtype == "bf16" else A.F32, tuning)
     ws = torch.empty(max(ws_bytes, 16) // 4 + 1, dtype=torch.float32, device=dev)
     out = torch.empty((cfg.B, cfg.R, cfg.Hq, cfg.D), dtype=torch.float32, device=dev)
 
@@ -354,7 +349,7 @@ def main():
             if events: events[0].record()
             d, nd, ml, me = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
         if events: events[1].record()
-        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)
+        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)
         if events: events[2].record()
         if not args.attn_only:
             res = A.spec_accept(logits, d, nd)
@@ -388,11 +383,21 @@ def main():
     # the rate this device delivers to a kernel that only streams (4 GiB, 5 launches)
     probe_buf = torch.ones(1 << 30, dtype=torch.float32, device=dev)
     probe_sink = torch.zeros(4, dtype=torch.float32, device=dev)
-    A.agentsam_stream_read_probe(probe_buf, probe_sink)
+    import ctypes
+    from paper_2512_18337_amd.build import BENCH_LIB
+    probe_lib = ctypes.CDLL(BENCH_LIB)                       # the benchmark's own helper, not the product library
+    probe_lib.bench_stream_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+
+    def stream_read_probe():
+        rc = probe_lib.bench_stream_read_probe(probe_buf.data_ptr(), probe_buf.numel() * 4, probe_sink.data_ptr(),
+                                               torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+
+    stream_read_probe()
     pe0, pe1 = ev(), ev()
     pe0.record()
     for _ in range(5):
-        A.agentsam_stream_read_probe(probe_buf, probe_sink)
+        stream_read_probe()
     pe1.record()
     torch.cuda.synchronize()
     stream_gbs = probe_buf.numel() * 4 * 5 / (pe0.elapsed_time(pe1) * 1e-3) / 1e9
@@ -450,7 +455,7 @@ def main():
         for _ in range(3):
             A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
         se0, se1 = ev(), ev()
-        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)   # the host queues the calls behind it
+        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)   # the host queues the calls behind it
         se0.record()
         for _ in range(20):
             A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
@@ -462,7 +467,7 @@ def main():
         # path is defined with the stateless one)
         def step_stateful():
             d, nd, _, _ = A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
-            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)
+            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)
             return A.spec_accept(logits, d, nd)
         for _ in range(3):
             step_stateful()
@@ -494,7 +499,7 @@ def main():
         result["detail"]["sam_prompt_build"] = measure_build(A, cfg)
     if args.maintain > 0:
         def rest(d, nd):
-            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)
+            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)
             A.spec_accept(logits, d, nd)
         result["detail"]["sam_maintenance"] = measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx,
                                                                   args.maintain, dev, rest)

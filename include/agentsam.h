@@ -46,25 +46,24 @@ extern "C" {
 
 const char *agentsam_strerror(int code);
 
-/* Measurement aid: reads buf[0 .. bytes rounded down to 16 MiB) once with 1024 workgroups of plain
- * streaming loads and does nothing else (device pointers; sink16 = 16 writable bytes, normally left
- * untouched).  Timing it gives the streaming-read rate of the device the benchmark runs on. */
-int agentsam_stream_read_probe(const void *buf, size_t bytes, void *sink16, void *stream);
-
-/* Tuning knobs for experiments and for tests of split invariance.
- *   "attn_kv_chunk"  KV positions handled by one workgroup of spec_verify_attn
- *                    (0 = choose automatically; otherwise a multiple of 128, >= 128).
- *   "attn_schedule"  how spec_verify_attn (bf16) spreads the batch over the GPU: 1 = every
- *                    (session, kv head) stream cut into chunks, one workgroup per chunk;
- *                    2 = all streams laid end to end and cut into one equal share per resident
- *                    workgroup; 0 = choose (2 for large batches unless a chunk size is set).
- *   "attn_cascade"   shared-prefix run of spec_verify_attn (bf16): 2 = look for pages that all sessions
- *                    list at the same place of their block tables and process them once per group of
- *                    sessions instead of once per session; 1 = never; 0 = look when the K/V stream
- *                    is large enough (>= 11 GB) for the detection to cost nothing.  Same results.
- *   "attn_v_mode"    0/1: how the bf16 kernels transpose V out of LDS (same results).
- * Returns AGENTSAM_ERR_ARG for an unknown key or a bad value. */
-int agentsam_set_option(const char *key, int64_t value);
+/* Per-call tuning word of spec_verify_attn and spec_verify_attn_workspace (the two must be given the
+ * same word: the workspace layout depends on it).  0 lets the library choose everything; the fields
+ * exist for experiments and for the tests of split invariance.  Results never depend on the word
+ * beyond rounding (the split decides what each softmax weight is rounded against).
+ *   schedule   how a bf16 batch is spread over the GPU: CHUNKS = every (session, kv head) stream cut into
+ *              chunks, one workgroup per chunk; BALANCED = all streams laid end to end and cut into one
+ *              equal share per resident workgroup; default: BALANCED for large batches.
+ *   cascade    shared-prefix run (bf16): ON = look for pages that all sessions list at the same place of
+ *              their block tables and process them once per group of sessions instead of once per
+ *              session; OFF = never; default: look when the K/V stream is large enough (>= 11 GB) for the
+ *              detection to cost nothing.
+ *   kv chunk   KV positions handled by one workgroup under the CHUNKS schedule (a multiple of 128,
+ *              128 .. 2^30); default: chosen from the batch. */
+#define AGENTSAM_ATTN_SCHEDULE_CHUNKS    ((uint64_t)1)
+#define AGENTSAM_ATTN_SCHEDULE_BALANCED  ((uint64_t)2)
+#define AGENTSAM_ATTN_CASCADE_OFF        ((uint64_t)1 << 2)
+#define AGENTSAM_ATTN_CASCADE_ON         ((uint64_t)2 << 2)
+#define AGENTSAM_ATTN_KV_CHUNK(positions) ((uint64_t)((positions) / 128) << 8)
 
 /* ------------------------------------------------------------------------------------------
  * Suffix automaton over a token memory (paper Sec. 5.4.2: the request context is indexed in a
@@ -315,13 +314,14 @@ int sam_draft_merged(const int32_t *row_ptr, const int32_t *edge_tok, const int3
  * Supported: D in {64,128}; Hq % Hkv == 0; bf16 needs page_size % 32 == 0; scale > 0;
  * (Hq/Hkv)*R <= 192 for bf16, R <= 32 for f32. */
 int spec_verify_attn_workspace(int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D,
-                               int32_t page_size, int32_t max_pages, int32_t dtype, size_t *bytes);
+                               int32_t page_size, int32_t max_pages, int32_t dtype, uint64_t tuning,
+                               size_t *bytes);
 
 int spec_verify_attn(const void *q, const void *k_cache, const void *v_cache,
                      const int32_t *block_table, int32_t max_pages, const int32_t *seq_lens,
                      int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
                      int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype,
-                     void *out, void *workspace, size_t workspace_bytes, void *stream);
+                     void *out, void *workspace, size_t workspace_bytes, uint64_t tuning, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * spec_accept (Alg. 4: "commit matched prefix; on mismatch fall back to standard decoding";
@@ -333,7 +333,7 @@ int spec_verify_attn(const void *q, const void *k_cache, const void *v_cache,
  *
  * Device inputs : logits[B,1+k,V] (f32 or bf16), draft[B,k], n_draft[B].
  * Device outputs: accept_len[B], out_tokens[B,1+k], tgt[B,1+k].
- * Limits: 0 <= k <= 63, V >= 1. */
+ * Limits: 0 <= k <= 64 (as sam_draft), V >= 1. */
 int spec_accept(const void *logits, int32_t logits_dtype, const int32_t *draft,
                 const int32_t *n_draft, int32_t B, int32_t k, int64_t V,
                 int32_t *accept_len, int32_t *out_tokens, int32_t *tgt, void *stream);

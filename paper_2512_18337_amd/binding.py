@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _vp = ctypes.c_void_p
 
-EXPORTS = ["agentsam_strerror", "agentsam_set_option", "agentsam_stream_read_probe", "sam_build", "sam_append", "sam_flat_sizes",
+EXPORTS = ["agentsam_strerror", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
            "sam_draft", "sam_draft_delta", "sam_draft_step", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
@@ -45,8 +45,6 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.agentsam_strerror.restype = ctypes.c_char_p
         L.agentsam_strerror.argtypes = [ctypes.c_int]
-        L.agentsam_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
-        L.agentsam_stream_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
         L.sam_build.argtypes = [_i32p, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(_vp)]
         L.sam_append.argtypes = [_vp, _i32p, ctypes.c_int64]
         L.sam_flat_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 3
@@ -77,10 +75,10 @@ def lib():
                                       [_vp] * 4 + [_vp, ctypes.c_int64, _vp])
         L.sam_draft_step.argtypes = ([_vp] * 8 + [ctypes.c_int64, _vp, _vp, ctypes.c_int64] + [_vp] * 4 +
                                      [ctypes.c_int32] * 5 + [_vp] * 6 + [_vp])
-        L.spec_verify_attn_workspace.argtypes = [ctypes.c_int32] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
+        L.spec_verify_attn_workspace.argtypes = [ctypes.c_int32] * 8 + [ctypes.c_uint64, ctypes.POINTER(ctypes.c_size_t)]
         L.spec_verify_attn.argtypes = ([_vp, _vp, _vp, _vp, ctypes.c_int32, _vp] + [ctypes.c_int32] * 6 +
                                        [ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
-                                        _vp, _vp, ctypes.c_size_t, _vp])
+                                        _vp, _vp, ctypes.c_size_t, ctypes.c_uint64, _vp])
         L.spec_accept.argtypes = [_vp, ctypes.c_int32, _vp, _vp, ctypes.c_int32, ctypes.c_int32,
                                   ctypes.c_int64, _vp, _vp, _vp, _vp]
         _lib = L
@@ -96,8 +94,12 @@ def _check(rc: int, where: str):
         raise AgentSamError(rc, where)
 
 
-def agentsam_set_option(key: str, value: int) -> None:
-    _check(lib().agentsam_set_option(key.encode(), int(value)), f"agentsam_set_option({key})")
+def attn_tuning(schedule: int = 0, cascade: int = 0, kv_chunk: int = 0) -> int:
+    """The per-call tuning word of spec_verify_attn (AGENTSAM_ATTN_* in the header): schedule 0 auto / 1 chunk
+    grid / 2 balanced; cascade 0 auto / 1 off / 2 on; kv_chunk 0 auto or KV positions per workgroup."""
+    if kv_chunk % 128:
+        raise ValueError("kv_chunk must be a multiple of 128")
+    return int(schedule) | (int(cascade) << 2) | ((int(kv_chunk) // 128) << 8)
 
 
 # ----------------------------------------------------------------------------- host automaton
@@ -434,12 +436,6 @@ def agentsched_pick(free_blocks: int, hit, need, prompt_tok, wait, *, lambda_max
     return lam.value, score, picked.value
 
 
-def agentsam_stream_read_probe(buf, sink) -> None:
-    """One streaming read of the device tensor buf (measurement aid, see the header)."""
-    _check(lib().agentsam_stream_read_probe(_dp(buf), buf.numel() * buf.element_size(), _dp(sink), _stream_ptr()),
-           "agentsam_stream_read_probe")
-
-
 def _dtype_code(t) -> int:
     import torch
     if t.dtype == torch.float32:
@@ -449,16 +445,17 @@ def _dtype_code(t) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
-def spec_verify_attn_workspace(B, R, Hq, Hkv, D, page_size, max_pages, dtype_code) -> int:
+def spec_verify_attn_workspace(B, R, Hq, Hkv, D, page_size, max_pages, dtype_code, tuning: int = 0) -> int:
     n = ctypes.c_size_t()
-    _check(lib().spec_verify_attn_workspace(B, R, Hq, Hkv, D, page_size, max_pages, dtype_code, ctypes.byref(n)),
-           "spec_verify_attn_workspace")
+    _check(lib().spec_verify_attn_workspace(B, R, Hq, Hkv, D, page_size, max_pages, dtype_code, int(tuning),
+                                            ctypes.byref(n)), "spec_verify_attn_workspace")
     return n.value
 
 
 def spec_verify_attn(q, k_cache, v_cache, block_table, seq_lens, scale: float, out=None, workspace=None,
-                     out_dtype=None):
-    """q[B,R,Hq,D]; caches [num_pages,Hkv,P,D]; block_table[B,max_pages] int32; seq_lens[B] int32 (device)."""
+                     out_dtype=None, tuning: int = 0):
+    """q[B,R,Hq,D]; caches [num_pages,Hkv,P,D]; block_table[B,max_pages] int32; seq_lens[B] int32 (device).
+    tuning: see attn_tuning()."""
     import torch
     B, R, Hq, D = q.shape
     num_pages, Hkv, P, D2 = k_cache.shape
@@ -469,13 +466,13 @@ def spec_verify_attn(q, k_cache, v_cache, block_table, seq_lens, scale: float, o
     code = _dtype_code(q)
     if out is None:
         out = torch.empty((B, R, Hq, D), dtype=out_dtype or torch.float32, device=q.device)
-    need = spec_verify_attn_workspace(B, R, Hq, Hkv, D, P, max_pages, code)
+    need = spec_verify_attn_workspace(B, R, Hq, Hkv, D, P, max_pages, code, tuning)
     if workspace is None or workspace.numel() * workspace.element_size() < need:
         workspace = torch.empty((max(need, 16) + 3) // 4, dtype=torch.float32, device=q.device)
     rc = lib().spec_verify_attn(_dp(q), _dp(k_cache), _dp(v_cache), _dp(block_table), max_pages, _dp(seq_lens),
                                 B, R, Hq, Hkv, D, P, num_pages, float(scale), code, _dtype_code(out),
                                 _dp(out), _dp(workspace), workspace.numel() * workspace.element_size(),
-                                _stream_ptr())
+                                int(tuning), _stream_ptr())
     _check(rc, "spec_verify_attn")
     return out
 

@@ -294,12 +294,8 @@ extern "C" int sam_draft(const int32_t *len, const int32_t *link, const int32_t 
         return AGENTSAM_ERR_NULL;
     // edge_tok / edge_dst / corpus may be NULL only for an automaton with no transitions (empty
     // memory): then every row is empty and nothing matches, so they are never dereferenced.
-    hipLaunchKernelGGL(sam_draft_kernel<false>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
-                       row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
-                       recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, nullptr,
-                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, 1);
-    AGENTSAM_LAUNCH_CHECK();
+    AGENTSAM_LAUNCH(sam_draft_kernel<false>, dim3((unsigned)B), dim3(64), (hipStream_t)stream,
+                    row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end, recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token, draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, nullptr, WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, 1);
     return AGENTSAM_OK;
 }
 
@@ -320,12 +316,8 @@ extern "C" int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, 
         !recent || !recent_len || !n_draft || !match_len || !match_end || (k > 0 && !draft))
         return AGENTSAM_ERR_NULL;
     const Overlay ov{(const unsigned long long *)overlay_key, overlay_dst, (unsigned)(overlay_cap - 1)};
-    hipLaunchKernelGGL(sam_draft_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
-                       row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
-                       recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       draft, n_draft, match_len, match_end, ov, rows_end,
-                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, 1);
-    AGENTSAM_LAUNCH_CHECK();
+    AGENTSAM_LAUNCH(sam_draft_kernel<true>, dim3((unsigned)B), dim3(64), (hipStream_t)stream,
+                    row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end, recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token, draft, n_draft, match_len, match_end, ov, rows_end, WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, 1);
     return AGENTSAM_OK;
 }
 
@@ -354,15 +346,12 @@ extern "C" int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, c
     const WideTable wt{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u};
     if (maintained) {
         const Overlay ov{(const unsigned long long *)overlay_key, overlay_dst, (unsigned)(overlay_cap - 1)};
-        hipLaunchKernelGGL(sam_draft_step_kernel<true>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream, A, root,
-                           corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state,
-                           cur_len, draft, n_draft, match_len, match_end, ov, wt);
+        AGENTSAM_LAUNCH(sam_draft_step_kernel<true>, dim3((unsigned)B), dim3(64), (hipStream_t)stream,
+                    A, root, corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state, cur_len, draft, n_draft, match_len, match_end, ov, wt);
     } else {
-        hipLaunchKernelGGL(sam_draft_step_kernel<false>, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream, A, root,
-                           corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state,
-                           cur_len, draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, wt);
+        AGENTSAM_LAUNCH(sam_draft_step_kernel<false>, dim3((unsigned)B), dim3(64), (hipStream_t)stream,
+                    A, root, corpus_end, new_tok, n_new, (int)max_new, (int)k, (int)min_match, (int)sep_token, cur_state, cur_len, draft, n_draft, match_len, match_end, Overlay{nullptr, nullptr, 0u}, wt);
     }
-    AGENTSAM_LAUNCH_CHECK();
     return AGENTSAM_OK;
 }
 
@@ -386,10 +375,8 @@ extern "C" int sam_apply_delta(const int32_t *rec_idx, const int32_t *rec_val, i
     const int64_t n = n_rec > n_lastpos ? n_rec : n_lastpos;
     if (n == 0) return AGENTSAM_OK;
     if ((n + 255) / 256 > 0x7fffffffll) return AGENTSAM_ERR_ARG;
-    hipLaunchKernelGGL(sam_apply_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                       rec_idx, (const int4 *)rec_val, n_rec, lastpos_idx, lastpos_val, n_lastpos,
-                       (int4 *)state_rec, lastpos);
-    AGENTSAM_LAUNCH_CHECK();
+    AGENTSAM_LAUNCH(sam_apply_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), (hipStream_t)stream,
+                    rec_idx, (const int4 *)rec_val, n_rec, lastpos_idx, lastpos_val, n_lastpos, (int4 *)state_rec, lastpos);
     return AGENTSAM_OK;
 }
 
@@ -451,15 +438,9 @@ extern "C" int sam_draft_merged(const int32_t *row_ptr, const int32_t *edge_tok,
     const size_t n = (size_t)B * M;
     if (workspace_bytes < n * (size_t)(k + 3) * sizeof(int32_t)) return AGENTSAM_ERR_WORKSPACE;
     int32_t *c_draft = (int32_t *)workspace, *c_n = c_draft + n * k, *c_len = c_n + n, *c_end = c_len + n;
-    hipLaunchKernelGGL(sam_draft_kernel<false>, dim3((unsigned)n), dim3(64), 0, (hipStream_t)stream,
-                       row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end,
-                       recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token,
-                       c_draft, c_n, c_len, c_end, Overlay{nullptr, nullptr, 0u}, nullptr,
-                       WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, (int)M);
-    AGENTSAM_LAUNCH_CHECK();
-    hipLaunchKernelGGL(sam_select_kernel, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream,
-                       weight, c_draft, c_n, c_len, c_end, (int)B, (int)M, (int)k, draft, n_draft, match_len, match_end,
-                       source);
-    AGENTSAM_LAUNCH_CHECK();
+    AGENTSAM_LAUNCH(sam_draft_kernel<false>, dim3((unsigned)n), dim3(64), (hipStream_t)stream,
+                    row_ptr, edge_tok, edge_dst, lastpos, corpus, (const int4 *)state_rec, root, corpus_end, recent, recent_len, (int)m, (int)k, (int)min_match, (int)sep_token, c_draft, c_n, c_len, c_end, Overlay{nullptr, nullptr, 0u}, nullptr, WideTable{(const int4 *)wide_table, wide_table ? (unsigned)(wide_slots - 1) : 0u}, (int)M);
+    AGENTSAM_LAUNCH(sam_select_kernel, dim3((unsigned)B), dim3(64), (hipStream_t)stream,
+                    weight, c_draft, c_n, c_len, c_end, (int)B, (int)M, (int)k, draft, n_draft, match_len, match_end, source);
     return AGENTSAM_OK;
 }

@@ -122,7 +122,7 @@ __global__ void accept_prefix_kernel(const int32_t *__restrict__ tgt, const int3
 extern "C" int spec_accept(const void *logits, int32_t logits_dtype, const int32_t *draft,
                            const int32_t *n_draft, int32_t B, int32_t k, int64_t V,
                            int32_t *accept_len, int32_t *out_tokens, int32_t *tgt, void *stream) {
-    if (B < 0 || k < 0 || k > 63 || V < 1 || V > 0x7ffffff0ll) return AGENTSAM_ERR_ARG;
+    if (B < 0 || k < 0 || k > 64 || V < 1 || V > 0x7ffffff0ll) return AGENTSAM_ERR_ARG;
     if (logits_dtype != AGENTSAM_F32 && logits_dtype != AGENTSAM_BF16) return AGENTSAM_ERR_UNSUPPORTED;
     if (B == 0) return AGENTSAM_OK;
     if (!logits || !n_draft || !accept_len || !out_tokens || !tgt || (k > 0 && !draft)) return AGENTSAM_ERR_NULL;
@@ -130,12 +130,12 @@ extern "C" int spec_accept(const void *logits, int32_t logits_dtype, const int32
     if (rows > 0x7fffffffll) return AGENTSAM_ERR_ARG;
     hipStream_t st = (hipStream_t)stream;
     if (logits_dtype == AGENTSAM_BF16)
-        hipLaunchKernelGGL(row_argmax_kernel<true>, dim3((unsigned)rows), dim3(kThreads), 0, st, logits, V, tgt);
+        AGENTSAM_LAUNCH(row_argmax_kernel<true>, dim3((unsigned)rows), dim3(kThreads), st,
+                    logits, V, tgt);
     else
-        hipLaunchKernelGGL(row_argmax_kernel<false>, dim3((unsigned)rows), dim3(kThreads), 0, st, logits, V, tgt);
-    AGENTSAM_LAUNCH_CHECK();
-    hipLaunchKernelGGL(accept_prefix_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), 0, st, tgt, draft,
-                       n_draft, (int)B, (int)k, accept_len, out_tokens);
-    AGENTSAM_LAUNCH_CHECK();
+        AGENTSAM_LAUNCH(row_argmax_kernel<false>, dim3((unsigned)rows), dim3(kThreads), st,
+                    logits, V, tgt);
+    AGENTSAM_LAUNCH(accept_prefix_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), st,
+                    tgt, draft, n_draft, (int)B, (int)k, accept_len, out_tokens);
     return AGENTSAM_OK;
 }

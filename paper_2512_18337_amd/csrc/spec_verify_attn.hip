@@ -23,13 +23,10 @@
 // The fp32 storage type runs through a plain (non-MFMA) kernel with the same chunking.
 #include <hip/hip_bf16.h>
 
-#include "common.h"
+#include <algorithm>
+#include <atomic>
 
-namespace agentsam {
-int64_t option_attn_v_mode();
-int64_t option_attn_schedule();
-int64_t option_attn_cascade();
-}
+#include "common.h"
 
 namespace {
 
@@ -53,7 +50,7 @@ struct AttnParams {
     const int32_t *bt, *seq;
     void *out;
     float *ws;
-    int B, R, Hq, Hkv, G, P, max_pages;
+    int B, R, Hq, Hkv, G, D, P, max_pages;
     int log2P;               // log2(P) when P is a power of two, else -1
     int64_t num_pages;
     float scale_log2;        // scale * log2(e)
@@ -97,6 +94,20 @@ __device__ __forceinline__ void store_out(void *out, int64_t idx, float4 v, int 
         o[2] = __float2bfloat16(v.z); o[3] = __float2bfloat16(v.w);
     } else {
         *(float4 *)((float *)out + idx) = v;
+    }
+}
+
+// A row that sees no KV position (seq_lens[b] - R + i < 0, in particular every row of an empty
+// session) has no softmax; its output is defined as zeros.
+__device__ __forceinline__ float inv_or_zero(float l) { return l > 0.f ? 1.0f / l : 0.f; }
+
+// zeros for every row of the query heads [h0, h0+nh) of session b (called by a whole workgroup)
+__device__ __forceinline__ void zero_session_heads(const void *out_, int out_bf16, int b, int R, int Hq, int D, int h0, int nh) {
+    void *out = const_cast<void *>(out_);
+    const int per_row = nh * D / 4;                          // the heads of one query row are contiguous
+    for (int idx = threadIdx.x; idx < R * per_row; idx += blockDim.x) {
+        const int i = idx / per_row, c = idx % per_row;
+        store_out(out, (((int64_t)b * R + i) * Hq + h0) * D + c * 4, float4{0.f, 0.f, 0.f, 0.f}, out_bf16);
     }
 }
 
@@ -293,13 +304,13 @@ __device__ __forceinline__ void softmax_exp(WaveState<D, MT> &w, const f32x4 (&s
 }
 
 // O^T += V^T . P^T for one tile
-template <int D, int MT, int VMODE>
+template <int D, int MT>
 __device__ __forceinline__ void pv_mfma(WaveState<D, MT> &w, const char *Vs, const bf16x8 (&pf)[MT], int n, int g) {
     using C = Bf16Cfg<D>;
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
         bf16x8 vf;
-        if (VMODE == 1) {
+        {
             // LDS transpose read (per 16 lanes): lane r supplies the 8-byte chunk (position r/4,
             // d-chunk r%4); lane i receives element i%4 of the chunks of lanes i/4, 4+i/4, 8+i/4,
             // 12+i/4, i.e. d = 16*dt + i at 4 consecutive positions
@@ -310,14 +321,6 @@ __device__ __forceinline__ void pv_mfma(WaveState<D, MT> &w, const char *Vs, con
             s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a1);
             s16x8 cat = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             vf = __builtin_bit_cast(bf16x8, cat);
-        } else {
-            s16x8 cat;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int pos = (j < 4) ? (4 * g + j) : (16 + 4 * g + j - 4);
-                cat[j] = *(const short *)(Vs + pos * C::kVStr + (dt * 16 + n) * 2);
-            }
-            vf = __builtin_bit_cast(bf16x8, cat);
         }
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt)
@@ -326,7 +329,7 @@ __device__ __forceinline__ void pv_mfma(WaveState<D, MT> &w, const char *Vs, con
 }
 
 // One 32-position tile (K at Ks, V at Vs in LDS) against the wavefront's rows, start to finish.
-template <int D, int MT, int VMODE>
+template <int D, int MT>
 __device__ __forceinline__ void compute_tile(WaveState<D, MT> &w, const char *Ks, const char *Vs, int pos0,
                                              int S, int R, float c /* scale*log2e */, int n, int g) {
     f32x4 sacc[2][MT];
@@ -339,7 +342,7 @@ __device__ __forceinline__ void compute_tile(WaveState<D, MT> &w, const char *Ks
     if (move) rescale<D, MT>(w, mx);
     if (mask) softmax_exp<D, MT, true>(w, sacc, c, pf);
     else softmax_exp<D, MT, false>(w, sacc, c, pf);
-    pv_mfma<D, MT, VMODE>(w, Vs, pf, n, g);
+    pv_mfma<D, MT>(w, Vs, pf, n, g);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -369,7 +372,7 @@ struct Segment {
 };
 
 __device__ __forceinline__ int session_len(const AttnParams &p, int b) {
-    return min(p.seq[b], p.max_pages * p.P);                 // never index past the block table
+    return max(0, min(p.seq[b], p.max_pages * p.P));         // never index past the block table
 }
 __device__ __forceinline__ int tiles_of(int S) { return S > 0 ? (S + kTile - 1) / kTile : 0; }
 
@@ -456,6 +459,7 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
         int nchunks_b, chunk_len;
         chunk_geometry(sg.S, p.chunk, nchunks_b, chunk_len);
         const int chunk = blockIdx.x / (p.B * p.Hkv);
+        if (sg.S <= 0 && chunk == 0) zero_session_heads(p.out, p.out_bf16, sg.b, p.R, p.Hq, p.D, sg.kvh * p.G, p.G);
         if (chunk >= nchunks_b) return;
         const int c0 = chunk * chunk_len, c1 = min(sg.S, c0 + chunk_len);
         sg.t0 = c0 / kTile;                                  // chunk_len is a multiple of 128
@@ -583,7 +587,7 @@ __device__ __forceinline__ TileSrc<D> tile_src(const AttnParams &p, const ChunkP
 }
 
 // -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the segment
-template <int D, int MT, int VMODE>
+template <int D, int MT>
 __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams p) {
     using C = Bf16Cfg<D>;
     constexpr int kStage = kWaves * C::kTileBytes;
@@ -671,14 +675,14 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
                     stage(t, kreg[0], vreg[0]);
                     wave_lds_fence();
                     issue_loads(t + 2 * kWaves, last, kreg[0], vreg[0]);
-                    compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
+                    compute_tile<D, MT>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
                     wave_lds_fence();
                     t += kWaves;
                     if (i + 1 >= n_my) break;
                     stage(t, kreg[1], vreg[1]);
                     wave_lds_fence();
                     issue_loads(t + 2 * kWaves, last, kreg[1], vreg[1]);
-                    compute_tile<D, MT, VMODE>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
+                    compute_tile<D, MT>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
                     wave_lds_fence();
                     t += kWaves;
                     if (i + 2 >= n_my) break;
@@ -749,7 +753,7 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
             for (int idx = tid_e; idx < rows_here * (D / 4); idx += 256) {
                 const int row = idx / (D / 4), c4 = idx % (D / 4);
                 const int hh = row / R, i = row % R;
-                const float inv = 1.0f / red_l[row];
+                const float inv = inv_or_zero(red_l[row]);
                 float4 v = *(const float4 *)(Osum + row * C::kOStr + c4 * 4);
                 v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
                 const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
@@ -788,9 +792,6 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
 //     references to the exact row maxima, then a final pass;
 //   - registers stay under 256 so that two workgroups share a compute unit and one's wavefront
 //     fills the other's stalls; one workgroup barrier per tile publishes the tile.
-// AGENTSAM_EXP_NO_DMA / AGENTSAM_EXP_NO_COMPUTE / AGENTSAM_EXP_NS (never defined by the build script) cut the
-// tile requests or the arithmetic out of the loop, or change the ring depth, to time the two halves
-// apart; results are then meaningless.
 template <int D>
 struct WideCfg {
     static constexpr int kRowBytes = D * 2;
@@ -971,15 +972,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             if (t < ntiles && wave == (t & (kWaves - 1))) issue(t, t);
         int slot_cur = 0;                                    // ring slot of tile t (t mod NS, kept incrementally)
         for (int t = 0; t < ntiles; ++t, slot_cur = (slot_cur + 1 == NS) ? 0 : slot_cur + 1) {
-#ifndef AGENTSAM_EXP_NO_DMA
             if (wave == (t & (kWaves - 1))) wait_vmcnt0();   // the tile I fetched has landed
-#endif
             __syncthreads();                                 // tile t visible; everyone is done with tile t-1
             const int tn = t + NS - 1;                       // goes into the slot tile t-1 occupied
-#ifdef AGENTSAM_EXP_NO_COMPUTE
-            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn, slot_cur == 0 ? NS - 1 : slot_cur - 1);
-            continue;
-#endif
 
             const int pos0 = c0 + t * kTile;
             const bool mask = pos0 + kTile > S - R;          // touches the new rows or the ragged end
@@ -1016,11 +1011,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
                         sx[pt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks & 1][pt], wx.qf[0][ks], sx[pt][0], 0, 0, 0);
                 }
             }
-#ifndef AGENTSAM_EXP_NO_DMA
             // The next tile is requested here rather than right after the barrier: the address arithmetic
             // and the load instructions of the fetching wavefront then run while its multiplications drain.
             if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn, slot_cur == 0 ? NS - 1 : slot_cur - 1);
-#endif
             // ---- first half of the V fragments: issued now so their LDS latency hides under the softmax
             auto load_vf = [&](int dt) {
                 const char *a0 = smem + (vx ^ (dt << 5));
@@ -1138,7 +1131,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
         if (pr < row_end) {
             if (final_out) {
                 const int hh = pr / R, i = pr % R;
-                const float inv = 1.0f / l;
+                const float inv = inv_or_zero(l);
                 const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D;
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) {
@@ -1198,7 +1191,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
             float4 v = *(const float4 *)(xo + row * kXStr + c4 * 4);
             if (final_out) {
                 const int hh = pr / R, i = pr % R;
-                const float inv = 1.0f / xl[row];
+                const float inv = inv_or_zero(xl[row]);
                 v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
                 const int64_t o = (((int64_t)b * R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
                 store_out(p.out, o, v, p.out_bf16);
@@ -1220,7 +1213,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnParams p, int heads_outer, int G_eff) {
     const int ho = blockIdx.x, b = blockIdx.y;
-    const int S = min(p.seq[b], p.max_pages * p.P);      // never index past the block table
+    const int S = session_len(p, b);
     const int nchunks_b = (S + p.chunk - 1) / p.chunk;
     if (nchunks_b <= 1) return;
     const int rows = G_eff * p.R;
@@ -1239,7 +1232,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnParams p, int
             const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
             acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
         }
-        const float inv = 1.0f / L;
+        const float inv = inv_or_zero(L);
         acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
         const int hh = pr / p.R, i = pr % p.R;
         const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)ho * G_eff + hh) * D + c4 * 4;
@@ -1254,7 +1247,10 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_merge_balanced_kernel(const AttnParams p, int nslots) {
     const int kvh = blockIdx.x, b = blockIdx.y;
     const int nt_b = tiles_of(session_len(p, b));
-    if (nt_b == 0) return;
+    if (nt_b == 0) {                                         // an empty session: no workgroup had any of it
+        zero_session_heads(p.out, p.out_bf16, b, p.R, p.Hq, D, kvh * p.G, p.G);
+        return;
+    }
     const int T = p.plan[p.B] * p.Hkv;
     const int share = balanced_share(T, nslots);
     const int g0 = p.plan[b] * p.Hkv + kvh * nt_b, g1 = g0 + nt_b;      // the stream's place in the sequence
@@ -1277,7 +1273,7 @@ __global__ __launch_bounds__(256) void attn_merge_balanced_kernel(const AttnPara
             const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
             acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
         }
-        const float inv = 1.0f / L;
+        const float inv = inv_or_zero(L);
         acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
         const int hh = pr / p.R, i = pr % p.R;
         const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
@@ -1316,7 +1312,10 @@ __global__ __launch_bounds__(256) void attn_merge_cascade_kernel(const AttnParam
     const int kvh = blockIdx.x, b = blockIdx.y;
     const int ptiles = shared_prefix_tiles(p, tmp);
     const int nt_b = max(0, tiles_of(session_len(p, b)) - ptiles);
-    if (nt_b == 0) return;                                   // (cannot happen for a valid session: its new rows follow the prefix)
+    if (nt_b == 0) {                                         // an empty session (a valid one has its new rows after the prefix)
+        zero_session_heads(p.out, p.out_bf16, b, p.R, p.Hq, D, kvh * p.G, p.G);
+        return;
+    }
     const int T = p.plan[p.B] * p.Hkv;
     const int share = balanced_share(T, p.nslots);
     const int g0 = p.plan[b] * p.Hkv + kvh * nt_b, g1 = g0 + nt_b;
@@ -1357,7 +1356,7 @@ __global__ __launch_bounds__(256) void attn_merge_cascade_kernel(const AttnParam
         };
         for (int j = 0; j < n_own; ++j) add(own(j), p.rows_pad, pr);
         for (int c = 0; c < n_pre; ++c) add(pre(c), p.rows_pad_p, prp);
-        const float inv = 1.0f / L;
+        const float inv = inv_or_zero(L);
         acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
         const int hh = pr / p.R, i = pr % p.R;
         const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
@@ -1376,8 +1375,9 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p) {
     __shared__ float row_m[kF32MaxR], row_l[kF32MaxR];
 
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int S = min(p.seq[b], p.max_pages * p.P);      // never index past the block table
+    const int S = session_len(p, b);
     const int c0 = chunk * p.chunk;
+    if (S <= 0 && chunk == 0) zero_session_heads(p.out, p.out_bf16, b, p.R, p.Hq, D, h, 1);
     if (c0 >= S) return;
     const int c1 = min(S, c0 + p.chunk);
     const int npos = c1 - c0;
@@ -1457,7 +1457,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p) {
             wo[(int64_t)i * D + d] = acc;
             if (d == 0) { wm[i] = row_m[i]; wl[i] = row_l[i]; }
         } else {
-            const float r = acc / row_l[i];
+            const float r = acc * inv_or_zero(row_l[i]);
             const int64_t o = (((int64_t)b * R + i) * p.Hq + h) * D + d;
             if (p.out_bf16) ((__hip_bfloat16 *)p.out)[o] = __float2bfloat16(r);
             else ((float *)p.out)[o] = r;
@@ -1468,6 +1468,21 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p) {
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+struct Tuning {
+    int sched;               // 0 auto, 1 chunk grid, 2 balanced
+    int casc;                // 0 auto, 1 never, 2 look for a shared prefix
+    int64_t kv_chunk;        // 0 auto, else KV positions per workgroup of the chunk grid
+};
+
+int parse_tuning(uint64_t word, Tuning *t) {
+    t->sched = (int)(word & 3);
+    t->casc = (int)((word >> 2) & 3);
+    t->kv_chunk = (int64_t)((word >> 8) & 0xffffff) * 128;
+    if (t->sched == 3 || t->casc == 3 || (word >> 32) != 0 || (word & 0xf0) != 0) return AGENTSAM_ERR_ARG;
+    if (t->kv_chunk > (1ll << 30)) return AGENTSAM_ERR_ARG;
+    return AGENTSAM_OK;
+}
+
 struct Plan {
     int chunk, nchunks_max, rows_pad, heads_outer;
     bool wide;
@@ -1485,15 +1500,17 @@ struct Plan {
 // <= 256 registers) or x 1 (narrow kernel, which takes the whole register file of a SIMD).
 constexpr int kComputeUnits = 256;
 
-int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages, int dtype, Plan *pl) {
+int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages, int dtype, uint64_t tuning, Plan *pl) {
     if (B < 0 || R < 1 || Hq < 1 || Hkv < 1 || page_size < 1 || max_pages < 1) return AGENTSAM_ERR_ARG;
     if (Hq % Hkv != 0) return AGENTSAM_ERR_ARG;
     if (D != 64 && D != 128) return AGENTSAM_ERR_UNSUPPORTED;
     if (dtype != AGENTSAM_F32 && dtype != AGENTSAM_BF16) return AGENTSAM_ERR_UNSUPPORTED;
+    Tuning tn;
+    if (const int rc = parse_tuning(tuning, &tn)) return rc;
     const int64_t smax = (int64_t)max_pages * page_size;
     if (smax > 0x7fffff00ll) return AGENTSAM_ERR_ARG;
     const int G = Hq / Hkv;
-    const int64_t opt = agentsam::option_attn_kv_chunk();
+    const int64_t opt = tn.kv_chunk;
     pl->wide = false;
     pl->cascade = false;
     pl->balanced = false;
@@ -1532,11 +1549,10 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
         // With at least two (session, kv head) streams per resident workgroup the batch is cut into
         // equal shares; with fewer, every stream is split anyway and the chunk grid keeps sessions
         // that share a prefix in step.  An explicit chunk size asks for the chunk grid.
-        const int64_t sched = agentsam::option_attn_schedule();
         const int64_t tiles_max = (int64_t)B * Hkv * ((smax + kTile - 1) / kTile);
-        pl->balanced = sched == 2 || (sched == 0 && opt == 0 && (int64_t)B * Hkv >= 2 * (int64_t)pl->nslots);
+        pl->balanced = tn.sched == 2 || (tn.sched == 0 && opt == 0 && (int64_t)B * Hkv >= 2 * (int64_t)pl->nslots);
         if (pl->balanced && tiles_max > 0x7fffffffll) {
-            if (sched == 2) return AGENTSAM_ERR_ARG;
+            if (tn.sched == 2) return AGENTSAM_ERR_ARG;
             pl->balanced = false;
         }
     }
@@ -1548,11 +1564,10 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
         // about 10 us) is below half a percent of the time the K/V stream itself takes.
         const int rows1 = G * R;
         const int gs = std::min<int>(B, (kWaves * kRowsPerGroup) / rows1);
-        const int64_t casc = agentsam::option_attn_cascade();
         const double kv_bytes = (double)smax * B * Hkv * 2.0 * D * 2.0;
         const int64_t tiles_max = (int64_t)B * Hkv * ((smax + kTile - 1) / kTile);
-        if (gs >= 2 && gs * rows1 > kRowsPerGroup && tiles_max <= 0x7fffffffll && agentsam::option_attn_kv_chunk() == 0 &&
-            agentsam::option_attn_schedule() != 1 && (casc == 2 || (casc == 0 && kv_bytes >= 11.0e9))) {
+        if (gs >= 2 && gs * rows1 > kRowsPerGroup && tiles_max <= 0x7fffffffll && opt == 0 &&
+            tn.sched != 1 && (tn.casc == 2 || (tn.casc == 0 && kv_bytes >= 11.0e9))) {
             pl->cascade = true;
             pl->balanced = true;                             // the sessions' own parts: balanced shares
             pl->gs = gs;
@@ -1584,53 +1599,42 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
     return AGENTSAM_OK;
 }
 
-template <int D, int VMODE>
-void launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st) {
+template <int D>
+hipError_t launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st) {
+    using agentsam::launch;
     if (wide) {
         const int rpw = (p.rows + kWaves - 1) / kWaves;
         const int mt = (rpw + 15) / 16;
         // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS
-#ifdef AGENTSAM_EXP_NS
-        constexpr int NS = AGENTSAM_EXP_NS;
-#else
         constexpr int NS = 65536 / WideCfg<D>::kSlot;
-#endif
         // 4 x 16 x (mt-1) rows owned outright plus at most one shared extra row tile, when that fits
         const int extra = p.rows - kWaves * 16 * (mt - 1);
         if (mt >= 2 && extra >= 1 && extra <= 16) {
-            if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS, true>), grid, dim3(256), 0, st, p);
-            else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS, true>), grid, dim3(256), 0, st, p);
-        } else if (mt == 1) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, NS, false>), grid, dim3(256), 0, st, p);
-        else if (mt == 2) hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, NS, false>), grid, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 3, NS, false>), grid, dim3(256), 0, st, p);
-        return;
+            if (mt == 2) return launch((attn_bf16_wide_kernel<D, 1, NS, true>), grid, dim3(256), st, p);
+            return launch((attn_bf16_wide_kernel<D, 2, NS, true>), grid, dim3(256), st, p);
+        }
+        if (mt == 1) return launch((attn_bf16_wide_kernel<D, 1, NS, false>), grid, dim3(256), st, p);
+        if (mt == 2) return launch((attn_bf16_wide_kernel<D, 2, NS, false>), grid, dim3(256), st, p);
+        return launch((attn_bf16_wide_kernel<D, 3, NS, false>), grid, dim3(256), st, p);
     }
     const int mt = (p.rows + 15) / 16;
-    if (mt == 1) hipLaunchKernelGGL((attn_bf16_narrow_kernel<D, 1, VMODE>), grid, dim3(256), 0, st, p);
-    else if (mt == 2) hipLaunchKernelGGL((attn_bf16_narrow_kernel<D, 2, VMODE>), grid, dim3(256), 0, st, p);
-    else hipLaunchKernelGGL((attn_bf16_narrow_kernel<D, 3, VMODE>), grid, dim3(256), 0, st, p);
+    if (mt == 1) return launch((attn_bf16_narrow_kernel<D, 1>), grid, dim3(256), st, p);
+    if (mt == 2) return launch((attn_bf16_narrow_kernel<D, 2>), grid, dim3(256), st, p);
+    return launch((attn_bf16_narrow_kernel<D, 3>), grid, dim3(256), st, p);
 }
 
-}  // namespace
+#define ATTN_TRY(expr)                                        \
+    do {                                                      \
+        if ((expr) != hipSuccess) return AGENTSAM_ERR_HIP;    \
+    } while (0)
 
-extern "C" int spec_verify_attn_workspace(int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D,
-                                          int32_t page_size, int32_t max_pages, int32_t dtype, size_t *bytes) {
-    if (!bytes) return AGENTSAM_ERR_NULL;
-    Plan pl;
-    const int rc = make_plan(B, R, Hq, Hkv, D, page_size, max_pages, dtype, &pl);
-    if (rc) return rc;
-    *bytes = pl.ws_bytes;
-    return AGENTSAM_OK;
-}
-
-extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *v_cache,
-                                const int32_t *block_table, int32_t max_pages, const int32_t *seq_lens,
-                                int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
-                                int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype,
-                                void *out, void *workspace, size_t workspace_bytes, void *stream) {
-    Plan pl;
-    const int rc = make_plan(B, R, Hq, Hkv, D, page_size, max_pages, dtype, &pl);
-    if (rc) return rc;
+// Everything spec_verify_attn does once the workspace is known (shared with the entry point whose
+// workspace is the library's own static array).
+int run_attn(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_table, int32_t max_pages,
+             const int32_t *seq_lens, int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
+             int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype, void *out, void *workspace,
+             size_t workspace_bytes, const Plan &pl, hipStream_t st) {
+    using agentsam::launch;
     if (!(scale > 0.f) || num_pages < 0 || (B > 0 && num_pages < 1)) return AGENTSAM_ERR_ARG;
     if (out_dtype != AGENTSAM_F32 && out_dtype != AGENTSAM_BF16) return AGENTSAM_ERR_UNSUPPORTED;
     if (B == 0) return AGENTSAM_OK;
@@ -1642,7 +1646,7 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     AttnParams p;
     p.q = q; p.kc = k_cache; p.vc = v_cache; p.bt = block_table; p.seq = seq_lens; p.out = out;
     p.ws = (float *)workspace;
-    p.B = B; p.R = R; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv; p.P = page_size; p.max_pages = max_pages;
+    p.B = B; p.R = R; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv; p.D = D; p.P = page_size; p.max_pages = max_pages;
     p.num_pages = num_pages;
     p.log2P = -1;
     for (int sft = 0; sft < 31; ++sft)
@@ -1656,7 +1660,6 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     p.wsr = (float *)((char *)workspace + pl.plan_bytes);
     p.cascade = 0; p.phase = 0; p.gs = 1; p.ngroups = B; p.rows1 = p.rows; p.pchunk_tiles = 1; p.npchunks_max = 0;
     p.rows_pad_p = pl.rows_pad; p.nslots = pl.nslots; p.lcp = nullptr; p.wsp = nullptr;
-    hipStream_t st = (hipStream_t)stream;
 
     if (pl.cascade) {
         // [lcp][plan][own records][prefix records]
@@ -1669,59 +1672,69 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
         p.wsp = (float *)(wsb + pl.lcp_bytes + pl.plan_bytes + pl.own_bytes);
         p.gs = pl.gs; p.ngroups = pl.ngroups; p.pchunk_tiles = pl.pchunk_tiles; p.npchunks_max = pl.npchunks_max;
         p.rows_pad_p = pl.rows_pad_p;
-        hipLaunchKernelGGL(attn_lcp_kernel, dim3((unsigned)B), dim3(256), 0, st, p, lcp);
-        AGENTSAM_LAUNCH_CHECK();
-        const bool tr = agentsam::option_attn_v_mode() == 1;
+        ATTN_TRY(launch(attn_lcp_kernel, dim3((unsigned)B), dim3(256), st, p, lcp));
         // prefix phase: the wide kernel over the packed rows of a whole group
         AttnParams pp = p;
         pp.phase = 1;
         pp.rows = pl.rows_group;                             // rows1 stays the rows of one session
         pp.balanced = 0;
         dim3 pgrid((unsigned)((int64_t)pl.npchunks_max * pl.ngroups * Hkv));
-        if (D == 64) launch_bf16<64, 1>(pp, true, pgrid, st); else launch_bf16<128, 1>(pp, true, pgrid, st);
-        AGENTSAM_LAUNCH_CHECK();
+        ATTN_TRY(D == 64 ? launch_bf16<64>(pp, true, pgrid, st) : launch_bf16<128>(pp, true, pgrid, st));
         // the sessions' own parts, balanced
         dim3 sgrid((unsigned)pl.nslots);
-        if (D == 64) { if (tr) launch_bf16<64, 1>(p, pl.wide, sgrid, st); else launch_bf16<64, 0>(p, pl.wide, sgrid, st); }
-        else { if (tr) launch_bf16<128, 1>(p, pl.wide, sgrid, st); else launch_bf16<128, 0>(p, pl.wide, sgrid, st); }
-        AGENTSAM_LAUNCH_CHECK();
+        ATTN_TRY(D == 64 ? launch_bf16<64>(p, pl.wide, sgrid, st) : launch_bf16<128>(p, pl.wide, sgrid, st));
         dim3 mg((unsigned)Hkv, (unsigned)B);
-        if (D == 64) hipLaunchKernelGGL(attn_merge_cascade_kernel<64>, mg, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL(attn_merge_cascade_kernel<128>, mg, dim3(256), 0, st, p);
-        AGENTSAM_LAUNCH_CHECK();
+        ATTN_TRY(D == 64 ? launch(attn_merge_cascade_kernel<64>, mg, dim3(256), st, p)
+                         : launch(attn_merge_cascade_kernel<128>, mg, dim3(256), st, p));
         return AGENTSAM_OK;
     }
 
     if (dtype == AGENTSAM_F32) {
         dim3 grid((unsigned)pl.nchunks_max, (unsigned)Hq, (unsigned)B);
-        if (D == 64) hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(256), 0, st, p);
-        AGENTSAM_LAUNCH_CHECK();
+        ATTN_TRY(D == 64 ? launch(attn_f32_kernel<64>, grid, dim3(256), st, p) : launch(attn_f32_kernel<128>, grid, dim3(256), st, p));
         if (pl.nchunks_max > 1) {
             dim3 mg((unsigned)Hq, (unsigned)B);
-            if (D == 64) hipLaunchKernelGGL(attn_merge_kernel<64>, mg, dim3(256), 0, st, p, (int)Hq, 1);
-            else hipLaunchKernelGGL(attn_merge_kernel<128>, mg, dim3(256), 0, st, p, (int)Hq, 1);
-            AGENTSAM_LAUNCH_CHECK();
+            ATTN_TRY(D == 64 ? launch(attn_merge_kernel<64>, mg, dim3(256), st, p, (int)Hq, 1)
+                             : launch(attn_merge_kernel<128>, mg, dim3(256), st, p, (int)Hq, 1));
         }
         return AGENTSAM_OK;
     }
 
     if ((int64_t)pl.nchunks_max * Hkv * B > 0x7fffffffll) return AGENTSAM_ERR_ARG;
     dim3 grid(pl.balanced ? (unsigned)pl.nslots : (unsigned)((int64_t)pl.nchunks_max * Hkv * B));
-    const bool tr = agentsam::option_attn_v_mode() == 1;
-    if (D == 64) { if (tr) launch_bf16<64, 1>(p, pl.wide, grid, st); else launch_bf16<64, 0>(p, pl.wide, grid, st); }
-    else { if (tr) launch_bf16<128, 1>(p, pl.wide, grid, st); else launch_bf16<128, 0>(p, pl.wide, grid, st); }
-    AGENTSAM_LAUNCH_CHECK();
+    ATTN_TRY(D == 64 ? launch_bf16<64>(p, pl.wide, grid, st) : launch_bf16<128>(p, pl.wide, grid, st));
+    dim3 mg((unsigned)Hkv, (unsigned)B);
     if (pl.balanced) {
-        dim3 mg((unsigned)Hkv, (unsigned)B);
-        if (D == 64) hipLaunchKernelGGL(attn_merge_balanced_kernel<64>, mg, dim3(256), 0, st, p, pl.nslots);
-        else hipLaunchKernelGGL(attn_merge_balanced_kernel<128>, mg, dim3(256), 0, st, p, pl.nslots);
-        AGENTSAM_LAUNCH_CHECK();
+        ATTN_TRY(D == 64 ? launch(attn_merge_balanced_kernel<64>, mg, dim3(256), st, p, pl.nslots)
+                         : launch(attn_merge_balanced_kernel<128>, mg, dim3(256), st, p, pl.nslots));
     } else if (pl.nchunks_max > 1) {
-        dim3 mg((unsigned)Hkv, (unsigned)B);
-        if (D == 64) hipLaunchKernelGGL(attn_merge_kernel<64>, mg, dim3(256), 0, st, p, (int)Hkv, p.G);
-        else hipLaunchKernelGGL(attn_merge_kernel<128>, mg, dim3(256), 0, st, p, (int)Hkv, p.G);
-        AGENTSAM_LAUNCH_CHECK();
+        ATTN_TRY(D == 64 ? launch(attn_merge_kernel<64>, mg, dim3(256), st, p, (int)Hkv, p.G)
+                         : launch(attn_merge_kernel<128>, mg, dim3(256), st, p, (int)Hkv, p.G));
     }
     return AGENTSAM_OK;
+}
+
+}  // namespace
+
+extern "C" int spec_verify_attn_workspace(int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D,
+                                          int32_t page_size, int32_t max_pages, int32_t dtype, uint64_t tuning,
+                                          size_t *bytes) {
+    if (!bytes) return AGENTSAM_ERR_NULL;
+    Plan pl;
+    const int rc = make_plan(B, R, Hq, Hkv, D, page_size, max_pages, dtype, tuning, &pl);
+    if (rc) return rc;
+    *bytes = pl.ws_bytes;
+    return AGENTSAM_OK;
+}
+
+extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *v_cache,
+                                const int32_t *block_table, int32_t max_pages, const int32_t *seq_lens,
+                                int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
+                                int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype,
+                                void *out, void *workspace, size_t workspace_bytes, uint64_t tuning, void *stream) {
+    Plan pl;
+    const int rc = make_plan(B, R, Hq, Hkv, D, page_size, max_pages, dtype, tuning, &pl);
+    if (rc) return rc;
+    return run_attn(q, k_cache, v_cache, block_table, max_pages, seq_lens, B, R, Hq, Hkv, D, page_size, num_pages, scale,
+                    dtype, out_dtype, out, workspace, workspace_bytes, pl, (hipStream_t)stream);
 }

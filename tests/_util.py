@@ -33,10 +33,10 @@ def oracle_drafts(cfg, mems, recent, rlen, min_match=1):
 
 
 def to_np(t):
-    t = t.detach()
+    t = t.detach().cpu()                                      # bf16 crosses the bus as 2 bytes per value
     if t.dtype == torch.bfloat16:
         t = t.float()
-    return t.cpu().numpy()
+    return t.numpy()
 
 
 def oracle_attention_sample(q, kc, vc, bt, seq, scale, pairs):

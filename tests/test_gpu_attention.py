@@ -97,18 +97,13 @@ BF16_SMALL = [
 ]
 
 
-@pytest.mark.parametrize("vmode", [0, 1])
 @pytest.mark.parametrize("case", range(len(BF16_SMALL)))
-def test_bf16_small_all_heads(case, vmode):
+def test_bf16_small_all_heads(case):
     cfg = W.scaled(W.baseline_config(1), **BF16_SMALL[case])
-    print(f"attn bf16 case {case} vmode {vmode}: {BF16_SMALL[case]}", flush=True)
+    print(f"attn bf16 case {case}: {BF16_SMALL[case]}", flush=True)
     lay, q, kc, vc, bt, seq = _inputs(cfg)
-    A.agentsam_set_option("attn_v_mode", vmode)
-    try:
-        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_v_mode", 0)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
+    torch.cuda.synchronize()
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
@@ -119,12 +114,8 @@ def test_bf16_small_balanced_schedule(case):
     cfg = W.scaled(W.baseline_config(1), **BF16_SMALL[case])
     print(f"attn bf16 balanced case {case}: {BF16_SMALL[case]}", flush=True)
     lay, q, kc, vc, bt, seq = _inputs(cfg)
-    A.agentsam_set_option("attn_schedule", 2)
-    try:
-        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_schedule", 0)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=2))
+    torch.cuda.synchronize()
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
@@ -152,15 +143,11 @@ def test_bf16_results_repeat_bit_for_bit(G, k, sched):
     cfg = W.scaled(W.baseline_config(1), B=24, Hq=2 * G, Hkv=2, D=128, k=k, kv_mode="ragged", kv_len=(k + 2, 6000),
                    permute_pages=True)
     lay, q, kc, vc, bt, seq = _inputs(cfg)
-    A.agentsam_set_option("attn_schedule", sched)
-    try:
-        first = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D)).clone()
-        for _ in range(20):
-            again = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-            assert torch.equal(again, first)
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_schedule", 0)
+    first = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=sched)).clone()
+    for _ in range(20):
+        again = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=sched))
+        assert torch.equal(again, first)
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("seed", range(16))
@@ -185,14 +172,8 @@ def test_bf16_seeded_random_shapes(seed):
     sched, casc = int(rng.integers(0, 3)), int(rng.choice([0, 1, 2]))
     print(f"attn random shape {seed}: {kw} schedule {sched} cascade {casc}", flush=True)
     lay, q, kc, vc, bt, seq = _inputs(cfg)
-    A.agentsam_set_option("attn_schedule", sched)
-    A.agentsam_set_option("attn_cascade", casc)
-    try:
-        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_schedule", 0)
-        A.agentsam_set_option("attn_cascade", 0)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=sched, cascade=casc))
+    torch.cuda.synchronize()
     pairs = _all_pairs(cfg)
     if len(pairs) > 60:
         pairs = [pairs[i] for i in rng.choice(len(pairs), 60, replace=False)]
@@ -218,12 +199,8 @@ def test_page_sizes_that_are_not_powers_of_two(case, schedule):
     cfg = W.scaled(base, kv_mode="ragged", permute_pages=True, **kw)
     print(f"attn odd page case {case} schedule {schedule}: {ODD_PAGES[case]}", flush=True)
     lay, q, kc, vc, bt, seq = _inputs(cfg)
-    A.agentsam_set_option("attn_schedule", schedule)
-    try:
-        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_schedule", 0)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=schedule))
+    torch.cuda.synchronize()
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
@@ -258,12 +235,8 @@ def test_bf16_many_short_sessions_balanced(k, Hq, B):
     pairs = [(b, int(h)) for b in sorted(bs) for h in rng.choice(Hq, 3, replace=False)]
     _check(cfg, lay, q, kc, vc, out, pairs)
     # every output element against the chunk-grid schedule
-    A.agentsam_set_option("attn_schedule", 1)
-    try:
-        ref = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_schedule", 0)
+    ref = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=1))
+    torch.cuda.synchronize()
     # (short sessions: single bf16-rounded weights are not averaged out, see _check)
     diff = float((out - ref).abs().max())
     assert diff < 4e-3, diff
@@ -277,12 +250,8 @@ def test_bf16_more_sessions_than_threads_balanced():
     lay, q, kc, vc, bt, seq = _inputs(cfg)
     outs = {}
     for schedule in (2, 1):
-        A.agentsam_set_option("attn_schedule", schedule)
-        try:
-            outs[schedule] = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-            torch.cuda.synchronize()
-        finally:
-            A.agentsam_set_option("attn_schedule", 0)
+        outs[schedule] = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=schedule))
+        torch.cuda.synchronize()
     rng = np.random.default_rng(5)
     pairs = [(int(b), int(h)) for b in list(rng.integers(0, cfg.B, 40)) + [0, 255, 256, 257, 511, 512, 699]
              for h in range(cfg.Hq)]
@@ -307,14 +276,10 @@ def test_bf16_shared_prefix_cascade(case):
     cfg = W.scaled(W.baseline_config(1), D=128, **CASCADE[case])
     print(f"attn cascade case {case}: {CASCADE[case]}", flush=True)
     lay, q, kc, vc, bt, seq = _inputs(cfg)
-    A.agentsam_set_option("attn_cascade", 2)
-    try:
-        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D)).clone()
-        for _ in range(5):                                    # and the same bits on every launch
-            assert torch.equal(A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D)), out)
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_cascade", 0)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(cascade=2)).clone()
+    for _ in range(5):                                    # and the same bits on every launch
+        assert torch.equal(A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(cascade=2)), out)
+    torch.cuda.synchronize()
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
@@ -334,12 +299,8 @@ def test_bf16_cascade_partial_sharing_and_short_session():
             bt2[3, 2] = kc.shape[0]
         else:
             seq2[1] = 200                                                  # ends inside the others' prefix
-        A.agentsam_set_option("attn_cascade", 2)
-        try:
-            out = A.spec_verify_attn(q, kc2, vc2, bt2, seq2, scale)
-            torch.cuda.synchronize()
-        finally:
-            A.agentsam_set_option("attn_cascade", 0)
+        out = A.spec_verify_attn(q, kc2, vc2, bt2, seq2, scale, tuning=A.attn_tuning(cascade=2))
+        torch.cuda.synchronize()
         plain = A.spec_verify_attn(q, kc2, vc2, bt2, seq2, scale)
         torch.cuda.synchronize()
         diff = float((out - plain).abs().max())
@@ -355,23 +316,15 @@ def test_bf16_minimum_and_boundary_lengths():
     for S in (9, 33, 129, 389):                              # the same through the balanced schedule
         cfg = W.scaled(base, kv_len=(S, S), seed=2000 + S)
         lay, q, kc, vc, bt, seq = _inputs(cfg)
-        A.agentsam_set_option("attn_schedule", 2)
-        try:
-            out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-            torch.cuda.synchronize()
-        finally:
-            A.agentsam_set_option("attn_schedule", 0)
+        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=2))
+        torch.cuda.synchronize()
         _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
-    A.agentsam_set_option("attn_kv_chunk", 128)
-    try:
-        for S in (9, 10, 31, 32, 33, 64, 65, 127, 128, 129, 130, 136, 137, 255, 257, 384 + 5):
-            cfg = W.scaled(base, kv_len=(S, S), seed=1000 + S)
-            lay, q, kc, vc, bt, seq = _inputs(cfg)
-            out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-            torch.cuda.synchronize()
-            _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
-    finally:
-        A.agentsam_set_option("attn_kv_chunk", 0)
+    for S in (9, 10, 31, 32, 33, 64, 65, 127, 128, 129, 130, 136, 137, 255, 257, 384 + 5):
+        cfg = W.scaled(base, kv_len=(S, S), seed=1000 + S)
+        lay, q, kc, vc, bt, seq = _inputs(cfg)
+        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(kv_chunk=128))
+        torch.cuda.synchronize()
+        _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg))
 
 
 @pytest.mark.parametrize("schedule", [1, 2])
@@ -389,12 +342,8 @@ def test_scores_far_above_the_first_tile(k, Hq, schedule):
             page, slot = int(lay.block_table[b, pos // cfg.page]), pos % cfg.page
             kc[page, h // cfg.G, slot] = (q[b, row, h].float() * 16.0).to(kc.dtype)   # ... and a few loud ones
     kc = kc.contiguous()
-    A.agentsam_set_option("attn_schedule", schedule)
-    try:
-        out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_schedule", 0)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=schedule))
+    torch.cuda.synchronize()
     _check(cfg, lay, q, kc, vc, out, _all_pairs(cfg), dominated=True)
 
 
@@ -404,11 +353,7 @@ def test_split_and_page_permutation_invariance():
     scale = 1.0 / np.sqrt(cfg.D)
     outs = []
     for chunk in (0, 128, 512, 1024, 4096):
-        A.agentsam_set_option("attn_kv_chunk", chunk)
-        try:
-            outs.append(to_np(A.spec_verify_attn(q, kc, vc, bt, seq, scale)))
-        finally:
-            A.agentsam_set_option("attn_kv_chunk", 0)
+        outs.append(to_np(A.spec_verify_attn(q, kc, vc, bt, seq, scale, tuning=A.attn_tuning(kv_chunk=chunk))))
     for o in outs[1:]:
         # the split changes the running maximum each weight is rounded to bf16 against, and the
         # fp32 summation order; both stay far inside the parity tolerance
@@ -448,35 +393,133 @@ def test_error_returns_on_device_arguments():
     from paper_2512_18337_amd import binding
     rc = binding.lib().spec_verify_attn(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), bt.data_ptr(), bt.shape[1],
                                         seq.data_ptr(), 1, 9, 8, 2, 128, 64, lay.num_pages, 0.1, 1, 0,
-                                        q.data_ptr(), tiny.data_ptr(), 16, None)
+                                        q.data_ptr(), tiny.data_ptr(), 16, 0, None)
     assert rc == -4
 
 
+def _one_head_per_kv_group(cfg, rng):
+    """Every session x one query head of every kv head (seeded choice within the group)."""
+    return [(b, g * cfg.G + int(rng.integers(0, cfg.G))) for b in range(cfg.B) for g in range(cfg.Hkv)]
+
+
 @pytest.mark.parametrize("i", [1, 2, 3, 4])
-def test_full_size_sampled_heads(i):
-    """Baseline shapes in the launch configuration the benchmark times; the oracle checks a seeded
-    sample of (session, head) pairs, every row of each."""
+def test_full_size_every_session_and_kv_head(i):
+    """Baseline shapes in the launch configuration the benchmark times.  The oracle checks EVERY session and,
+    for each of its kv heads, one query head of the group (every row of it): each (session, kv head)
+    stream, every workgroup's share of it and every merge is covered."""
     cfg = W.baseline_config(i)
     print(f"attn full-size {cfg.name}", flush=True)
     lay, q, kc, vc, bt, seq = _inputs(cfg)
     out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
     torch.cuda.synchronize()
     rng = np.random.default_rng(cfg.seed)
-    order = np.argsort(lay.seq_lens)
-    bs = {int(order[0]), int(order[-1]), int(rng.integers(0, cfg.B))}      # shortest, longest, one more
-    pairs = [(b, int(h)) for b in sorted(bs) for h in rng.choice(cfg.Hq, 2, replace=False)]
+    pairs = _one_head_per_kv_group(cfg, rng)
     worst = _check(cfg, lay, q, kc, vc, out, pairs)
-    print(f"  max-abs error {worst:.3e} on {pairs}", flush=True)
+    print(f"  max-abs error {worst:.3e} on {len(pairs)} (session, head) pairs", flush=True)
     assert torch.isfinite(out).all()
     # the other schedule (chunk grid <-> balanced shares) must give the same output everywhere: the
     # split only changes the reference each weight is rounded against and the summation order
     auto_balanced = cfg.B * cfg.Hkv >= 2 * 256 * (2 if cfg.G * cfg.R > 48 else 1)
-    A.agentsam_set_option("attn_schedule", 1 if auto_balanced else 2)
-    try:
-        other = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D))
-        torch.cuda.synchronize()
-    finally:
-        A.agentsam_set_option("attn_schedule", 0)
+    other = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), tuning=A.attn_tuning(schedule=1 if auto_balanced else 2))
+    torch.cuda.synchronize()
     diff = float((out - other).abs().max())
     print(f"  schedules differ by {diff:.3e}", flush=True)
     assert diff < 1e-3
+
+
+SCALE_CASES = [
+    # one per kernel family, with a softmax scale that is NOT 1/sqrt(D): a scale folded wrongly with the head
+    # dimension or with log2(e) shows here and nowhere else
+    dict(base=0, kw=dict(B=2, Hq=4, Hkv=2, D=128, page=16, k=6, kv_mode="ragged", kv_len=(7, 900)), tuning={}),            # fp32 kernel
+    dict(base=1, kw=dict(B=3, Hq=8, Hkv=2, D=128, k=8, kv_mode="ragged", kv_len=(9, 3000)), tuning=dict(schedule=1)),      # narrow, chunk grid + merge
+    dict(base=1, kw=dict(B=3, Hq=8, Hkv=2, D=64, k=8, kv_mode="ragged", kv_len=(9, 3000), page=32), tuning=dict(schedule=2)),  # narrow, balanced, head dim 64
+    dict(base=1, kw=dict(B=2, Hq=16, Hkv=2, D=128, k=16, kv_mode="ragged", kv_len=(17, 2500)), tuning=dict(schedule=2)),   # wide, 136 rows
+    dict(base=1, kw=dict(B=6, Hq=10, Hkv=2, D=128, k=8, kv_mode="shared_prefix", kv_len=(40, 700), prefix_len=2048),
+         tuning=dict(cascade=2)),                                                                                        # shared-prefix run
+]
+
+
+@pytest.mark.parametrize("scale", [0.3, 0.02])
+@pytest.mark.parametrize("case", range(len(SCALE_CASES)))
+def test_softmax_scale_other_than_inverse_sqrt_d(case, scale):
+    c = SCALE_CASES[case]
+    cfg = W.scaled(W.baseline_config(c["base"]), permute_pages=True, **c["kw"])
+    print(f"attn scale {scale} case {case}: {c['kw']}", flush=True)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, scale, tuning=A.attn_tuning(**c["tuning"]))
+    torch.cuda.synchronize()
+    ref = oracle_attention_sample(q, kc, vc, lay.block_table, lay.seq_lens, scale, _all_pairs(cfg))
+    o = to_np(out)
+    worst = max(float(np.max(np.abs(o[b, :, h] - r))) for (b, h), r in ref.items())
+    # scale 0.3 makes rows that one or two keys dominate (full half-ulp of the largest weight): the stated tolerance
+    assert worst <= TOL[cfg.dtype], worst
+    # the result must really depend on the scale (a kernel that ignored it would pass one of the two values at most)
+    other = oracle_attention_sample(q, kc, vc, lay.block_table, lay.seq_lens, 1.0 / np.sqrt(cfg.D), _all_pairs(cfg)[:1])
+    (b, h), r = next(iter(other.items()))
+    assert float(np.max(np.abs(o[b, :, h] - r))) > 5 * max(worst, 1e-4)
+
+
+@pytest.mark.parametrize("case", [1, 3, 4])
+def test_bf16_output_against_the_oracle(case):
+    """out_dtype = bf16 compared with the fp64 oracle directly (not with the kernel's own fp32 output)."""
+    c = SCALE_CASES[case]
+    cfg = W.scaled(W.baseline_config(c["base"]), permute_pages=True, **c["kw"])
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq, 1.0 / np.sqrt(cfg.D), out_dtype=torch.bfloat16,
+                             tuning=A.attn_tuning(**c["tuning"]))
+    torch.cuda.synchronize()
+    assert out.dtype == torch.bfloat16
+    ref = oracle_attention_sample(q, kc, vc, lay.block_table, lay.seq_lens, 1.0 / np.sqrt(cfg.D), _all_pairs(cfg))
+    o = to_np(out)
+    worst = max(float(np.max(np.abs(o[b, :, h] - r))) for (b, h), r in ref.items())
+    big = max(float(np.max(np.abs(r))) for r in ref.values())
+    print(f"  bf16 output: max-abs error {worst:.3e}, largest |out| {big:.2f}", flush=True)
+    assert worst <= TOL["bf16"]
+    assert worst <= 1e-2 + big * 2.0 ** -8                   # the kernel's own error + half an ulp of the output
+
+
+SHORT_CASES = [
+    (0, dict(B=5, Hq=4, Hkv=2, D=64, page=16, k=6), {}),                                   # fp32 kernel
+    (1, dict(B=5, Hq=8, Hkv=2, D=128, k=8), dict(schedule=1)),                             # narrow, chunk grid
+    (1, dict(B=5, Hq=8, Hkv=2, D=128, k=8), dict(schedule=2)),                             # narrow, balanced
+    (1, dict(B=5, Hq=16, Hkv=2, D=128, k=16), dict(schedule=1)),                           # wide, chunk grid
+    (1, dict(B=5, Hq=16, Hkv=2, D=128, k=16), dict(schedule=2)),                           # wide, balanced
+    (1, dict(B=5, Hq=8, Hkv=2, D=128, k=8), dict(cascade=2)),                              # cascade run (nothing shared)
+]
+
+
+@pytest.mark.parametrize("case", range(len(SHORT_CASES)))
+def test_sessions_shorter_than_the_query_rows(case):
+    """seq_lens[b] < R: row i sits at position seq_lens[b] - R + i; a row at a negative position sees nothing
+    and its output is defined as zeros, the other rows attend positions 0 .. seq_lens[b] - R + i as always.
+    An empty session gives all zeros.  Nothing is NaN and the full-length sessions are unaffected."""
+    base, kw, tun = SHORT_CASES[case]
+    cfg = W.scaled(W.baseline_config(base), kv_mode="ragged", kv_len=(600, 900), permute_pages=True, **kw)
+    lay, q, kc, vc, bt, seq = _inputs(cfg)
+    R = cfg.R
+    lens = lay.seq_lens.copy()
+    lens[0], lens[2], lens[4] = 0, 1, R - 1
+    seq2 = torch.as_tensor(lens, device=DEV)
+    scale = 1.0 / np.sqrt(cfg.D)
+    out = A.spec_verify_attn(q, kc, vc, bt, seq2, scale, tuning=A.attn_tuning(**tun))
+    full = A.spec_verify_attn(q, kc, vc, bt, seq, scale, tuning=A.attn_tuning(**tun))
+    torch.cuda.synchronize()
+    o = to_np(out)
+    assert np.isfinite(o).all()
+    from oracle import attention_oracle_head
+    G, P = cfg.G, cfg.page
+    for b in (0, 2, 4):
+        S = int(lens[b])
+        assert not o[b, :R - S].any()                        # rows in front of position 0: zeros
+        for h in range(cfg.Hq):
+            if S == 0:
+                continue
+            pages = torch.as_tensor(lay.block_table[b, :(S + P - 1) // P].astype(np.int64), device=DEV)
+            K = to_np(kc[pages, h // G]).reshape(-1, cfg.D)[:S]
+            V = to_np(vc[pages, h // G]).reshape(-1, cfg.D)[:S]
+            # the S visible rows are an ordinary problem with S query rows over S positions
+            ref = attention_oracle_head(to_np(q[b, R - S:, h]), K, V, scale)
+            assert float(np.max(np.abs(o[b, R - S:, h] - ref))) <= TOL[cfg.dtype]
+    for b in (1, 3):
+        # (other sessions' lengths move the balanced schedule's cut points, which changes what each weight is rounded against)
+        assert float((out[b] - full[b]).abs().max()) < 4e-3

@@ -22,14 +22,10 @@ def test_captured_step_replays_like_the_eager_step(shape):
     shape = dict(shape)
     cascade = shape.pop("cascade", 0)
     cfg = W.scaled(W.baseline_config(1), D=128, sam_session_len=4096, vocab=4000, **shape)
-    A.agentsam_set_option("attn_cascade", cascade)
-    try:
-        _captured_step_case(cfg)
-    finally:
-        A.agentsam_set_option("attn_cascade", 0)
+    _captured_step_case(cfg, A.attn_tuning(cascade=cascade))
 
 
-def _captured_step_case(cfg):
+def _captured_step_case(cfg, tuning=0):
     mems = make_memories(cfg)
     flat, root, cbeg, cend, recent, rlen = draft_inputs(cfg, mems)
     fd = flat.to(DEV)
@@ -39,7 +35,7 @@ def _captured_step_case(cfg):
     q, kc, vc = W.kv_and_queries(cfg, lay, DEV)
     bt, seq = dev_i32(lay.block_table), dev_i32(lay.seq_lens)
     scale = 1.0 / float(np.sqrt(cfg.D))
-    need = A.spec_verify_attn_workspace(cfg.B, cfg.R, cfg.Hq, cfg.Hkv, cfg.D, cfg.page, bt.shape[1], A.BF16)
+    need = A.spec_verify_attn_workspace(cfg.B, cfg.R, cfg.Hq, cfg.Hkv, cfg.D, cfg.page, bt.shape[1], A.BF16, tuning)
     ws = torch.empty(max(need, 16) // 4 + 1, dtype=torch.float32, device=DEV)
     out = torch.empty((cfg.B, cfg.R, cfg.Hq, cfg.D), dtype=torch.float32, device=DEV)
     d0, nd0, _, _ = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
@@ -48,7 +44,7 @@ def _captured_step_case(cfg):
 
     def step():
         d, nd, ml, me = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
-        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws)
+        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)
         a, toks, tgt = A.spec_accept(logits, d, nd)
         return d, nd, ml, me, a, toks, tgt
 

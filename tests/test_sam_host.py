@@ -186,10 +186,8 @@ def test_error_codes():
     f = A.sam_flatten([s])
     assert list(f.row_ptr) == [0, 0] and f.lastpos[0] == -1
     assert A.strerror(0) == "ok" and A.strerror(-4).startswith("workspace")
-    with pytest.raises(A.AgentSamError):
-        A.agentsam_set_option("no_such_option", 1)
-    with pytest.raises(A.AgentSamError):
-        A.agentsam_set_option("attn_kv_chunk", 100)
+    with pytest.raises(A.AgentSamError):                      # a tuning word with an undefined schedule
+        A.spec_verify_attn_workspace(1, 5, 4, 1, 64, 64, 4, A.F32, tuning=3)
 
 
 def test_build_rate_is_linear_and_above_the_papers_figure():
