@@ -323,6 +323,23 @@ int spec_verify_attn(const void *q, const void *k_cache, const void *v_cache,
                      int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype,
                      void *out, void *workspace, size_t workspace_bytes, uint64_t tuning, void *stream);
 
+/* spec_verify_attn_static: spec_verify_attn for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments,
+ * results and errors, but no workspace argument: the partial results go to a static device array
+ * inside the library, AGENTSAM_STATIC_WORKSPACE_BYTES (32 MiB) per GPU, held until the process ends.
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library routine).
+ * AGENTSAM_ERR_WORKSPACE when spec_verify_attn_workspace() for the same arguments exceeds that size
+ * (the headline batch, 64 sessions x 8 kv heads of 36 packed rows, needs 9.6 MB).  All calls on one
+ * GPU share the one array: calls that overlap on a GPU (two streams, two threads) race and give
+ * undefined results; calls ordered on one stream are safe.  The first call on a GPU looks the
+ * array's address up (no device work): make it outside a graph capture. */
+#define AGENTSAM_STATIC_WORKSPACE_BYTES (32u << 20)
+int spec_verify_attn_static(const void *q, const void *k_cache, const void *v_cache,
+                            const int32_t *block_table, int32_t max_pages, const int32_t *seq_lens,
+                            int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
+                            int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype,
+                            void *out, uint64_t tuning, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * spec_accept (Alg. 4: "commit matched prefix; on mismatch fall back to standard decoding";
  * Sec. 5.4.1: lossless, i.e. the output equals greedy decoding).

@@ -25,7 +25,7 @@ _vp = ctypes.c_void_p
 EXPORTS = ["agentsam_strerror", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
-           "sam_draft", "sam_draft_delta", "sam_draft_step", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_accept",
+           "sam_draft", "sam_draft_delta", "sam_draft_step", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_verify_attn_static", "spec_accept",
            "spec_adaptive_k", "agentsched_pick"]
 
 
@@ -79,6 +79,9 @@ def lib():
         L.spec_verify_attn.argtypes = ([_vp, _vp, _vp, _vp, ctypes.c_int32, _vp] + [ctypes.c_int32] * 6 +
                                        [ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
                                         _vp, _vp, ctypes.c_size_t, ctypes.c_uint64, _vp])
+        L.spec_verify_attn_static.argtypes = ([_vp, _vp, _vp, _vp, ctypes.c_int32, _vp] + [ctypes.c_int32] * 6 +
+                                              [ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
+                                               _vp, ctypes.c_uint64, _vp])
         L.spec_accept.argtypes = [_vp, ctypes.c_int32, _vp, _vp, ctypes.c_int32, ctypes.c_int32,
                                   ctypes.c_int64, _vp, _vp, _vp, _vp]
         _lib = L
@@ -474,6 +477,25 @@ def spec_verify_attn(q, k_cache, v_cache, block_table, seq_lens, scale: float, o
                                 _dp(out), _dp(workspace), workspace.numel() * workspace.element_size(),
                                 int(tuning), _stream_ptr())
     _check(rc, "spec_verify_attn")
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def spec_verify_attn_static(q, k_cache, v_cache, block_table, seq_lens, scale: float, out, tuning: int = 0):
+    """spec_verify_attn with the library's static workspace; `out` is the caller's (this call allocates nothing)."""
+    import torch
+    B, R, Hq, D = q.shape
+    num_pages, Hkv, P, D2 = k_cache.shape
+    assert D2 == D and v_cache.shape == k_cache.shape and k_cache.dtype == q.dtype == v_cache.dtype
+    assert q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous() and out.is_contiguous()
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous() and seq_lens.dtype == torch.int32
+    assert tuple(out.shape) == (B, R, Hq, D)
+    rc = lib().spec_verify_attn_static(_dp(q), _dp(k_cache), _dp(v_cache), _dp(block_table), block_table.shape[1],
+                                       _dp(seq_lens), B, R, Hq, Hkv, D, P, num_pages, float(scale), _dtype_code(q),
+                                       _dtype_code(out), _dp(out), int(tuning), _stream_ptr())
+    _check(rc, "spec_verify_attn_static")
     return out
 
 

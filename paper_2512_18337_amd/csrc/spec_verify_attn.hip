@@ -28,6 +28,11 @@
 
 #include "common.h"
 
+// Workspace of spec_verify_attn_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; the kernels get the device
+// address that call returns.
+static __device__ __align__(256) unsigned char scratch[AGENTSAM_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -1737,4 +1742,40 @@ extern "C" int spec_verify_attn(const void *q, const void *k_cache, const void *
     if (rc) return rc;
     return run_attn(q, k_cache, v_cache, block_table, max_pages, seq_lens, B, R, Hq, Hkv, D, page_size, num_pages, scale,
                     dtype, out_dtype, out, workspace, workspace_bytes, pl, (hipStream_t)stream);
+}
+
+// ---- the entry point that allocates nothing, for callers that cannot (graph capture, tight loops)
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];              // device address of `scratch`, per device
+
+int static_workspace(void **ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return AGENTSAM_ERR_HIP;
+    void *pv = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!pv) {
+        // every GPU holds its own copy of the array at its own address: ask with that device current
+        if (hipGetSymbolAddress(&pv, HIP_SYMBOL(scratch)) != hipSuccess || !pv) return AGENTSAM_ERR_HIP;
+        g_scratch_ptr[dev].store(pv, std::memory_order_release);   // (two threads racing here store the same value)
+    }
+    *ptr = pv;
+    return AGENTSAM_OK;
+}
+}  // namespace
+
+extern "C" int spec_verify_attn_static(const void *q, const void *k_cache, const void *v_cache,
+                                       const int32_t *block_table, int32_t max_pages, const int32_t *seq_lens,
+                                       int32_t B, int32_t R, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
+                                       int64_t num_pages, float scale, int32_t dtype, int32_t out_dtype,
+                                       void *out, uint64_t tuning, void *stream) {
+    Plan pl;
+    const int rc = make_plan(B, R, Hq, Hkv, D, page_size, max_pages, dtype, tuning, &pl);
+    if (rc) return rc;
+    if (pl.ws_bytes > (size_t)AGENTSAM_STATIC_WORKSPACE_BYTES) return AGENTSAM_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (const int rs = static_workspace(&ws)) return rs;
+    // Nothing in the workspace has to start at zero: every record, prefix sum and page count a launch
+    // reads was written earlier in the same call, so the previous call's contents are simply overwritten.
+    return run_attn(q, k_cache, v_cache, block_table, max_pages, seq_lens, B, R, Hq, Hkv, D, page_size, num_pages, scale,
+                    dtype, out_dtype, out, ws, (size_t)AGENTSAM_STATIC_WORKSPACE_BYTES, pl, (hipStream_t)stream);
 }
