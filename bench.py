@@ -6,15 +6,22 @@ of synthetic sessions (inputs resident in HBM before the timed region).  The def
 is the configuration the headline metric is quoted on: B=64 sessions, 32k-token KV per session,
 k=8 drafts (baseline workload 2).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--seed S] [--no-cpu-baseline]
+                    [--no-targets] [--ksweep] [--maintain STEPS] ...
+
+Beside the headline step the default run also times spec_verify_attn alone on workloads 3 and 4
+(`detail.targets`), the two other configurations the bandwidth target is stated for.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
+import hashlib
 import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -22,15 +29,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
-
-# HBM bytes of one spec_verify_attn launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE
-# runs, scaled by a copy kernel of known size); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2-b64-32k": 8.605e9,         # profiles/spec_verify_attn_cfg2_hbm_traffic.txt
-    "cfg3-ragged-b128": 18.32e9,     # profiles/spec_verify_attn_cfg3_kernel_trace_and_traffic.txt
-    "cfg4-shared-prefix": 2.25e9,    # profiles/spec_verify_attn_cfg4_kernel_trace_and_traffic.txt (logical bytes: 14.19e9)
-    "cfg1-b16-8k": 0.551e9,          # profiles/spec_verify_attn_cfg1_kernel_trace_and_traffic.txt
-}
+MFMA_PEAK_TFLOPS = 2500.0        # MI355X published dense bf16 matrix rate
+ATTN_SOURCE = os.path.join(ROOT, "paper_2512_18337_amd", "csrc", "spec_verify_attn.hip")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
 
 def parse():
@@ -39,11 +40,16 @@ def parse():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="baseline workload index (default: the headline one)")
+    ap.add_argument("--seed", type=int, default=None, help="seed of the synthetic inputs (default: the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-targets", action="store_true", help="skip the attention-only timings of workloads 3 and 4")
     ap.add_argument("--attn-only", action="store_true", help="time only spec_verify_attn (for profiling)")
     ap.add_argument("--kv-chunk", type=int, default=0)
-    ap.add_argument("--schedule", type=int, default=0, help="attn_schedule option: 0 auto, 1 chunk grid, 2 balanced")
-    ap.add_argument("--cascade", type=int, default=0, help="attn_cascade option: 0 auto, 1 off, 2 on")
+    ap.add_argument("--schedule", type=int, default=0, help="attention schedule: 0 auto, 1 chunk grid, 2 balanced")
+    ap.add_argument("--cascade", type=int, default=0, help="shared-prefix run: 0 auto, 1 off, 2 on")
+    ap.add_argument("--ksweep", action="store_true",
+                    help="also time spec_verify_attn for k = 0..16 drafts on this workload's batch and context lengths and "
+                         "derive the speculation controller's choice from that table (detail.ksweep)")
     ap.add_argument("--maintain", type=int, default=0, metavar="STEPS",
                     help="also time STEPS rounds of incremental automaton maintenance (append, delta export, "
                          "device update, sam_draft_delta); reported under detail.sam_maintenance")
@@ -58,65 +64,77 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h, budget_s=20.0):
-    """The CPU oracle as it stands, timed on this machine's host cores on a bounded sample of the step."""
+# ------------------------------------------------------------------------------------- CPU oracle timing
+def host_threads() -> int:
+    """Host cores this process may use (a one-GPU machine gives 16 whatever the machine has)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(n, 16))
+
+
+def cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h, budget_s=18.0):
+    """The CPU oracle as it stands, timed on this machine's host cores on a bounded sample of the step: once with
+    its sessions / (session, head) pairs farmed out to one thread per core (the numerical library held to one
+    thread each), once on a single thread."""
     import torch
-    from oracle import accept_oracle, attention_oracle_head, draft_oracle_batch
+    from threadpoolctl import threadpool_limits
+    from oracle import accept_oracle, attention_oracle_head, draft_oracle
     from oracle.attention import gather_kv
-    cpu0, wall0 = time.process_time(), time.perf_counter()
-    # draft lookup: every session
-    T = np.concatenate(mems)
-    if cfg.sam_mode == "per_session":
-        sizes = np.array([len(m) for m in mems], dtype=np.int64)
-        begin = np.concatenate([[0], np.cumsum(sizes)[:-1]]); end = begin + sizes
-    else:
-        begin = np.zeros(cfg.B, dtype=np.int64); end = np.full(cfg.B, len(T), dtype=np.int64)
-    t0 = time.perf_counter()
-    draft_oracle_batch(T, begin, end, recent, rlen, cfg.k, cfg.sep)
-    t_draft = time.perf_counter() - t0
-    # accept: every row
-    lg = logits.float().cpu().numpy()
-    t0 = time.perf_counter()
-    accept_oracle(lg, draft_h, nd_h)
-    t_accept = time.perf_counter() - t0
-    # attention: seeded sample of (session, head) pairs, every row of each; extrapolated linearly
-    scale = 1.0 / np.sqrt(cfg.D)
+    nthr = host_threads()
     P = cfg.page
+    scale = 1.0 / np.sqrt(cfg.D)
+    if cfg.sam_mode == "per_session":
+        mem_of = lambda b: mems[b]
+    else:
+        mem_of = lambda b: mems[0]
+    lg = logits.float().cpu().numpy()
     total_pos = int(lay.seq_lens.astype(np.int64).sum()) * cfg.Hq
 
-    def sample_attention(budget):
-        rng = np.random.default_rng(cfg.seed)
-        done, t_attn, pos_done = 0, 0.0, 0
-        while t_attn < budget and done < cfg.B * cfg.Hq:
-            b = int(rng.integers(0, cfg.B)); h = int(rng.integers(0, cfg.Hq))
-            S = int(lay.seq_lens[b]); npg = (S + P - 1) // P
-            pages = torch.as_tensor(lay.block_table[b, :npg].astype(np.int64), device=kc.device)
-            g = h // cfg.G
-            Kp = kc[pages, g].float().cpu().numpy()[:, None]          # [npg,1,P,D] page-shaped host copy
-            Vp = vc[pages, g].float().cpu().numpy()[:, None]
-            qh = q[b, :, h].float().cpu().numpy()
-            ident = np.arange(npg)
-            t0 = time.perf_counter()
-            K = gather_kv(Kp, ident, S, 0); V = gather_kv(Vp, ident, S, 0)
-            attention_oracle_head(qh, K, V, scale)
-            t_attn += time.perf_counter() - t0
-            done += 1; pos_done += S
-        return done, t_attn, t_attn * total_pos / max(1, pos_done)
+    def draft_one(b):
+        draft_oracle(mem_of(b), recent[b, cfg.m - rlen[b]:], cfg.k, cfg.sep)
 
-    done, t_attn, t_attn_full = sample_attention(budget_s)
+    def accept_one(b):
+        accept_oracle(lg[b:b + 1], draft_h[b:b + 1], nd_h[b:b + 1])
+
+    def attn_pair(job):
+        qh, Kp, Vp, S = job
+        ident = np.arange(Kp.shape[0])
+        attention_oracle_head(qh, gather_kv(Kp, ident, S, 0), gather_kv(Vp, ident, S, 0), scale)
+
+    def stage_session(b, heads):
+        """Host copies of what the oracle reads for some query heads of session b (not timed: the oracle's input)."""
+        S = int(lay.seq_lens[b]); npg = (S + P - 1) // P
+        pages = torch.as_tensor(lay.block_table[b, :npg].astype(np.int64), device=kc.device)
+        jobs, kv = [], {}
+        for h in heads:
+            g = h // cfg.G
+            if g not in kv:
+                kv[g] = (kc[pages, g].cpu().float().numpy()[:, None], vc[pages, g].cpu().float().numpy()[:, None])
+            jobs.append((q[b, :, h].float().cpu().numpy(), kv[g][0], kv[g][1], S))
+        return jobs
+
+    def run(workers, budget):
+        """(t_draft, t_accept, t_attn extrapolated to the whole batch, pairs done, t_attn measured)"""
+        with threadpool_limits(limits=1), ThreadPoolExecutor(max_workers=workers) as pool:
+            t0 = time.perf_counter(); list(pool.map(draft_one, range(cfg.B))); t_draft = time.perf_counter() - t0
+            t0 = time.perf_counter(); list(pool.map(accept_one, range(cfg.B))); t_accept = time.perf_counter() - t0
+            rng = np.random.default_rng(cfg.seed)
+            done, pos_done, t_attn = 0, 0, 0.0
+            for b in rng.permutation(cfg.B):                  # whole sessions, in a seeded order, until the budget is spent
+                if t_attn >= budget:
+                    break
+                heads = list(range(cfg.Hq)) if workers > 1 else [int(h) for h in rng.choice(cfg.Hq, 4, replace=False)]
+                jobs = stage_session(int(b), heads)
+                t0 = time.perf_counter(); list(pool.map(attn_pair, jobs)); t_attn += time.perf_counter() - t0
+                done += len(jobs); pos_done += int(lay.seq_lens[b]) * len(jobs)
+        return t_draft, t_accept, t_attn * total_pos / max(1, pos_done), done, t_attn
+
+    cpu0, wall0 = time.process_time(), time.perf_counter()
+    td, ta, tattn_full, done, tattn = run(nthr, budget_s)
     cpu1, wall1 = time.process_time(), time.perf_counter()
-    t_step = t_draft + t_attn_full + t_accept
-    cores = max(1, int(round((cpu1 - cpu0) / max(1e-9, wall1 - wall0))))
-    # the same oracle held to one thread (its library routines otherwise use every core), on a shorter sample
-    single = None
-    try:
-        from threadpoolctl import threadpool_limits
-        with threadpool_limits(limits=1):
-            done1, t_attn1, t_attn_full1 = sample_attention(budget_s / 4)
-        single = {"value": cfg.B * cfg.k / (t_draft + t_attn_full1 + t_accept), "unit": "tokens/s",
-                  "sample": f"attention oracle on {done1} pairs ({t_attn1:.1f} s, extrapolated to {t_attn_full1:.1f} s)"}
-    except ImportError:
-        pass
+    td1, ta1, tattn_full1, done1, tattn1 = run(1, budget_s / 4)
     model = ""
     try:
         with open("/proc/cpuinfo") as f:
@@ -124,13 +142,161 @@ def cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h,
     except OSError:
         pass
     return {
-        "value": cfg.B * cfg.k / t_step, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-        "sample": (f"draft oracle on all {cfg.B} sessions ({t_draft:.3f} s) + accept oracle on all "
-                   f"{cfg.B * cfg.R} rows ({t_accept:.3f} s) + fp64 attention oracle on {done} seeded "
-                   f"(session, head) pairs of {cfg.B * cfg.Hq} ({t_attn:.1f} s, extrapolated linearly by "
-                   f"KV positions to {t_attn_full:.1f} s)"),
-        "host_cpus": os.cpu_count(), "cpu_model": model, "single_thread": single,
+        "value": cfg.B * cfg.k / (td + tattn_full + ta), "unit": "tokens/s", "cores": nthr, "kind": "oracle",
+        "sample": (f"{nthr} worker threads, one per host core, the numerical library held to one thread each: draft oracle "
+                   f"on all {cfg.B} sessions ({td:.3f} s) + accept oracle on all {cfg.B * cfg.R} rows ({ta:.3f} s) + fp64 "
+                   f"attention oracle on {done} (session, head) pairs of {cfg.B * cfg.Hq}, whole sessions in a seeded order "
+                   f"({tattn:.1f} s, extrapolated linearly by KV positions to {tattn_full:.1f} s)"),
+        "cpu_time_over_wall_time": (cpu1 - cpu0) / max(1e-9, wall1 - wall0),
+        "host_cpus": os.cpu_count(), "cpu_model": model,
+        "single_thread": {"value": cfg.B * cfg.k / (td1 + tattn_full1 + ta1), "unit": "tokens/s", "cores": 1,
+                          "sample": (f"the same on one thread: draft {td1:.3f} s, accept {ta1:.3f} s, attention oracle on "
+                                     f"{done1} pairs ({tattn1:.1f} s, extrapolated to {tattn_full1:.1f} s)")},
     }
+
+
+# ------------------------------------------------------------------------------------- roofline
+def attention_work(cfg, lay):
+    """Algorithmic bytes (every session's whole K/V once per kv head), the bytes of the distinct pages, and the matrix work."""
+    kv_elem = 2 if cfg.dtype == "bf16" else 4
+    positions = float(lay.seq_lens.astype(np.int64).sum())
+    alg_bytes = positions * cfg.Hkv * 2 * cfg.D * kv_elem
+    used_pages = np.unique(lay.block_table[lay.block_table >= 0]).size
+    unique_bytes = float(used_pages) * cfg.page * cfg.Hkv * 2 * cfg.D * kv_elem
+    flops = 4.0 * cfg.D * cfg.G * cfg.R * positions * cfg.Hkv
+    return alg_bytes, unique_bytes, flops
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per spec_verify_attn call from the rocprofv3 counter runs recorded in profiles/traffic.json, or None
+    when the kernel source has changed since they were taken (the record names the source it was measured on)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(workload)
+        with open(ATTN_SOURCE, "rb") as f:
+            sha = hashlib.sha256(f.read()).hexdigest()
+    except (OSError, ValueError):
+        return None
+    if not rec or rec.get("kernel_source_sha256") != sha:
+        return None
+    return float(rec["hbm_bytes_per_call"])
+
+
+def attention_roofline(cfg, lay, t_attn_ms, stream_gbs=None):
+    """What bounds spec_verify_attn on this workload and how close the launch came.  Pages that several sessions
+    list are needed from HBM once, so the memory bound counts the DISTINCT pages; the bound of the workload is the
+    larger of that and the matrix work at the dense bf16 rate, and `frac` = bound / measured time."""
+    alg_bytes, unique_bytes, flops = attention_work(cfg, lay)
+    unique_bytes = min(unique_bytes, alg_bytes)              # (whole pages: the unused end of a last page is not read)
+    t = t_attn_ms * 1e-3
+    t_hbm = unique_bytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = flops / (MFMA_PEAK_TFLOPS * 1e12) if cfg.dtype == "bf16" else 0.0
+    r = {"kernel": "spec_verify_attn", "launch_ms": t_attn_ms, "traffic": measured_traffic(cfg.name),
+         "algorithmic_bytes": alg_bytes, "unique_bytes": unique_bytes, "matrix_flops": flops,
+         "hbm_bound_ms": t_hbm * 1e3, "mfma_bound_ms": t_mfma * 1e3,
+         "logical_GBs": alg_bytes / t / 1e9, "unique_GBs": unique_bytes / t / 1e9,
+         "mfma_TFLOPs": flops / t / 1e12, "mfma_frac_of_2500": flops / t / (MFMA_PEAK_TFLOPS * 1e12)}
+    if t_hbm >= t_mfma:
+        r.update({"bound": "hbm", "achieved": unique_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"})
+    else:
+        r.update({"bound": "mfma", "achieved": flops / t / 1e12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"})
+    r["frac"] = r["achieved"] / r["peak"]
+    if stream_gbs:
+        r["stream_read_GBs"] = stream_gbs
+        r["frac_of_stream_read"] = unique_bytes / t / 1e9 / stream_gbs
+    return r
+
+
+# ------------------------------------------------------------------------------------- inputs and timing
+class AttnInputs:
+    def __init__(self, A, W, cfg, dev, tuning):
+        import torch
+        self.cfg, self.tuning = cfg, tuning
+        self.lay = W.kv_layout(cfg)
+        self.q, self.kc, self.vc = W.kv_and_queries(cfg, self.lay, dev)
+        self.bt = torch.as_tensor(self.lay.block_table, device=dev)
+        self.seq = torch.as_tensor(self.lay.seq_lens, device=dev)
+        self.scale = 1.0 / float(np.sqrt(cfg.D))
+        self.ws_bytes = A.spec_verify_attn_workspace(cfg.B, cfg.R, cfg.Hq, cfg.Hkv, cfg.D, cfg.page, self.bt.shape[1],
+                                                     A.BF16 if cfg.dtype == "bf16" else A.F32, tuning)
+        self.ws = torch.empty(max(self.ws_bytes, 16) // 4 + 1, dtype=torch.float32, device=dev)
+        self.out = torch.empty((cfg.B, cfg.R, cfg.Hq, cfg.D), dtype=torch.float32, device=dev)
+        self.A = A
+
+    def attn(self):
+        self.A.spec_verify_attn(self.q, self.kc, self.vc, self.bt, self.seq, self.scale, out=self.out, workspace=self.ws,
+                                tuning=self.tuning)
+
+    def time_attn(self, launches, warmup=3):
+        """Mean HIP-event time of one spec_verify_attn call (all its launches), in ms, on the launch stream."""
+        import torch
+        for _ in range(warmup):
+            self.attn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+        for e0, e1 in evs:
+            e0.record(); self.attn(); e1.record()
+        torch.cuda.synchronize()
+        return float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+
+
+def stream_read_rate(dev):
+    """The rate this device delivers to a kernel that only streams (4 GiB, 5 launches), GB/s."""
+    import torch
+    from paper_2512_18337_amd.build import BENCH_LIB
+    probe_lib = ctypes.CDLL(BENCH_LIB)                       # the benchmark's own helper, not the product library
+    probe_lib.bench_stream_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    buf = torch.ones(1 << 30, dtype=torch.float32, device=dev)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+
+    def probe():
+        rc = probe_lib.bench_stream_read_probe(buf.data_ptr(), buf.numel() * 4, sink.data_ptr(),
+                                               torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+
+    probe()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        probe()
+    e1.record()
+    torch.cuda.synchronize()
+    return buf.numel() * 4 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def measure_targets(A, W, dev, stream_gbs, seed):
+    """spec_verify_attn alone (10 launches) on the two other workloads the bandwidth target names."""
+    import torch
+    out = {}
+    for i in (3, 4):
+        cfg = W.baseline_config(i)
+        if seed is not None:
+            cfg = W.scaled(cfg, seed=seed + i)
+        inp = AttnInputs(A, W, cfg, dev, 0)
+        t = inp.time_attn(10)
+        out[cfg.name] = attention_roofline(cfg, inp.lay, t, stream_gbs)
+        del inp
+        torch.cuda.empty_cache()
+    return out
+
+
+def measure_ksweep(A, W, cfg, dev, p_accept):
+    """t_attn(k) for k = 0..16 on this workload's batch and context lengths, and what the controller makes of it."""
+    import torch
+    ks, ts = list(range(0, 17)), []
+    for k in ks:
+        c = W.scaled(cfg, k=k, name=f"{cfg.name}+k{k}")
+        inp = AttnInputs(A, W, c, dev, 0)
+        ts.append(inp.time_attn(8) * 1e-3)
+        del inp
+        torch.cuda.empty_cache()
+    res = {"k": ks, "t_attn_ms": [t * 1e3 for t in ts], "accept_probability": p_accept}
+    # the layers outside this path cost something per verified row: nothing (the attention layer alone), then 1 % and
+    # 10 % of a plain decoding step of this layer per row
+    for name, per_row in (("attention_only", 0.0), ("rows_cost_1pct_of_step_each", 0.01 * ts[0]),
+                          ("rows_cost_10pct_of_step_each", 0.10 * ts[0])):
+        kstar, gain = A.spec_choose_k(ks, ts, p_accept, per_row)
+        res[name] = {"per_row_cost_ms": per_row * 1e3, "k_star": kstar, "tokens_per_time_vs_k0": gain}
+    return res
 
 
 def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest=None):
@@ -302,6 +468,8 @@ def main():
                           "launches": 5}))
         return
     cfg = W.baseline_config(args.config)
+    if args.seed is not None:
+        cfg = W.scaled(cfg, seed=args.seed)
     if args.set:
         import ast
         cfg = W.scaled(cfg, name=cfg.name + "+" + ",".join(args.set),
@@ -322,15 +490,8 @@ def main():
     cend_d = torch.as_tensor(flat.corpus_end[idx], device=dev)
     recent_d = torch.as_tensor(recent, device=dev)
     rlen_d = torch.as_tensor(rlen, device=dev)
-    lay = W.kv_layout(cfg)
-    q, kc, vc = W.kv_and_queries(cfg, lay, dev)
-    bt = torch.as_tensor(lay.block_table, device=dev)
-    seq = torch.as_tensor(lay.seq_lens, device=dev)
-    scale = 1.0 / float(np.sqrt(cfg.D))
-    ws_bytes = A.spec_verify_attn_workspace(cfg.B, cfg.R, cfg.Hq, cfg.Hkv, cfg.D, cfg.page, bt.shape[1],
-                                            A.BF16 if cfg.dtype == "bf16" else A.F32, tuning)
-    ws = torch.empty(max(ws_bytes, 16) // 4 + 1, dtype=torch.float32, device=dev)
-    out = torch.empty((cfg.B, cfg.R, cfg.Hq, cfg.D), dtype=torch.float32, device=dev)
+    inp = AttnInputs(A, W, cfg, dev, tuning)
+    lay, q, kc, vc = inp.lay, inp.q, inp.kc, inp.vc
 
     # the logits stand in for the LM head: built once from the library's own drafts
     draft, n_draft, _, _ = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
@@ -339,7 +500,6 @@ def main():
     logits = W.verify_logits(cfg, draft_h, nd_h, dev)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
-
     flush = torch.zeros(128 << 20, dtype=torch.float32, device=dev) if args.cold else None
 
     def step(events=None):
@@ -349,7 +509,7 @@ def main():
             if events: events[0].record()
             d, nd, ml, me = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
         if events: events[1].record()
-        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)
+        inp.attn()
         if events: events[2].record()
         if not args.attn_only:
             res = A.spec_accept(logits, d, nd)
@@ -380,36 +540,7 @@ def main():
         t_accept = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
         accept_len = res[0].cpu().numpy()
 
-    # the rate this device delivers to a kernel that only streams (4 GiB, 5 launches)
-    probe_buf = torch.ones(1 << 30, dtype=torch.float32, device=dev)
-    probe_sink = torch.zeros(4, dtype=torch.float32, device=dev)
-    import ctypes
-    from paper_2512_18337_amd.build import BENCH_LIB
-    probe_lib = ctypes.CDLL(BENCH_LIB)                       # the benchmark's own helper, not the product library
-    probe_lib.bench_stream_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
-
-    def stream_read_probe():
-        rc = probe_lib.bench_stream_read_probe(probe_buf.data_ptr(), probe_buf.numel() * 4, probe_sink.data_ptr(),
-                                               torch.cuda.current_stream().cuda_stream)
-        assert rc == 0, rc
-
-    stream_read_probe()
-    pe0, pe1 = ev(), ev()
-    pe0.record()
-    for _ in range(5):
-        stream_read_probe()
-    pe1.record()
-    torch.cuda.synchronize()
-    stream_gbs = probe_buf.numel() * 4 * 5 / (pe0.elapsed_time(pe1) * 1e-3) / 1e9
-    del probe_buf
-
-    kv_elem = 2 if cfg.dtype == "bf16" else 4
-    alg_bytes = float(lay.seq_lens.astype(np.int64).sum()) * cfg.Hkv * 2 * cfg.D * kv_elem
-    # distinct pages only (smaller than alg_bytes when sessions share pages), and the matrix work
-    used_pages = np.unique(lay.block_table[lay.block_table >= 0]).size
-    unique_bytes = float(used_pages) * cfg.page * cfg.Hkv * 2 * cfg.D * kv_elem
-    attn_flops = 4.0 * cfg.D * cfg.G * cfg.R * float(lay.seq_lens.astype(np.int64).sum()) * cfg.Hkv
-    achieved = alg_bytes / (t_attn * 1e-3) / 1e9
+    stream_gbs = stream_read_rate(dev)
     result = {
         "metric": "verified tokens/s/GPU (B=64, 32k ctx, k=8); verify-attn HBM GB/s % of peak",
         "value": cfg.B * cfg.k / (ms_step * 1e-3),
@@ -419,15 +550,10 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "head_dim": cfg.D,
                    "kv_len": [int(lay.seq_lens.min()), int(lay.seq_lens.max())], "page": cfg.page, "k": cfg.k,
-                   "sam_tokens": int(sum(len(m) for m in mems)), "vocab": cfg.vocab,
+                   "sam_tokens": int(sum(len(m) for m in mems)), "vocab": cfg.vocab, "seed": cfg.seed,
                    "step": "sam_draft + spec_verify_attn + spec_accept", "attn_only": bool(args.attn_only),
                    "cold_caches": bool(args.cold)},
-        "roofline": {"bound": "hbm", "kernel": "spec_verify_attn", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "algorithmic_bytes": alg_bytes,
-                     "launch_ms": t_attn, "stream_read_GBs": stream_gbs, "frac_of_stream_read": achieved / stream_gbs,
-                     "unique_bytes": unique_bytes, "unique_GBs": unique_bytes / (t_attn * 1e-3) / 1e9,
-                     "mfma_TFLOPs": attn_flops / (t_attn * 1e-3) / 1e12, "mfma_frac_of_2500": attn_flops / (t_attn * 1e-3) / 2.5e15},
+        "roofline": attention_roofline(cfg, lay, t_attn, stream_gbs),
         "detail": {"t_draft_us": t_draft * 1e3, "t_attn_us": t_attn * 1e3, "t_accept_us": t_accept * 1e3,
                    "sessions_per_s_sam_draft": (cfg.B / (t_draft * 1e-3)) if t_draft else None,
                    # the walk makes at least one dependent 16-byte record load per window token
@@ -438,7 +564,7 @@ def main():
                    "accept_hbm_GBs": (logits.numel() * logits.element_size() / (t_accept * 1e-3) / 1e9)
                    if t_accept else None,
                    "sam_build_tokens_per_s": sum(len(m) for m in mems) / t_build,
-                   "attn_workspace_bytes": ws_bytes},
+                   "attn_workspace_bytes": inp.ws_bytes},
     }
     if not args.attn_only:
         # the stateful lookup: the window once (the prompt), then calls that consume only what a step commits
@@ -455,7 +581,7 @@ def main():
         for _ in range(3):
             A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
         se0, se1 = ev(), ev()
-        A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)   # the host queues the calls behind it
+        inp.attn()                                            # the host queues the calls behind it
         se0.record()
         for _ in range(20):
             A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
@@ -467,7 +593,7 @@ def main():
         # path is defined with the stateless one)
         def step_stateful():
             d, nd, _, _ = A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
-            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)
+            inp.attn()
             return A.spec_accept(logits, d, nd)
         for _ in range(3):
             step_stateful()
@@ -499,14 +625,19 @@ def main():
         result["detail"]["sam_prompt_build"] = measure_build(A, cfg)
     if args.maintain > 0:
         def rest(d, nd):
-            A.spec_verify_attn(q, kc, vc, bt, seq, scale, out=out, workspace=ws, tuning=tuning)
+            inp.attn()
             A.spec_accept(logits, d, nd)
         result["detail"]["sam_maintenance"] = measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx,
                                                                   args.maintain, dev, rest)
+    if args.ksweep:
+        p_acc = float(np.mean(cfg.match_prob))
+        result["detail"]["ksweep"] = measure_ksweep(A, W, cfg, dev, p_acc)
     if not args.no_cpu_baseline and not args.attn_only:
         result["cpu_baseline"] = cpu_baseline(cfg, mems, recent, rlen, q, kc, vc, lay, logits, draft_h, nd_h)
     else:
         result["cpu_baseline"] = None
+    if not args.no_targets and not args.attn_only and args.config == 2 and not args.set:
+        result["detail"]["targets"] = measure_targets(A, W, dev, stream_gbs, args.seed)
     print(json.dumps(result))
 
 

@@ -66,9 +66,9 @@ const char *agentsam_strerror(int code);
 #define AGENTSAM_ATTN_KV_CHUNK(positions) ((uint64_t)((positions) / 128) << 8)
 
 /* ------------------------------------------------------------------------------------------
- * Suffix automaton over a token memory (paper Sec. 5.4.2: the request context is indexed in a
- * suffix automaton, built incrementally token by token; verified tokens are inserted as the
- * context grows.  Alg. 4: BuildSAM, "incrementally extend S with streamed tokens").
+ * Suffix automaton over a token memory (paper Sec. 5.4.2: a request's context is indexed in a
+ * suffix automaton that grows one token at a time, the verified tokens of every step included;
+ * Alg. 4, BuildSAM and step 2).
  *
  * A memory is a sequence of non-negative token ids.  Several sessions may be concatenated in
  * one memory, each terminated by `sep_token`, an id no query ever contains (Sec. 5.4.2,
@@ -80,7 +80,9 @@ typedef struct sam sam_t;
 /* Build the automaton of tokens[0..n) (host pointer; n may be 0).  *out receives the handle. */
 int sam_build(const int32_t *tokens, int64_t n, int32_t sep_token, sam_t **out);
 
-/* Extend the automaton with n more tokens (host pointer), amortised O(1) per token. */
+/* Extend the automaton with n more tokens (host pointer): amortised O(1) hash operations per token
+ * (the changes a maintained device copy needs are logged in O(1) per token as well; the walk that
+ * finds which end positions moved is done once per sam_delta_export, see there). */
 int sam_append(sam_t *s, const int32_t *tokens, int64_t n);
 
 /* Sizes of the flattened form: states (root included), transitions, memory tokens. */
@@ -124,8 +126,8 @@ int sam_wide_table(const sam_t *s, int32_t state_base, int32_t *table, int64_t s
 void sam_free(sam_t *s);
 
 /* ------------------------------------------------------------------------------------------
- * Keeping a device copy current without flattening again (Sec. 5.4.2: verified tokens are
- * inserted as the context grows; Alg. 4, "incrementally extend S with streamed tokens").
+ * Keeping a device copy current without flattening again (Sec. 5.4.2: what a step verifies goes
+ * into the automaton as the context grows; Alg. 4 step 2).
  *
  * After sam_flatten() the automaton records what a device copy of those arrays is missing once
  * sam_append() has run: states whose walk record or last eligible end position changed (new
@@ -182,9 +184,8 @@ int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32
                     const int32_t *wide_table, int64_t wide_slots, void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * sam_draft_step: sam_draft with the matched state carried from call to call (Alg. 4, the decoding
- * loop: x_t is the current verified suffix and the decoder follows transitions from where it stands;
- * Sec. 5.4.2: "given the current verified suffix, the decoder follows SAM transitions").  A call
+ * sam_draft_step: sam_draft with the matched state carried from call to call (Alg. 4, decoding
+ * loop; Sec. 5.4.2: the lookup continues from the state the verified text has reached).  A call
  * consumes only the tokens committed since the previous call, so its cost does not depend on how
  * long the match is, and the match is not cut to a window.
  *
@@ -220,8 +221,8 @@ int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, const int32_
                    void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * Asynchronous construction (Sec. 5.4.2, "Asynchronous SAM construction"; Alg. 4 step 2: a
- * background thread extends the automaton with streamed tokens).  A builder owns one child thread, a
+ * Asynchronous construction (Sec. 5.4.2, asynchronous SAM construction; Alg. 4 step 2: the
+ * automaton is extended off the decoding thread).  A builder owns one child thread, a
  * waiting queue and the automata of the requests submitted to it.
  *
  *   sam_builder_submit   copies the tokens (a prompt, or tokens generated since) into the queue and
@@ -249,8 +250,8 @@ int sam_builder_release(sam_builder_t *b, int64_t request_id);
 void sam_builder_destroy(sam_builder_t *b);
 
 /* ------------------------------------------------------------------------------------------
- * sam_draft (paper Sec. 5.4.2 and Alg. 4, FollowTransitions: "given the current verified
- * suffix, follow SAM transitions to retrieve a matching continuation with a specified length").
+ * sam_draft (paper Sec. 5.4.2 and Alg. 4, FollowTransitions: the drafts are a continuation, of a
+ * given length, of an earlier occurrence of the text verified so far).
  *
  * For each session b: feed its window recent[b, m-recent_len[b] .. m) (right-aligned) through
  * the automaton whose root is root[b]; this yields the longest suffix of the window that occurs
@@ -274,9 +275,8 @@ int sam_draft(const int32_t *len, const int32_t *link, const int32_t *row_ptr,
               const int32_t *wide_table, int64_t wide_slots, void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * sam_draft_merged (Alg. 4: S_merged = MergeSAM(S_session, S_cross, weights); Sec. 5.4.2: the
- * session's own context and the top-K retrieved contexts, "the similarity scores determine the
- * weights of each SAM during the merge").
+ * sam_draft_merged (Alg. 4, MergeSAM of the session's automaton with those of retrieved contexts;
+ * Sec. 5.4.2: each automaton enters the merge with a weight taken from its similarity score).
  *
  * Every session queries M automata with the same window: root[B,M], corpus_end[B,M], weight[B,M]
  * (all automata live in the one set of flattened arrays).  The automata are not physically merged;
@@ -295,7 +295,7 @@ int sam_draft_merged(const int32_t *row_ptr, const int32_t *edge_tok, const int3
                      const int32_t *wide_table, int64_t wide_slots, void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * spec_verify_attn (Alg. 4: "Validate with main LLM" - the attention of the pass in which the
+ * spec_verify_attn (Alg. 4, validation by the main model: the attention of the pass in which the
  * target model scores the base token and the k drafts of every session at once).
  *
  *   R = 1+k query rows per session; row i sits at KV position seq_lens[b]-R+i and attends
@@ -303,13 +303,16 @@ int sam_draft_merged(const int32_t *row_ptr, const int32_t *edge_tok, const int3
  *   out[b,i,h,:] = softmax_j(scale * q[b,i,h,:] . K_b[j, h/(Hq/Hkv), :]) . V_b[j, h/(Hq/Hkv), :]
  *
  * Device inputs : q[B,R,Hq,D]; k_cache, v_cache [num_pages,Hkv,page_size,D]; block_table
- *                 [B,max_pages] (page id of KV positions p*page_size..); seq_lens[B] (>= R).
+ *                 [B,max_pages] (page id of KV positions p*page_size..); seq_lens[B].
  *                 dtype selects f32 or bf16 storage of q/k/v; accumulation is fp32.
+ *                 seq_lens[b] is taken as min(max(seq_lens[b], 0), max_pages*page_size).  A row whose
+ *                 position seq_lens[b]-R+i is negative (seq_lens[b] < R) sees nothing: its output is
+ *                 zeros (every row of an empty session); the other rows are computed as always.
  * Device output : out[B,R,Hq,D] in out_dtype.
  * workspace     : device scratch of at least spec_verify_attn_workspace() bytes (partial
  *                 results of the KV splits); contents need no initialisation.
  * Sessions may list the same pages (a shared prefix): results are those of the definition above
- * whatever is shared; see "attn_cascade" for how sharing is used.
+ * whatever is shared; see the cascade field of the tuning word for how sharing is used.
  * A page id outside [0,num_pages) is treated as a page of zeros (never dereferenced).
  * Supported: D in {64,128}; Hq % Hkv == 0; bf16 needs page_size % 32 == 0; scale > 0;
  * (Hq/Hkv)*R <= 192 for bf16, R <= 32 for f32. */
@@ -341,8 +344,8 @@ int spec_verify_attn_static(const void *q, const void *k_cache, const void *v_ca
                             void *out, uint64_t tuning, void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * spec_accept (Alg. 4: "commit matched prefix; on mismatch fall back to standard decoding";
- * Sec. 5.4.1: lossless, i.e. the output equals greedy decoding).
+ * spec_accept (Alg. 4: the matched draft prefix is committed and decoding goes on from the first
+ * mismatch; Sec. 5.4.1: lossless, i.e. the output equals greedy decoding).
  *
  *   tgt[b,i]        = lowest index of the maximum of logits[b,i,:]   (NaN never wins)
  *   accept_len[b]   = number of leading drafts j < n_draft[b] with draft[b,j] == tgt[b,j]
@@ -356,23 +359,48 @@ int spec_accept(const void *logits, int32_t logits_dtype, const int32_t *draft,
                 int32_t *accept_len, int32_t *out_tokens, int32_t *tgt, void *stream);
 
 /* ------------------------------------------------------------------------------------------
- * Host-side controllers of the serving loop.
+ * Host-side controllers of the serving loop (all pointers are host memory).
  *
- * spec_adaptive_k (Sec. 5.4.2, "Adaptive switch for speculative decoding"; Alg. 4 step 4): beyond a
- * context length or a batch size - thresholds the deployment determines empirically - speculation no
- * longer pays.  *k_out = 0 if context_len > context_threshold or batch > batch_threshold, else k.
+ * Speculation depth (Sec. 5.4.2, adaptive switch for speculative decoding; Alg. 4 step 4: beyond
+ * some context length or batch size validating the drafts costs more than they save).
  *
- * agentsched_pick (Alg. 3, Agent Scheduler): which queued request to admit next.  Per request i:
- * hit[i] = KV blocks it would reuse, need[i] = new KV blocks it needs, prompt_tok[i] = prompt length,
- * wait[i] = time waited.  With H = sum hit, U = max(0, free_blocks - H), D = sum need:
- *     lambda   = lambda_max * logistic(k * (D / (U + eps) - 1))
- *     sjf_mix  = clamp(1 - lambda / lambda_max, 0, 1)
- *     need_eff = sjf_mix * prompt_tok[i] / tokens_per_block + (1 - sjf_mix) * need[i]
- *     score[i] = a * hit[i] - (b + lambda) * need_eff + c * wait[i]
- * *picked = the highest-scoring request with need[i] <= free_blocks (the earlier one on equal
- * scores), -1 if none fits.  score may be NULL.  All arrays are host memory; a, b, c, k, lambda_max,
- * eps are the deployment's constants (the paper prints none).
+ *   spec_choose_k         from a measured table: k_values[n] (strictly increasing, k_values[0] = 0) and
+ *                         t_step[n], the time of this path's step with that many drafts.  With every
+ *                         draft accepted independently with probability p_accept, a step with k drafts
+ *                         commits 1 + p + ... + p^k tokens and costs
+ *                             t_step(k) + max(other_floor, other_per_row * batch * (1 + k)),
+ *                         the second term being the layers outside this path (weights streamed once,
+ *                         then work per verified row; pass 0, 0 for this path alone).
+ *                         *k_star = the depth with the most committed tokens per unit of cost (the
+ *                         smaller on equal rates), *gain = that rate over the rate of k = 0 (>= 1; may
+ *                         be NULL).  Speculating pays iff p + ... + p^k > cost(k) / cost(0) - 1.
+ *   spec_switch_frontier  the same choice over a grid: batches[nb] and contexts[nc] strictly increasing,
+ *                         t_step[nb][nc][n_k].  k_star[nb][nc] as above; context_threshold[i] = the
+ *                         largest grid context up to which k_star > 0 without interruption at
+ *                         batches[i] (-1: none), batch_threshold[j] likewise along the batches at
+ *                         contexts[j].  These are the two thresholds of spec_adaptive_k.
+ *   spec_adaptive_k       the switch itself: *k_out = 0 if context_len > context_threshold or
+ *                         batch > batch_threshold, else k.
+ *
+ * agentsched_pick (Alg. 3): which queued request to admit next.  Per request i: hit[i] = KV blocks it
+ * would reuse, need[i] = new KV blocks it needs, prompt_tok[i] = prompt length, wait[i] = time waited.
+ * With H = sum hit, U = max(0, free_blocks - H), D = sum need:
+ *     lambda  = lambda_max * logistic(k * (D / (U + eps) - 1))                 price of a block
+ *     w       = clamp(1 - lambda / lambda_max, 0, 1)
+ *     cost_i  = w * prompt_tok[i] / tokens_per_block + (1 - w) * need[i]
+ *     score_i = a * hit[i] - (b + lambda) * cost_i + c * wait[i]
+ * *picked = the highest-scoring request with need[i] <= free_blocks (the earlier one on equal scores),
+ * -1 if none fits.  score may be NULL.  a, b, c, k, lambda_max, eps are the deployment's constants (the
+ * paper prints none).
  * ---------------------------------------------------------------------------------------- */
+int spec_choose_k(const int32_t *k_values, const double *t_step, int32_t n, double p_accept, int32_t batch,
+                  double other_floor, double other_per_row, int32_t *k_star, double *gain);
+
+int spec_switch_frontier(const int32_t *batches, int32_t n_batches, const int64_t *contexts, int32_t n_contexts,
+                         const int32_t *k_values, int32_t n_k, const double *t_step, double p_accept,
+                         double other_floor, double other_per_row, int32_t *k_star, int64_t *context_threshold,
+                         int32_t *batch_threshold);
+
 int spec_adaptive_k(int32_t batch, int64_t context_len, int32_t k, int32_t batch_threshold,
                     int64_t context_threshold, int32_t *k_out);
 

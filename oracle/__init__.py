@@ -14,7 +14,8 @@ code.
   accept     - first-index argmax per row and the matched draft prefix
                                                              [Alg. 4 "commit matched prefix"]
   sched      - AgentSched shadow price, scores and pick; the adaptive
-               speculation switch                            [Alg. 3; Alg. 4 step 4]
+               speculation switch and the depth / thresholds
+               it is fed with                                [Alg. 3; Alg. 4 step 4]
 
 Every function is pinned by tests that run without a GPU (worked examples,
 closed forms, invariants, an independent brute force, library special cases),
@@ -28,4 +29,6 @@ from .draft import (  # noqa: F401
 )
 from .attention import attention_oracle, attention_oracle_head          # noqa: F401
 from .accept import accept_oracle                                        # noqa: F401
-from .sched import adaptive_k_oracle, agentsched_oracle                   # noqa: F401
+from .sched import (  # noqa: F401
+    adaptive_k_oracle, agentsched_oracle, choose_k_oracle, expected_committed_oracle, switch_frontier_oracle,
+)

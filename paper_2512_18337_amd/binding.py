@@ -26,7 +26,7 @@ EXPORTS = ["agentsam_strerror", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
            "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
            "sam_draft", "sam_draft_delta", "sam_draft_step", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_verify_attn_static", "spec_accept",
-           "spec_adaptive_k", "agentsched_pick"]
+           "spec_adaptive_k", "spec_choose_k", "spec_switch_frontier", "agentsched_pick"]
 
 
 class AgentSamError(RuntimeError):
@@ -59,6 +59,10 @@ def lib():
         L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 5
         L.spec_adaptive_k.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                       ctypes.POINTER(ctypes.c_int32)]
+        L.spec_choose_k.argtypes = [_vp, _vp, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, ctypes.c_double,
+                                    ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)]
+        L.spec_switch_frontier.argtypes = [_vp, ctypes.c_int32, _vp, ctypes.c_int32, _vp, ctypes.c_int32, _vp,
+                                           ctypes.c_double, ctypes.c_double, ctypes.c_double, _vp, _vp, _vp]
         L.agentsched_pick.argtypes = ([ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64] + [ctypes.c_double] * 6 +
                                       [ctypes.c_int32, ctypes.POINTER(ctypes.c_double), _vp,
                                        ctypes.POINTER(ctypes.c_int64)])
@@ -421,6 +425,37 @@ def spec_adaptive_k(batch: int, context_len: int, k: int, batch_threshold: int, 
     _check(lib().spec_adaptive_k(int(batch), int(context_len), int(k), int(batch_threshold), int(context_threshold),
                                  ctypes.byref(out)), "spec_adaptive_k")
     return out.value
+
+
+def spec_choose_k(k_values, t_step, p_accept: float, other_per_row: float = 0.0, batch: int = 1,
+                  other_floor: float = 0.0):
+    """Returns (k*, committed tokens per unit of cost relative to k = 0)."""
+    kv = np.ascontiguousarray(k_values, dtype=np.int32)
+    ts = np.ascontiguousarray(t_step, dtype=np.float64)
+    assert kv.shape == ts.shape and kv.ndim == 1
+    ks, gain = ctypes.c_int32(), ctypes.c_double()
+    _check(lib().spec_choose_k(_vp(kv.ctypes.data), _vp(ts.ctypes.data), kv.shape[0], float(p_accept), int(batch),
+                               float(other_floor), float(other_per_row), ctypes.byref(ks), ctypes.byref(gain)),
+           "spec_choose_k")
+    return ks.value, gain.value
+
+
+def spec_switch_frontier(batches, contexts, k_values, t_step, p_accept: float, other_floor: float = 0.0,
+                         other_per_row: float = 0.0):
+    """t_step[nb][nc][nk].  Returns (k_star[nb][nc], context_threshold[nb], batch_threshold[nc])."""
+    bs = np.ascontiguousarray(batches, dtype=np.int32)
+    cs = np.ascontiguousarray(contexts, dtype=np.int64)
+    kv = np.ascontiguousarray(k_values, dtype=np.int32)
+    ts = np.ascontiguousarray(t_step, dtype=np.float64)
+    assert ts.shape == (bs.shape[0], cs.shape[0], kv.shape[0])
+    kstar = np.zeros((bs.shape[0], cs.shape[0]), np.int32)
+    cthr = np.zeros(bs.shape[0], np.int64)
+    bthr = np.zeros(cs.shape[0], np.int32)
+    ptr = lambda x: _vp(x.ctypes.data)
+    _check(lib().spec_switch_frontier(ptr(bs), bs.shape[0], ptr(cs), cs.shape[0], ptr(kv), kv.shape[0], ptr(ts),
+                                      float(p_accept), float(other_floor), float(other_per_row), ptr(kstar), ptr(cthr),
+                                      ptr(bthr)), "spec_switch_frontier")
+    return kstar, cthr, bthr
 
 
 def agentsched_pick(free_blocks: int, hit, need, prompt_tok, wait, *, lambda_max: float, k: float, eps: float,

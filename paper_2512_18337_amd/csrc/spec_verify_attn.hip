@@ -73,8 +73,6 @@ struct AttnParams {
     int phase;               // 1: prefix phase of a cascade run
     int gs, ngroups;         // sessions per group, number of groups
     int rows1;               // packed rows of ONE session (G*R); == rows except in the prefix phase
-    int pchunk_tiles;        // prefix phase: tiles per workgroup
-    int npchunks_max;        // prefix phase: grid extent over chunks
     int rows_pad_p;          // rows per prefix record
     int nslots;              // workgroups of the balanced (suffix) launch
     const int32_t *lcp;      // [B] pages each session has in common with session 0 (written by attn_lcp_kernel)
@@ -432,10 +430,10 @@ __device__ __forceinline__ int balanced_share(int T, int nslots) {
     return s < kMinShare ? kMinShare : s;
 }
 
-// Calls body(Segment) for every segment of this workgroup, in order.  `tmp`: 8 ints of LDS that the
-// body does not touch.  Everything handed to the body is uniform over the workgroup (scalar registers).
+// Calls body(Segment) for every segment of workgroup `wg` of `nwg`, in order.  `tmp`: 8 ints of LDS that
+// the body does not touch.  Everything handed to the body is uniform over the workgroup (scalar registers).
 template <class Body>
-__device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, Body body) {
+__device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, int wg, int nwg, Body body) {
     Segment sg;
     sg.rows = p.rows;
     int nt_b;                    // tiles of the current stream (chunk grid: end of my chunk)
@@ -444,26 +442,28 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
     int ptiles = 0;              // cascade: tiles of the shared prefix, which the streams below start after
     if (p.cascade) ptiles = shared_prefix_tiles(p, tmp);
     if (p.phase == 1) {
-        // prefix phase: workgroup (chunk, group, kv head); the group's sessions share these tiles, so
-        // their rows are packed side by side and the block table of the group's first session serves all
-        sg.kvh = blockIdx.x % p.Hkv;
-        const int grp = (blockIdx.x / p.Hkv) % p.ngroups;
-        const int chunk = blockIdx.x / (p.Hkv * p.ngroups);
-        sg.t0 = chunk * p.pchunk_tiles;
-        if (sg.t0 >= ptiles) return;
-        sg.b = grp * p.gs;
+        // prefix phase: the streams are (group, kv head) pairs, all ptiles long, laid end to end (kv head minor)
+        // and cut into nwg equal shares.  The group's sessions share these tiles, so their rows are packed side
+        // by side and the block table of the group's first session serves all.
+        const int T = p.ngroups * p.Hkv * ptiles;
+        const int share = balanced_share(T, nwg);
+        const int lo = wg * share;
+        if (lo >= T) return;
+        remaining = min(T, lo + share) - lo;
+        const int s = lo / ptiles;
+        sg.t0 = lo - s * ptiles;
+        sg.kvh = s % p.Hkv;
+        sg.b = (s / p.Hkv) * p.gs;
         sg.rows = min(p.gs, p.B - sg.b) * p.rows1;
         sg.S = ptiles * kTile + p.R;                         // every row sees the whole prefix: nothing is masked
-        remaining = min(p.pchunk_tiles, ptiles - sg.t0);
-        nt_b = sg.t0 + remaining;
-        chunk_rec = ((int64_t)grp * p.Hkv + sg.kvh) * p.npchunks_max + chunk;
+        nt_b = ptiles;
     } else if (!p.balanced) {
-        sg.kvh = blockIdx.x % p.Hkv;
-        sg.b = (blockIdx.x / p.Hkv) % p.B;
+        sg.kvh = wg % p.Hkv;
+        sg.b = (wg / p.Hkv) % p.B;
         sg.S = session_len(p, sg.b);
         int nchunks_b, chunk_len;
         chunk_geometry(sg.S, p.chunk, nchunks_b, chunk_len);
-        const int chunk = blockIdx.x / (p.B * p.Hkv);
+        const int chunk = wg / (p.B * p.Hkv);
         if (sg.S <= 0 && chunk == 0) zero_session_heads(p.out, p.out_bf16, sg.b, p.R, p.Hq, p.D, sg.kvh * p.G, p.G);
         if (chunk >= nchunks_b) return;
         const int c0 = chunk * chunk_len, c1 = min(sg.S, c0 + chunk_len);
@@ -482,9 +482,9 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
             sessions_tiles += tot;
         }
         const int T = __builtin_amdgcn_readfirstlane(sessions_tiles) * p.Hkv;   // uniform: scalar registers
-        const int share = balanced_share(T, (int)gridDim.x);
-        const int lo = (int)blockIdx.x * share;
-        if (blockIdx.x != 0 && lo >= T) return;              // workgroup 0 stays to write the plan
+        const int share = balanced_share(T, nwg);
+        const int lo = wg * share;
+        if (wg != 0 && lo >= T) return;                      // workgroup 0 stays to write the plan
         // pass 2: the stream my share starts in; workgroup 0 also leaves the prefix sums for the merge
         int carry = 0;
         if (tid == 0) tmp[4] = -1;                           // ordered before the writes below by the scan's barriers
@@ -493,11 +493,11 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
             const int nt = bb < p.B ? max(0, tiles_of(session_len(p, bb)) - ptiles) : 0;
             int tot;
             const int excl = carry + block_scan_excl(nt, tmp, tot);
-            if (blockIdx.x == 0 && bb < p.B) p.plan[bb] = excl;
+            if (wg == 0 && bb < p.B) p.plan[bb] = excl;
             if (nt > 0 && excl * p.Hkv <= lo && lo < (excl + nt) * p.Hkv) { tmp[4] = bb; tmp[5] = excl; }
             carry += tot;
         }
-        if (blockIdx.x == 0 && tid == 0) p.plan[p.B] = carry;
+        if (wg == 0 && tid == 0) p.plan[p.B] = carry;
         __syncthreads();
         if (lo >= T) return;
         sg.b = __builtin_amdgcn_readfirstlane(tmp[4]);
@@ -514,27 +514,41 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
     while (remaining > 0) {                                  // (one round on the chunk grid)
         sg.nt = min(remaining, nt_b - sg.t0);
         const bool whole = sg.t0 == 0 && sg.nt == nt_b;
-        if (p.phase == 1 || !p.balanced) sg.rec = chunk_rec;
-        else if (!whole) sg.rec = 2 * (int64_t)blockIdx.x + (first ? 0 : 1);
-        else sg.rec = ptiles > 0 ? 2 * (int64_t)p.nslots + (int64_t)sg.b * p.Hkv + sg.kvh : -1;   // (the prefix part is pending)
-        if (p.phase == 0 && ptiles > 0) {                    // the stream's tiles come after the shared prefix
-            Segment abs = sg;
-            abs.t0 += ptiles;
-            body(abs);
-        } else {
+        if (p.phase == 1) {
+            // one record per (workgroup, stream) pair that occurs.  Walking the shares in order, every new
+            // segment moves on by one workgroup, by one stream, or by both, so wg + stream index is a
+            // different number for every segment and stays below nwg + number of streams.
+            sg.rec = (int64_t)wg + (sg.b / p.gs) * p.Hkv + sg.kvh;
             body(sg);
+        } else {
+            if (!p.balanced) sg.rec = chunk_rec;
+            else if (p.cascade) sg.rec = (whole && ptiles == 0) ? -1 : (int64_t)wg + (int64_t)sg.b * p.Hkv + sg.kvh;   // (as in the prefix phase)
+            else sg.rec = whole ? -1 : 2 * (int64_t)wg + (first ? 0 : 1);
+            if (ptiles > 0) {                                // the stream's tiles come after the shared prefix
+                Segment abs = sg;
+                abs.t0 += ptiles;
+                body(abs);
+            } else {
+                body(sg);
+            }
         }
         remaining -= sg.nt;
         first = false;
         sg.t0 = 0;
         if (remaining > 0 && ++sg.kvh == p.Hkv) {
             sg.kvh = 0;
-            do {                                             // sessions without tiles own no part of the sequence
-                ++sg.b;
-                if (sg.b >= p.B) return;                     // cannot happen while seq_lens is unchanged
-                sg.S = __builtin_amdgcn_readfirstlane(session_len(p, sg.b));
-                nt_b = max(0, tiles_of(sg.S) - ptiles);
-            } while (nt_b == 0);
+            if (p.phase == 1) {                              // next group
+                sg.b += p.gs;
+                if (sg.b >= p.B) return;                     // cannot happen: the shares end with the last group
+                sg.rows = min(p.gs, p.B - sg.b) * p.rows1;
+            } else {
+                do {                                         // sessions without tiles own no part of the sequence
+                    ++sg.b;
+                    if (sg.b >= p.B) return;                 // cannot happen while seq_lens is unchanged
+                    sg.S = __builtin_amdgcn_readfirstlane(session_len(p, sg.b));
+                    nt_b = max(0, tiles_of(sg.S) - ptiles);
+                } while (nt_b == 0);
+            }
         }
     }
 }
@@ -611,7 +625,7 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
     // tile loads: lane -> (row, 16-byte column); one instruction reads 1 KB contiguous
     const int ld_row = lane / C::kLanesPerRow, ld_col = lane % C::kLanesPerRow;
 
-    for_each_segment(p, sched_tmp, [&](const Segment &sg) __attribute__((always_inline)) {
+    for_each_segment(p, sched_tmp, (int)blockIdx.x, (int)gridDim.x, [&](const Segment &sg) __attribute__((always_inline)) {
         const int b = sg.b, kvh = sg.kvh, S = sg.S;
         WaveState<D, MT> w;
         init_state<D, MT>(w, p, b, kvh, 0, p.rows, n, g);
@@ -878,12 +892,11 @@ __device__ __forceinline__ void lds_dma_tile(const char *kb, const char *vb, con
 #undef AGENTSAM_DMA_GROUP
 
 template <int D, int MT, int NS, bool XT>
-__global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
+__device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *sched_tmp, int wg, int nwg) {
     using W = WideCfg<D>;
-    __shared__ __align__(16) char smem[NS * W::kSlot];
-    __shared__ int sched_tmp[8];
-
-    const int tid = threadIdx.x;
+    // (opaque: a kernel that runs two bodies one after the other computes each body's lane constants when
+    // that body starts, instead of keeping both sets in registers across both)
+    const int tid = opaque((int)threadIdx.x);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave index lives in an SGPR
     const int n = lane & 15, g = lane >> 4;
     const int R = p.R;
@@ -919,7 +932,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     const int64_t page_bytes = (int64_t)p.Hkv * p.P * D * 2;
     const unsigned smem_addr = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem;   // LDS byte address
 
-    for_each_segment(p, sched_tmp, [&](const Segment &sg) __attribute__((always_inline)) {
+    for_each_segment(p, sched_tmp, wg, nwg, [&](const Segment &sg) __attribute__((always_inline)) {
     const int b = sg.b, kvh = sg.kvh, S = sg.S;
     const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
     const int row_end = min(sg.rows, row0 + rpw);            // (a short last group of the prefix phase has fewer rows)
@@ -1210,6 +1223,39 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
     });
 }
 
+template <int D, int MT, int NS, bool XT>
+__global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
+    __shared__ __align__(16) char smem[NS * WideCfg<D>::kSlot];
+    __shared__ int sched_tmp[8];
+    wide_body<D, MT, NS, XT>(p, smem, sched_tmp, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Shared-prefix ("cascade") run in one launch.  Every workgroup has a share of the prefix phase (the wide
+// body over the packed rows of a whole group of sessions: bound by the matrix and softmax arithmetic)
+// and a share of the sessions' own parts (the wide body over one session's rows: bound by memory).
+// Even workgroups take the prefix share first, odd ones the own-part share, and a compute unit holds one
+// of each, so its matrix pipe and its memory stream are both busy for most of the launch, and every
+// workgroup has the same total work: no tail.
+template <int D, int MTP, bool XTP, int NS>
+__global__ __launch_bounds__(256, 2) void attn_cascade_fused_kernel(const AttnParams p) {
+    __shared__ __align__(16) char smem[NS * WideCfg<D>::kSlot];
+    __shared__ int sched_tmp[8];
+    const int wg = (int)blockIdx.x, nwg = (int)gridDim.x;
+#pragma nounroll
+    for (int step = 0; step < 2; ++step) {
+        if (((step ^ wg) & 1) == 0) {
+            AttnParams pp = p;
+            pp.phase = 1;
+            pp.rows = p.gs * p.rows1;                        // rows1 stays the rows of one session
+            pp.balanced = 0;
+            wide_body<D, MTP, NS, XTP>(pp, smem, sched_tmp, wg, nwg);
+        } else {
+            wide_body<D, 1, NS, false>(p, smem, sched_tmp, wg, nwg);
+        }
+        __syncthreads();
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // log-sum-exp merge of the chunk partials (sessions with more than one chunk)
 //   out = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c ,  M = max_c m_c
@@ -1314,13 +1360,16 @@ __global__ __launch_bounds__(256) void attn_lcp_kernel(const AttnParams p, int32
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_cascade_kernel(const AttnParams p) {
     __shared__ int tmp[4];
-    const int kvh = blockIdx.x, b = blockIdx.y;
+    constexpr int kRowsPerWg = 256 / (D / 4);                // one thread per (row, 4 output values)
+    const int kvh = blockIdx.x, b = blockIdx.y, slab = blockIdx.z;
     const int ptiles = shared_prefix_tiles(p, tmp);
     const int nt_b = max(0, tiles_of(session_len(p, b)) - ptiles);
     if (nt_b == 0) {                                         // an empty session (a valid one has its new rows after the prefix)
-        zero_session_heads(p.out, p.out_bf16, b, p.R, p.Hq, D, kvh * p.G, p.G);
+        if (slab == 0) zero_session_heads(p.out, p.out_bf16, b, p.R, p.Hq, D, kvh * p.G, p.G);
         return;
     }
+    // the session's own part: the records of the workgroups whose shares overlap the stream, or the stream's
+    // own record when one workgroup had all of it
     const int T = p.plan[p.B] * p.Hkv;
     const int share = balanced_share(T, p.nslots);
     const int g0 = p.plan[b] * p.Hkv + kvh * nt_b, g1 = g0 + nt_b;
@@ -1328,45 +1377,46 @@ __global__ __launch_bounds__(256) void attn_merge_cascade_kernel(const AttnParam
     if (ptiles == 0 && i0 == i1) return;                     // no prefix part, one workgroup had the stream: output written
     const int64_t recf = ws_record_floats(p.rows_pad, D);
     const int64_t recfp = ws_record_floats(p.rows_pad_p, D);
-    const int first_slot = (i0 * share < g0) ? 1 : 0;
-    // the session's own part: one record if a single workgroup had it (slot after the per-workgroup ones), else
-    // one per workgroup
-    const int n_own = (i0 == i1) ? 1 : i1 - i0 + 1;
-    auto own = [&](int j) {
-        if (i0 == i1) return p.wsr + (2 * (int64_t)p.nslots + (int64_t)b * p.Hkv + kvh) * recf;
-        const int i = i0 + j;
-        return p.wsr + (2 * (int64_t)i + (i == i0 ? first_slot : 0)) * recf;
-    };
-    // the prefix part: the chunks of the session's group, rows [so*rows1, (so+1)*rows1) of each record
+    const int n_own = i1 - i0 + 1;
+    auto own = [&](int j) { return p.wsr + ((int64_t)(i0 + j) + (int64_t)b * p.Hkv + kvh) * recf; };
+    // the prefix part: the same arithmetic over the (group, kv head) streams of ptiles tiles each; the
+    // session's rows are the slice [so*rows1, (so+1)*rows1) of its group's packed rows
     const int grp = b / p.gs, so = b % p.gs;
-    const int n_pre = (ptiles + p.pchunk_tiles - 1) / p.pchunk_tiles;
-    auto pre = [&](int c) { return p.wsp + (((int64_t)grp * p.Hkv + kvh) * p.npchunks_max + c) * recfp; };
-    const int rows1 = p.rows1;
-    for (int idx = threadIdx.x; idx < rows1 * (D / 4); idx += 256) {
-        const int pr = idx / (D / 4), c4 = idx % (D / 4);
-        const int prp = so * rows1 + pr;
-        // one pass over the records with a running maximum (every record is read once)
-        float M = kNegBig, L = 0.f;
-        float4 acc{0.f, 0.f, 0.f, 0.f};
-        auto add = [&](const float *rec, int rpad, int row) {
-            const float m = rec[(int64_t)rpad * D + row];
-            const float l = rec[(int64_t)rpad * D + rpad + row];
-            const float4 o = *(const float4 *)(rec + (int64_t)row * D + c4 * 4);
-            const float Mn = fmaxf(M, m);
-            const float sa = exp2f(M - Mn), sb = exp2f(m - Mn);
-            M = Mn;
-            L = L * sa + l * sb;
-            acc.x = acc.x * sa + o.x * sb; acc.y = acc.y * sa + o.y * sb;
-            acc.z = acc.z * sa + o.z * sb; acc.w = acc.w * sa + o.w * sb;
-        };
-        for (int j = 0; j < n_own; ++j) add(own(j), p.rows_pad, pr);
-        for (int c = 0; c < n_pre; ++c) add(pre(c), p.rows_pad_p, prp);
-        const float inv = inv_or_zero(L);
-        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-        const int hh = pr / p.R, i = pr % p.R;
-        const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
-        store_out(p.out, o, acc, p.out_bf16);
+    int n_pre = 0, j0 = 0;
+    const int sp = grp * p.Hkv + kvh;
+    if (ptiles > 0) {
+        const int share_p = balanced_share(p.ngroups * p.Hkv * ptiles, p.nslots);
+        const int q0 = sp * ptiles, q1 = q0 + ptiles;
+        j0 = q0 / share_p;
+        n_pre = (q1 - 1) / share_p - j0 + 1;
     }
+    auto pre = [&](int j) { return p.wsp + ((int64_t)(j0 + j) + sp) * recfp; };
+    const int rows1 = p.rows1;
+    const int pr = slab * kRowsPerWg + (int)threadIdx.x / (D / 4), c4 = (int)threadIdx.x % (D / 4);
+    if (pr >= rows1) return;
+    const int prp = so * rows1 + pr;
+    // pass 1: the common reference; pass 2: the weighted sums (independent loads, several in flight)
+    float M = kNegBig;
+    for (int j = 0; j < n_own; ++j) M = fmaxf(M, own(j)[(int64_t)p.rows_pad * D + pr]);
+    for (int j = 0; j < n_pre; ++j) M = fmaxf(M, pre(j)[(int64_t)p.rows_pad_p * D + prp]);
+    float L = 0.f;
+    float4 acc{0.f, 0.f, 0.f, 0.f};
+    auto add = [&](const float *rec, int rpad, int row) {
+        const float w = exp2f(rec[(int64_t)rpad * D + row] - M);
+        const float l = rec[(int64_t)rpad * D + rpad + row];
+        const float4 o = *(const float4 *)(rec + (int64_t)row * D + c4 * 4);
+        L += w * l;
+        acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
+    };
+#pragma unroll 4
+    for (int j = 0; j < n_own; ++j) add(own(j), p.rows_pad, pr);
+#pragma unroll 4
+    for (int j = 0; j < n_pre; ++j) add(pre(j), p.rows_pad_p, prp);
+    const float inv = inv_or_zero(L);
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    const int hh = pr / p.R, i = pr % p.R;
+    const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
+    store_out(p.out, o, acc, p.out_bf16);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1497,7 +1547,7 @@ struct Plan {
     size_t ws_bytes;
     // shared-prefix run
     bool cascade;
-    int gs, ngroups, rows_group, rows_pad_p, pchunk_tiles, npchunks_max;
+    int gs, ngroups, rows_group, rows_pad_p;
     size_t lcp_bytes, own_bytes; // workspace: [lcp][plan][own records][prefix records]
 };
 
@@ -1565,35 +1615,32 @@ int make_plan(int B, int R, int Hq, int Hkv, int D, int page_size, int max_pages
     const size_t rec_bytes = (size_t)pl->rows_pad * (D + 2) * sizeof(float);
     if (dtype == AGENTSAM_BF16) {
         // Shared-prefix run: groups of gs sessions (as many as fit the wide kernel's 192 packed rows) take
-        // the common prefix together.  Looked for by default only when the detection (two small launches,
-        // about 10 us) is below half a percent of the time the K/V stream itself takes.
+        // the common prefix together, in the same launch as the sessions' own parts (which then go through
+        // the wide kernel body too: up to 64 packed rows per session).  Looked for by default only when the
+        // detection (a small launch, about 5 us) is below half a percent of the time the K/V stream itself takes.
         const int rows1 = G * R;
         const int gs = std::min<int>(B, (kWaves * kRowsPerGroup) / rows1);
         const double kv_bytes = (double)smax * B * Hkv * 2.0 * D * 2.0;
         const int64_t tiles_max = (int64_t)B * Hkv * ((smax + kTile - 1) / kTile);
-        if (gs >= 2 && gs * rows1 > kRowsPerGroup && tiles_max <= 0x7fffffffll && opt == 0 &&
+        if (gs >= 2 && rows1 <= 64 && gs * rows1 > kRowsPerGroup && tiles_max <= 0x7fffffffll && opt == 0 &&
             tn.sched != 1 && (tn.casc == 2 || (tn.casc == 0 && kv_bytes >= 11.0e9))) {
             pl->cascade = true;
             pl->balanced = true;                             // the sessions' own parts: balanced shares
+            pl->wide = true;
+            // two workgroups per compute unit, fewer when the batch cannot have 16 tiles for each
+            pl->nslots = (int)std::min<int64_t>(2 * kComputeUnits, std::max<int64_t>(16, tiles_max / 16));
             pl->gs = gs;
             pl->ngroups = (B + gs - 1) / gs;
             pl->rows_group = gs * rows1;
             pl->rows_pad_p = (pl->rows_group + 3) & ~3;
-            const int64_t max_tiles = (smax + kTile - 1) / kTile;
-            int64_t pc = (max_tiles * pl->ngroups * Hkv + 1023) / 1024;      // about 1024 prefix workgroups
-            if (pc < 64) pc = 64;
-            if (pc > kMaxChunk / kTile) pc = kMaxChunk / kTile;
-            pl->pchunk_tiles = (int)pc;
-            pl->npchunks_max = (int)((max_tiles + pc - 1) / pc);
-            if ((int64_t)pl->npchunks_max * pl->ngroups * Hkv > 0x7fffffffll) pl->cascade = false;
         }
     }
     if (pl->cascade) {
         pl->lcp_bytes = ((size_t)B * sizeof(int32_t) + 255) & ~(size_t)255;
         pl->plan_bytes = (((size_t)B + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
-        pl->own_bytes = (2 * (size_t)pl->nslots + (size_t)B * Hkv) * rec_bytes;
+        pl->own_bytes = ((size_t)pl->nslots + (size_t)B * Hkv) * rec_bytes;
         pl->ws_bytes = pl->lcp_bytes + pl->plan_bytes + pl->own_bytes +
-                       (size_t)pl->ngroups * Hkv * pl->npchunks_max * (size_t)pl->rows_pad_p * (D + 2) * sizeof(float);
+                       ((size_t)pl->nslots + (size_t)pl->ngroups * Hkv) * (size_t)pl->rows_pad_p * (D + 2) * sizeof(float);
     } else if (pl->balanced) {
         pl->plan_bytes = (((size_t)B + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
         pl->ws_bytes = pl->plan_bytes + 2 * (size_t)pl->nslots * rec_bytes;
@@ -1626,6 +1673,23 @@ hipError_t launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st
     if (mt == 1) return launch((attn_bf16_narrow_kernel<D, 1>), grid, dim3(256), st, p);
     if (mt == 2) return launch((attn_bf16_narrow_kernel<D, 2>), grid, dim3(256), st, p);
     return launch((attn_bf16_narrow_kernel<D, 3>), grid, dim3(256), st, p);
+}
+
+// the fused shared-prefix launch: the prefix phase's kernel variant follows the group's packed rows
+template <int D>
+hipError_t launch_cascade(const AttnParams &p, int rows_group, dim3 grid, hipStream_t st) {
+    using agentsam::launch;
+    constexpr int NS = 65536 / WideCfg<D>::kSlot;
+    const int rpw = (rows_group + kWaves - 1) / kWaves;
+    const int mt = (rpw + 15) / 16;
+    const int extra = rows_group - kWaves * 16 * (mt - 1);
+    if (mt >= 2 && extra >= 1 && extra <= 16) {
+        if (mt == 2) return launch((attn_cascade_fused_kernel<D, 1, true, NS>), grid, dim3(256), st, p);
+        return launch((attn_cascade_fused_kernel<D, 2, true, NS>), grid, dim3(256), st, p);
+    }
+    if (mt == 1) return launch((attn_cascade_fused_kernel<D, 1, false, NS>), grid, dim3(256), st, p);
+    if (mt == 2) return launch((attn_cascade_fused_kernel<D, 2, false, NS>), grid, dim3(256), st, p);
+    return launch((attn_cascade_fused_kernel<D, 3, false, NS>), grid, dim3(256), st, p);
 }
 
 #define ATTN_TRY(expr)                                        \
@@ -1663,7 +1727,7 @@ int run_attn(const void *q, const void *k_cache, const void *v_cache, const int3
     p.balanced = pl.balanced ? 1 : 0;
     p.plan = (int32_t *)workspace;
     p.wsr = (float *)((char *)workspace + pl.plan_bytes);
-    p.cascade = 0; p.phase = 0; p.gs = 1; p.ngroups = B; p.rows1 = p.rows; p.pchunk_tiles = 1; p.npchunks_max = 0;
+    p.cascade = 0; p.phase = 0; p.gs = 1; p.ngroups = B; p.rows1 = p.rows;
     p.rows_pad_p = pl.rows_pad; p.nslots = pl.nslots; p.lcp = nullptr; p.wsp = nullptr;
 
     if (pl.cascade) {
@@ -1675,20 +1739,14 @@ int run_attn(const void *q, const void *k_cache, const void *v_cache, const int3
         p.plan = (int32_t *)(wsb + pl.lcp_bytes);
         p.wsr = (float *)(wsb + pl.lcp_bytes + pl.plan_bytes);
         p.wsp = (float *)(wsb + pl.lcp_bytes + pl.plan_bytes + pl.own_bytes);
-        p.gs = pl.gs; p.ngroups = pl.ngroups; p.pchunk_tiles = pl.pchunk_tiles; p.npchunks_max = pl.npchunks_max;
+        p.gs = pl.gs; p.ngroups = pl.ngroups;
         p.rows_pad_p = pl.rows_pad_p;
         ATTN_TRY(launch(attn_lcp_kernel, dim3((unsigned)B), dim3(256), st, p, lcp));
-        // prefix phase: the wide kernel over the packed rows of a whole group
-        AttnParams pp = p;
-        pp.phase = 1;
-        pp.rows = pl.rows_group;                             // rows1 stays the rows of one session
-        pp.balanced = 0;
-        dim3 pgrid((unsigned)((int64_t)pl.npchunks_max * pl.ngroups * Hkv));
-        ATTN_TRY(D == 64 ? launch_bf16<64>(pp, true, pgrid, st) : launch_bf16<128>(pp, true, pgrid, st));
-        // the sessions' own parts, balanced
-        dim3 sgrid((unsigned)pl.nslots);
-        ATTN_TRY(D == 64 ? launch_bf16<64>(p, pl.wide, sgrid, st) : launch_bf16<128>(p, pl.wide, sgrid, st));
-        dim3 mg((unsigned)Hkv, (unsigned)B);
+        // one launch for the prefix phase (the packed rows of a whole group) and the sessions' own parts
+        ATTN_TRY(D == 64 ? launch_cascade<64>(p, pl.rows_group, dim3((unsigned)pl.nslots), st)
+                         : launch_cascade<128>(p, pl.rows_group, dim3((unsigned)pl.nslots), st));
+        const int slabs = (p.rows + (256 / (D / 4)) - 1) / (256 / (D / 4));
+        dim3 mg((unsigned)Hkv, (unsigned)B, (unsigned)slabs);
         ATTN_TRY(D == 64 ? launch(attn_merge_cascade_kernel<64>, mg, dim3(256), st, p)
                          : launch(attn_merge_cascade_kernel<128>, mg, dim3(256), st, p));
         return AGENTSAM_OK;

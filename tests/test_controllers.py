@@ -79,3 +79,118 @@ def test_argument_errors():
         A.agentsched_pick(10, [1], [1], [16], [0.0], **dict(P, lambda_max=0.0))
     with pytest.raises(A.AgentSamError):
         A.agentsched_pick(10, [-1], [1], [16], [0.0], **P)
+
+
+# ------------------------------------------------------------------------------------------ speculation depth
+from oracle import choose_k_oracle, expected_committed_oracle, switch_frontier_oracle   # noqa: E402
+
+
+def _enumerated_committed(k, p):
+    """Every accept / reject outcome of the k drafts written out: 2^k outcomes, each with its probability and the
+    tokens it commits (accepted prefix up to the first rejection, plus one)."""
+    total = 0.0
+    for mask in range(1 << k):
+        prob, prefix, running = 1.0, 0, True
+        for j in range(k):
+            ok = (mask >> j) & 1
+            prob *= p if ok else (1.0 - p)
+            if running and ok:
+                prefix += 1
+            else:
+                running = False
+        total += prob * (prefix + 1)
+    return total
+
+
+def test_expected_committed_tokens_oracle_pins():
+    for p in (0.0, 0.17, 0.6, 0.65, 0.99, 1.0):
+        for k in range(0, 11):
+            e = expected_committed_oracle(k, p)
+            assert e == pytest.approx(_enumerated_committed(k, p), rel=1e-12)                 # brute force over outcomes
+            if p < 1.0:
+                assert e == pytest.approx((1 - p ** (k + 1)) / (1 - p), rel=1e-12)            # geometric series
+            assert 1.0 <= e <= k + 1 + 1e-12
+    assert expected_committed_oracle(8, 1.0) == 9.0 and expected_committed_oracle(8, 0.0) == 1.0
+    # the workload list's own figures: E[accepted drafts] = sum p^j
+    assert expected_committed_oracle(8, 0.6) - 1 == pytest.approx(1.475, abs=1e-3)
+    assert expected_committed_oracle(8, 0.7) - 1 == pytest.approx(2.199, abs=1e-3)
+    assert expected_committed_oracle(4, 0.7) - 1 == pytest.approx(1.773, abs=1e-3)
+
+
+def test_choose_k_oracle_pins():
+    ks = list(range(0, 9))
+    # constant cost: every extra draft is free, the deepest wins; p = 0: nothing is ever accepted, k = 0 wins
+    assert choose_k_oracle(ks, [1.0] * 9, 0.5)[0] == 8
+    assert choose_k_oracle(ks, [1.0 + 0.01 * k for k in ks], 0.0) == (0, 1.0)
+    # p = 1 and cost a + b(1+k): (1+k)/(a + b(1+k)) grows with k whenever a > 0
+    assert choose_k_oracle(ks, [2.0 + 0.5 * (1 + k) for k in ks], 1.0)[0] == 8
+    # cost proportional to the rows and p < 1: (1 + p + ..)/(1+k) falls with k, so no speculation
+    assert choose_k_oracle(ks, [0.3 * (1 + k) for k in ks], 0.9)[0] == 0
+    # the break-even rule: depth k beats no speculation iff p + .. + p^k > cost(k)/cost(0) - 1
+    for p in (0.04, 0.06, 0.3):
+        t = [1.0, 1.055]                                      # cost of 8 drafts: 5.5 % over a plain step
+        pays = sum(p ** j for j in range(1, 9)) > t[1] / t[0] - 1
+        assert (choose_k_oracle([0, 8], t, p)[0] == 8) == pays
+    # the other layers: free below the floor, per row above it -> the depth stops where the rows reach the floor
+    k, gain = choose_k_oracle(ks, [1.0] * 9, 0.8, batch=4, other_floor=2.0, other_per_row=0.1)   # floor reached at 20 rows = k 4
+    assert k == 4 and gain == pytest.approx(expected_committed_oracle(4, 0.8) * 3.0 / 3.0)
+    # gain is relative to k = 0
+    k, gain = choose_k_oracle([0, 4], [2.0, 2.5], 0.5)
+    assert k == 4 and gain == pytest.approx(expected_committed_oracle(4, 0.5) / 2.5 * 2.0)
+
+
+def test_switch_frontier_oracle_pins():
+    # a surface on which verification costs nothing at short contexts and k-proportionally more at long ones:
+    # t(B, S, k) = S/1000 * (1 + k * S / 64000); with p = 0.5 (sum p^j < 1) speculation stops paying beyond a context
+    batches, contexts, ks = [1, 8, 64], [1000, 8000, 32000, 128000], [0, 2, 4]
+    t = [[[S / 1000 * (1 + k * S / 64000) for k in ks] for S in contexts] for _ in batches]
+    kstar, cthr, bthr = switch_frontier_oracle(batches, contexts, ks, t, 0.5)
+    for i in range(3):
+        for j, S in enumerate(contexts):
+            pays = any(sum(0.5 ** m for m in range(1, k + 1)) > (1 + k * S / 64000) - 1 for k in ks[1:])
+            assert (kstar[i][j] > 0) == pays
+    assert cthr == [8000, 8000, 8000] and bthr == [64, 64, -1, -1]
+    # row-proportional other layers switch speculation off beyond a batch size
+    t1 = [[[1.0 for _ in ks] for _ in contexts] for _ in batches]
+    kstar, cthr, bthr = switch_frontier_oracle(batches, contexts, ks, t1, 0.5, other_floor=1.0, other_per_row=0.05)
+    assert [row[0] for row in kstar] == [4, 2, 0]             # 1 + k <= 20 rows / batch stay under the floor
+    assert bthr == [8] * 4 and cthr == [128000, 128000, -1]
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_speculation_controller_matches_oracle(seed):
+    rng = np.random.default_rng(100 + seed)
+    for _ in range(50):
+        nk = int(rng.integers(1, 9))
+        ks = [0] + sorted(rng.choice(np.arange(1, 33), nk - 1, replace=False).tolist())
+        t = (rng.uniform(0.5, 2.0) * (1 + np.asarray(ks) * rng.uniform(0, 0.1))).tolist()
+        p = float(rng.choice([0.0, 1.0, rng.uniform(0, 1)]))
+        batch = int(rng.integers(1, 200))
+        floor_, per_row = float(rng.choice([0.0, rng.uniform(0, 3)])), float(rng.choice([0.0, rng.uniform(0, 0.02)]))
+        k1, g1 = A.spec_choose_k(ks, t, p, per_row, batch, floor_)
+        k0, g0 = choose_k_oracle(ks, t, p, batch, floor_, per_row)
+        assert k1 == k0 and g1 == pytest.approx(g0, rel=1e-12)
+    batches = sorted(rng.choice(np.arange(1, 300), 4, replace=False).tolist())
+    contexts = sorted(rng.choice(np.arange(1, 200000), 5, replace=False).tolist())
+    ks = [0, 1, 3, 8, 16]
+    t = rng.uniform(0.5, 1.0, (4, 5, 1)) * (1 + np.asarray(ks)[None, None, :] * rng.uniform(0, 0.3, (4, 5, 1)))
+    for p in (0.2, 0.6, 0.95):
+        got = A.spec_switch_frontier(batches, contexts, ks, t, p, 0.7, 0.002)
+        want = switch_frontier_oracle(batches, contexts, ks, t.tolist(), p, 0.7, 0.002)
+        assert got[0].tolist() == want[0] and got[1].tolist() == want[1] and got[2].tolist() == want[2]
+        # the thresholds feed the switch: inside both, speculation stays on
+        for i, b in enumerate(batches):
+            for j, s in enumerate(contexts):
+                if s <= got[1][i] and b <= got[2][j]:
+                    assert got[0][i, j] > 0
+
+
+def test_speculation_controller_argument_errors():
+    with pytest.raises(A.AgentSamError):
+        A.spec_choose_k([1, 2], [1.0, 1.0], 0.5)              # the table must start at k = 0
+    with pytest.raises(A.AgentSamError):
+        A.spec_choose_k([0, 2, 2], [1.0, 1.0, 1.0], 0.5)
+    with pytest.raises(A.AgentSamError):
+        A.spec_choose_k([0, 2], [1.0, 0.0], 0.5)
+    with pytest.raises(A.AgentSamError):
+        A.spec_choose_k([0, 2], [1.0, 1.0], 1.5)

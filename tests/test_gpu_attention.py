@@ -263,9 +263,12 @@ CASCADE = [
     # B, Hq, Hkv, k, kv_mode, kv_len, prefix_len: groups of 4 / 5 / 2 sessions, a short last group, no sharing at all
     dict(B=6, Hq=10, Hkv=2, k=8, kv_mode="shared_prefix", kv_len=(40, 700), prefix_len=2048),     # 45 rows, groups 4 + 2
     dict(B=11, Hq=8, Hkv=2, k=8, kv_mode="shared_prefix", kv_len=(9, 300), prefix_len=1024),      # 36 rows, groups 5 + 5 + 1
-    dict(B=5, Hq=16, Hkv=4, k=16, kv_mode="shared_prefix", kv_len=(17, 900), prefix_len=1536),    # 68 rows, groups of 2, wide own parts
+    dict(B=5, Hq=16, Hkv=4, k=16, kv_mode="shared_prefix", kv_len=(17, 900), prefix_len=1536),    # 68 rows: too many for a shared-prefix run, plain run
     dict(B=7, Hq=8, Hkv=2, k=8, kv_mode="ragged", kv_len=(9, 2000), permute_pages=True),          # nothing shared
     dict(B=4, Hq=8, Hkv=2, k=8, kv_mode="shared_prefix", kv_len=(9, 60), prefix_len=64),          # one shared page
+    dict(B=7, Hq=28, Hkv=4, k=8, kv_mode="shared_prefix", kv_len=(40, 1500), prefix_len=4096),    # 63 rows, groups of 3 (3 + 3 + 1)
+    dict(B=9, Hq=4, Hkv=2, k=8, kv_mode="shared_prefix", kv_len=(9, 900), prefix_len=3072),       # 18 rows, groups of 9 + (none): 162 rows
+    dict(B=40, Hq=12, Hkv=4, k=8, kv_mode="shared_prefix", kv_len=(30, 400), prefix_len=12288),   # 27 rows, groups of 7: shares of many tiles
 ]
 
 
