@@ -301,8 +301,11 @@ def measure_ksweep(A, W, cfg, dev, p_accept):
 
 def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest=None):
     """Incremental maintenance of the device automaton: every round appends 2 tokens per session (about
-    what a verified step commits) to the memories, exports the delta, updates the device copy and drafts
-    from it.  Host times are wall clock, device times HIP events."""
+    what a verified step commits) to the memories, exports the delta (only what is new since the last
+    export), and one launch scatters it into the device copy and inserts its transitions into the device
+    overlay table; the lookup then runs on the maintained copy.  Host times are wall clock, device times
+    HIP events."""
+    import dataclasses
     import torch
     rng = np.random.default_rng(cfg.seed)
     mems = [list(m) for m in mems]
@@ -315,32 +318,45 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
     mem_len = [len(m) for m in mems]
     root_d = torch.as_tensor(flat.roots[idx], device=dev)
     rows_end_d = torch.as_tensor(flat.rows_end[idx], device=dev)
-    t_host, t_dev, t_draft, n_ov = [], [], [], 0
-    for _ in range(steps):
-        th = time.perf_counter()
+    # the overlay table lives on the device for the whole run: room for every transition the run can log
+    cap = 1 << 12
+    while cap < 2 * 8 * per_mem * len(mems) * (4 * steps + 1):
+        cap *= 2
+    keys_d, dsts_d = A.overlay_table(cap, device=dev)
+
+    def up(a):                                                # pinned staging: the copy is a DMA on the current stream
+        return torch.from_numpy(np.ascontiguousarray(a)).pin_memory().to(dev, non_blocking=True)
+
+    def host_part():
         for i, T in enumerate(mems):
             p = int(rng.integers(0, max(1, len(T) - per_mem)))
             add = [x for x in T[p:p + per_mem] if x != cfg.sep] or [0]      # text seen before: matches, clones
             A.sam_append(sams[i], np.asarray(add, np.int32))
             T += add
-        n_ov = sum(A.sam_delta_sizes(s)[2] for s in sams)
-        cap = 2
-        while cap < 2 * n_ov:
-            cap *= 2
-        keys, dsts = A.overlay_table(cap)
-        deltas = [A.sam_delta_export(s, keys, dsts, int(flat.roots[i]), int(flat.corpus_begin[i]))
-                  for i, s in enumerate(sams)]
-        t_host.append(time.perf_counter() - th)
-        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        e0.record()
+        deltas = [A.sam_delta_export(s, int(flat.roots[i]), int(flat.corpus_begin[i])) for i, s in enumerate(sams)]
+        assert 2 * sum(d.n_overlay for d in deltas) <= cap
+        return deltas
+
+    def device_part(deltas):
         for i, d in enumerate(deltas):
-            A.sam_apply_delta(d, fd.state_rec, fd.lastpos)
+            dd = dataclasses.replace(d, rec_idx=up(d.rec_idx), rec_val=up(d.rec_val), lastpos_idx=up(d.lastpos_idx),
+                                     lastpos_val=up(d.lastpos_val), ov_key=up(d.ov_key.view(np.int64)), ov_dst=up(d.ov_dst))
+            A.sam_apply_delta(dd, fd.state_rec, fd.lastpos, keys_d, dsts_d)
             n = d.new_tokens.shape[0]
             at = int(flat.corpus_begin[i]) + mem_len[i]
-            fd.corpus[at:at + n] = torch.as_tensor(d.new_tokens, device=dev)
+            fd.corpus[at:at + n] = up(d.new_tokens)
             mem_len[i] += n
-        keys_d, dsts_d = torch.as_tensor(keys.view(np.int64), device=dev), torch.as_tensor(dsts, device=dev)
-        cend_d = torch.as_tensor((flat.corpus_begin + np.asarray(mem_len))[idx].astype(np.int32), device=dev)
+        return up((flat.corpus_begin + np.asarray(mem_len))[idx].astype(np.int32))
+
+    t_host, t_dev, t_draft, n_ov, n_ov_round = [], [], [], 0, []
+    for _ in range(steps):
+        th = time.perf_counter()
+        deltas = host_part()
+        t_host.append(time.perf_counter() - th)
+        n_ov = sum(d.n_overlay for d in deltas); n_ov_round.append(sum(d.ov_key.size for d in deltas))
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record()
+        cend_d = device_part(deltas)
         e1.record()
         A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
         e2.record()
@@ -351,60 +367,40 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
         # Whole rounds, wall clock: (a) one thing after the other; (b) the step is launched first, the host
         # appends and exports while the GPU runs it, and the device copy is updated on a second stream as soon
         # as the step's lookup has finished, next to the attention (Sec. 5.4.2: maintenance off the decoding path).
-        def host_part():
-            for i, T in enumerate(mems):
-                p = int(rng.integers(0, max(1, len(T) - per_mem)))
-                add = [x for x in T[p:p + per_mem] if x != cfg.sep] or [0]
-                A.sam_append(sams[i], np.asarray(add, np.int32))
-                T += add
-            n = sum(A.sam_delta_sizes(s)[2] for s in sams)
-            cap = 2
-            while cap < 2 * n:
-                cap *= 2
-            keys, dsts = A.overlay_table(cap)
-            return keys, dsts, [A.sam_delta_export(s, keys, dsts, int(flat.roots[i]), int(flat.corpus_begin[i]))
-                                for i, s in enumerate(sams)]
-
-        def up(a):                                            # pinned staging: the copy is a DMA on the current stream
-            return torch.from_numpy(np.ascontiguousarray(a)).pin_memory().to(dev, non_blocking=True)
-
-        def device_part(keys, dsts, deltas):
-            import dataclasses
-            for i, d in enumerate(deltas):
-                dd = dataclasses.replace(d, rec_idx=up(d.rec_idx), rec_val=up(d.rec_val), lastpos_idx=up(d.lastpos_idx),
-                                         lastpos_val=up(d.lastpos_val))
-                A.sam_apply_delta(dd, fd.state_rec, fd.lastpos)
-                n = d.new_tokens.shape[0]
-                at = int(flat.corpus_begin[i]) + mem_len[i]
-                fd.corpus[at:at + n] = up(d.new_tokens)
-                mem_len[i] += n
-            return (up(keys.view(np.int64)), up(dsts),
-                    up((flat.corpus_begin + np.asarray(mem_len))[idx].astype(np.int32)))
-
-        state = [keys_d, dsts_d, cend_d]
         main, side = torch.cuda.current_stream(), torch.cuda.Stream()
         # third mode: as "overlapped", with the lookup carrying its matched state (three tokens consumed per call)
         new_tok_d = recent_d[:, -3:].contiguous()
         n_new_d = torch.full((recent_d.shape[0],), 3, dtype=torch.int32, device=dev)
         cur_state = torch.full((recent_d.shape[0],), -1, dtype=torch.int32, device=dev)
         cur_len = torch.zeros((recent_d.shape[0],), dtype=torch.int32, device=dev)
+        # the bare step on the same maintained copy, nothing appended: what a round is compared with
+        for _ in range(3):
+            d, nd, _, _ = A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
+            rest(d, nd)
+        torch.cuda.synchronize()
+        tr0 = time.perf_counter()
+        for _ in range(steps):
+            d, nd, _, _ = A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
+            rest(d, nd)
+        torch.cuda.synchronize()
+        res_rounds["step_ms_without_maintenance"] = (time.perf_counter() - tr0) / steps * 1e3
         for mode in ("sequential", "overlapped", "overlapped_carried_state"):
             torch.cuda.synchronize()
             tr0 = time.perf_counter()
             for _ in range(steps):
                 if mode == "sequential":
-                    state = list(device_part(*host_part()))
-                    d, nd, _, _ = A.sam_draft_delta(fd, state[0], state[1], rows_end_d, root_d, state[2], recent_d, rlen_d,
+                    cend_d = device_part(host_part())
+                    d, nd, _, _ = A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d, rlen_d,
                                                     cfg.k, cfg.sep)
                     rest(d, nd)
                     torch.cuda.synchronize()
                 else:
                     if mode == "overlapped":
-                        d, nd, _, _ = A.sam_draft_delta(fd, state[0], state[1], rows_end_d, root_d, state[2], recent_d,
+                        d, nd, _, _ = A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d,
                                                         rlen_d, cfg.k, cfg.sep)
                     else:
-                        d, nd, _, _ = A.sam_draft_step(fd, root_d, state[2], new_tok_d, n_new_d, cur_state, cur_len,
-                                                       cfg.k, cfg.sep, overlay_key=state[0], overlay_dst=state[1],
+                        d, nd, _, _ = A.sam_draft_step(fd, root_d, cend_d, new_tok_d, n_new_d, cur_state, cur_len,
+                                                       cfg.k, cfg.sep, overlay_key=keys_d, overlay_dst=dsts_d,
                                                        rows_end=rows_end_d)
                     looked_up = torch.cuda.Event()
                     looked_up.record(main)
@@ -412,7 +408,7 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
                     hp = host_part()                          # the GPU is busy with the step meanwhile
                     with torch.cuda.stream(side):
                         side.wait_event(looked_up)            # the lookup must not see a half-updated copy
-                        state = list(device_part(*hp))
+                        cend_d = device_part(hp)
                     main.wait_stream(side)                    # the next lookup sees the whole update
             torch.cuda.synchronize()
             res_rounds["round_ms_" + mode] = (time.perf_counter() - tr0) / steps * 1e3
@@ -420,7 +416,26 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
             "host_append_and_export_us": float(np.median(t_host)) * 1e6,
             "device_update_us_incl_uploads": float(np.median(t_dev)) * 1e3,
             "t_draft_delta_us": float(np.median(t_draft)) * 1e3,
-            "overlay_transitions_at_end": int(n_ov), "full_flatten_ms": t_flatten * 1e3}
+            "overlay_transitions_per_round": float(np.median(n_ov_round)),
+            "overlay_transitions_at_end": int(n_ov), "overlay_capacity": cap, "full_flatten_ms": t_flatten * 1e3}
+
+
+def measure_periodic_append(A):
+    """Maintenance on a continuously repetitive memory (the prompt of the paper's TTFT / TPOT table): 30k and 128k
+    tokens of period 3, then 3 tokens appended and one delta exported per round, 300 rounds."""
+    out = {}
+    for name, n in (("30k", 30000), ("128k", 131072)):
+        base = np.tile(np.array([5, 6, 7], np.int32), n // 3 + 1)[:n]
+        s = A.sam_build(base, 9)
+        A.sam_flatten([s])
+        t0 = time.perf_counter()
+        n_lp = 0
+        for r in range(300):
+            A.sam_append(s, np.array([5, 6, 7], np.int32) if n % 3 == 0 else np.roll(np.array([5, 6, 7], np.int32), -(n % 3)))
+            n_lp += A.sam_delta_export(s).lastpos_idx.size
+        dt = time.perf_counter() - t0
+        out[name] = {"round_us_append3_and_export": dt / 300 * 1e6, "lastpos_updates_per_round": n_lp / 300}
+    return out
 
 
 def measure_build(A, cfg):
@@ -623,6 +638,7 @@ def main():
         result["detail"]["ms_per_step_graph"] = (time.perf_counter() - tg0) / args.steps * 1e3
     if not args.attn_only:
         result["detail"]["sam_prompt_build"] = measure_build(A, cfg)
+        result["detail"]["sam_periodic_memory_maintenance"] = measure_periodic_append(A)
     if args.maintain > 0:
         def rest(d, nd):
             inp.attn()

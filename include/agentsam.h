@@ -133,27 +133,40 @@ void sam_free(sam_t *s);
  * sam_append() has run: states whose walk record or last eligible end position changed (new
  * states included), transitions added or redirected to a clone, and the new tokens.
  *
- *   sam_delta_sizes   counts of each; flat_states = states covered by the last sam_flatten
- *                     (only those have a transition row).  AGENTSAM_ERR_ARG before any flatten.
+ *   sam_delta_sizes   counts of each; n_overlay = transitions logged since the last sam_flatten (an upper
+ *                     bound of the distinct keys the overlay table must hold: keep its capacity >= twice
+ *                     that), n_overlay_new = those logged since the last sam_delta_export; flat_states =
+ *                     states covered by the last sam_flatten (only those have a transition row).
+ *                     AGENTSAM_ERR_ARG before any flatten.
  *   sam_delta_export  writes, into caller-provided HOST arrays,
  *       rec_idx[n_rec], rec_val[4*n_rec]          state ids and their new 16-byte walk records; a
  *                                                 record of a maintained state names ANY one of its
  *                                                 transitions, flagged -2-d when there are others
  *       lastpos_idx[n_lastpos], lastpos_val[..]   state ids and their new lastpos
- *       overlay_key[cap], overlay_dst[cap]        open-addressing table (linear probing, the hash of
- *                                                 csrc/sam_hash.h) of ALL transitions added or
- *                                                 redirected since the last sam_flatten, key =
- *                                                 state << 32 | token; the caller passes it filled
- *                                                 with ~0 keys (several automata packed in one set of
- *                                                 arrays may be exported into the same table);
- *                                                 cap a power of two >= 2 * n_overlay
+ *       ov_key[<= n_overlay_new], ov_dst[..]      the transitions added or redirected since the last
+ *                                                 export (overlay_all = 0) or since the last sam_flatten
+ *                                                 (overlay_all != 0, n_overlay entries at most: for a
+ *                                                 table that had to be re-created larger), key =
+ *                                                 state << 32 | token, every key once with its latest
+ *                                                 destination; *n_ov_written = how many
  *       new_tokens[n_new_tokens]                  to be written at corpus[corpus_base + old length ..)
- *     and forgets the record / lastpos / token changes (the overlay keeps growing until the next
- *     sam_flatten, which the caller should do once it is no longer small next to the automaton).
- *     Ids are offset by state_base / corpus_base as in sam_flatten.  The device arrays state_rec and
- *     lastpos must have room for the grown automaton (at most 2 states per token).
- *   sam_apply_delta   device: scatters the exported records and lastpos values (device copies of
- *                     the exported arrays) into state_rec and lastpos.
+ *     and forgets these changes (the log of transitions is kept until the next sam_flatten).  Cost:
+ *     proportional to what is exported; the last eligible end positions are brought up to date here
+ *     (and in sam_delta_sizes), one walk towards the root per chain of suffix links that changed, not
+ *     one per appended token.  Ids are offset by state_base / corpus_base as in sam_flatten.  The
+ *     device arrays state_rec and lastpos must have room for the grown automaton (at most 2 states per
+ *     token).
+ *   sam_apply_delta   device: scatters the exported records and lastpos values into state_rec and lastpos
+ *                     and inserts the exported transitions into the overlay table overlay_key[cap] /
+ *                     overlay_dst[cap] (device; open addressing with linear probing and the hash of
+ *                     csrc/sam_hash.h; free slots hold key ~0, which is how the caller creates it; cap a
+ *                     power of two that keeps the table at most half full, see n_overlay).  All inputs
+ *                     are device copies of the exported arrays.  One launch, O(delta).  A lookup on the
+ *                     same arrays must not run at the same time (order them on the stream or with events).
+ *   sam_reflatten_due *due = 1 when the log of transitions since the last sam_flatten has grown beyond
+ *                     max_overlay_fraction of the transitions that flatten wrote (or there was none): time
+ *                     to flatten again (on the builder's child thread: sam_builder_flatten) and to switch
+ *                     the lookups to the new arrays and an empty overlay once they are uploaded.
  *   sam_draft_delta   device: sam_draft on a maintained copy.  A transition is looked up in the
  *                     state's record, then in the overlay, then - for states below rows_end[b], the
  *                     end of the state-id range that has flattened rows in session b's automaton -
@@ -163,16 +176,20 @@ void sam_free(sam_t *s);
  *                     row_ptr tells) are then looked up there instead of being searched.  It need
  *                     not follow later appends: the overlay is asked first.
  * ---------------------------------------------------------------------------------------- */
-int sam_delta_sizes(const sam_t *s, int64_t *n_rec, int64_t *n_lastpos, int64_t *n_overlay,
+int sam_delta_sizes(const sam_t *s, int64_t *n_rec, int64_t *n_lastpos, int64_t *n_overlay, int64_t *n_overlay_new,
                     int64_t *n_new_tokens, int64_t *flat_states);
 
 int sam_delta_export(sam_t *s, int32_t state_base, int32_t corpus_base,
                      int32_t *rec_idx, int32_t *rec_val, int32_t *lastpos_idx, int32_t *lastpos_val,
-                     uint64_t *overlay_key, int32_t *overlay_dst, int64_t overlay_cap, int32_t *new_tokens);
+                     int32_t overlay_all, uint64_t *ov_key, int32_t *ov_dst, int64_t *n_ov_written, int32_t *new_tokens);
 
 int sam_apply_delta(const int32_t *rec_idx, const int32_t *rec_val, int64_t n_rec,
                     const int32_t *lastpos_idx, const int32_t *lastpos_val, int64_t n_lastpos,
-                    int32_t *state_rec, int32_t *lastpos, void *stream);
+                    const uint64_t *ov_key, const int32_t *ov_dst, int64_t n_ov,
+                    int32_t *state_rec, int32_t *lastpos,
+                    uint64_t *overlay_key, int32_t *overlay_dst, int64_t overlay_cap, void *stream);
+
+int sam_reflatten_due(const sam_t *s, double max_overlay_fraction, int32_t *due);
 
 int sam_draft_delta(const int32_t *row_ptr, const int32_t *edge_tok, const int32_t *edge_dst,
                     const int32_t *lastpos, const int32_t *corpus, const int32_t *state_rec,
@@ -233,6 +250,14 @@ int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, const int32_
  *                        A returned automaton stays valid and unchanged until the caller's next submit
  *                        or release for that request (use it with sam_flatten, sam_delta_export, ...;
  *                        never sam_free it).  Returns the error of a failed background append, if any.
+ *   sam_builder_flatten  queues a sam_flatten of the request's automaton (same arguments; the arrays are
+ *                        HOST memory of the caller with room for cap_states / cap_edges / cap_tokens
+ *                        entries, and must stay untouched until the request has nothing pending).  It
+ *                        runs on the child thread after the entries submitted before it, so a grown
+ *                        automaton is flattened again off the decoding thread.
+ *                        sam_builder_flatten_result: AGENTSAM_OK once the last one has written the arrays,
+ *                        AGENTSAM_ERR_WORKSPACE if they were too small (the automaton stays usable),
+ *                        AGENTSAM_ERR_ARG if the request never had one.
  *   sam_builder_wait     blocks until the request has nothing pending.
  *   sam_builder_release  forgets the request; its automaton is freed (at once, or when the child
  *                        thread reaches its last entry).  The id may not be reused until then.
@@ -245,6 +270,11 @@ typedef struct sam_builder sam_builder_t;
 int sam_builder_create(sam_builder_t **out);
 int sam_builder_submit(sam_builder_t *b, int64_t request_id, const int32_t *tokens, int64_t n, int32_t sep_token);
 int sam_builder_poll(sam_builder_t *b, int64_t request_id, sam_t **out, int64_t *pending_tokens);
+int sam_builder_flatten(sam_builder_t *b, int64_t request_id, int32_t state_base, int32_t edge_base, int32_t corpus_base,
+                        int32_t *len, int32_t *link, int32_t *row_ptr, int32_t *edge_tok, int32_t *edge_dst,
+                        int32_t *lastpos, int32_t *corpus, int32_t *state_rec, int64_t cap_states, int64_t cap_edges,
+                        int64_t cap_tokens);
+int sam_builder_flatten_result(sam_builder_t *b, int64_t request_id);
 int sam_builder_wait(sam_builder_t *b, int64_t request_id);
 int sam_builder_release(sam_builder_t *b, int64_t request_id);
 void sam_builder_destroy(sam_builder_t *b);

@@ -24,7 +24,8 @@ _vp = ctypes.c_void_p
 
 EXPORTS = ["agentsam_strerror", "sam_build", "sam_append", "sam_flat_sizes",
            "sam_flatten", "sam_wide_slots", "sam_wide_table", "sam_free", "sam_builder_create", "sam_builder_submit", "sam_builder_poll",
-           "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_delta_sizes", "sam_delta_export", "sam_apply_delta",
+           "sam_builder_wait", "sam_builder_release", "sam_builder_destroy", "sam_builder_flatten", "sam_builder_flatten_result",
+           "sam_delta_sizes", "sam_delta_export", "sam_apply_delta", "sam_reflatten_due",
            "sam_draft", "sam_draft_delta", "sam_draft_step", "sam_draft_merged", "spec_verify_attn_workspace", "spec_verify_attn", "spec_verify_attn_static", "spec_accept",
            "spec_adaptive_k", "spec_choose_k", "spec_switch_frontier", "agentsched_pick"]
 
@@ -56,7 +57,10 @@ def lib():
                                        [_vp, ctypes.c_size_t, _vp, ctypes.c_int64, _vp])
         L.sam_wide_slots.argtypes = [_vp, ctypes.POINTER(ctypes.c_int64)]
         L.sam_wide_table.argtypes = [_vp, ctypes.c_int32, _i32p, ctypes.c_int64]
-        L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 5
+        L.sam_delta_sizes.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int64)] * 6
+        L.sam_reflatten_due.argtypes = [_vp, ctypes.c_double, ctypes.POINTER(ctypes.c_int32)]
+        L.sam_builder_flatten.argtypes = [_vp, ctypes.c_int64] + [ctypes.c_int32] * 3 + [_vp] * 8 + [ctypes.c_int64] * 3
+        L.sam_builder_flatten_result.argtypes = [_vp, ctypes.c_int64]
         L.spec_adaptive_k.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                       ctypes.POINTER(ctypes.c_int32)]
         L.spec_choose_k.argtypes = [_vp, _vp, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, ctypes.c_double,
@@ -73,8 +77,10 @@ def lib():
         L.sam_builder_release.argtypes = [_vp, ctypes.c_int64]
         L.sam_builder_destroy.argtypes = [_vp]
         L.sam_builder_destroy.restype = None
-        L.sam_delta_export.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32] + [_vp] * 6 + [ctypes.c_int64, _vp]
-        L.sam_apply_delta.argtypes = [_vp, _vp, ctypes.c_int64, _vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
+        L.sam_delta_export.argtypes = ([_vp, ctypes.c_int32, ctypes.c_int32] + [_vp] * 4 + [ctypes.c_int32, _vp, _vp,
+                                       ctypes.POINTER(ctypes.c_int64), _vp])
+        L.sam_apply_delta.argtypes = ([_vp, _vp, ctypes.c_int64, _vp, _vp, ctypes.c_int64, _vp, _vp, ctypes.c_int64] +
+                                      [_vp, _vp, _vp, _vp, ctypes.c_int64, _vp])
         L.sam_draft_delta.argtypes = ([_vp] * 8 + [ctypes.c_int64] + [_vp] * 5 + [ctypes.c_int32] * 5 +
                                       [_vp] * 4 + [_vp, ctypes.c_int64, _vp])
         L.sam_draft_step.argtypes = ([_vp] * 8 + [ctypes.c_int64, _vp, _vp, ctypes.c_int64] + [_vp] * 4 +
@@ -150,6 +156,19 @@ class SamBuilder:
         _check(lib().sam_builder_poll(self._h, int(request_id), ctypes.byref(out), ctypes.byref(pending)),
                "sam_builder_poll")
         return (Sam(out.value, owned=False) if out.value else None), pending.value
+
+    def flatten(self, request_id: int, out: "FlatSam") -> None:
+        """Queue a sam_flatten of the request's automaton into the host arrays of `out` (one automaton at state,
+        edge and corpus base 0; the arrays' sizes are the capacities).  Keep `out` alive and untouched until
+        poll() hands the automaton out again; flatten_result() then tells whether it fitted."""
+        pp = lambda a: _vp(a.ctypes.data)
+        _check(lib().sam_builder_flatten(self._h, int(request_id), 0, 0, 0, pp(out.len), pp(out.link), pp(out.row_ptr),
+                                         pp(out.edge_tok), pp(out.edge_dst), pp(out.lastpos), pp(out.corpus),
+                                         pp(out.state_rec), out.len.shape[0], out.edge_tok.shape[0], out.corpus.shape[0]),
+               "sam_builder_flatten")
+
+    def flatten_result(self, request_id: int) -> int:
+        return lib().sam_builder_flatten_result(self._h, int(request_id))
 
     def wait(self, request_id: int) -> None:
         _check(lib().sam_builder_wait(self._h, int(request_id)), "sam_builder_wait")
@@ -255,33 +274,48 @@ class SamDelta:
     rec_val: np.ndarray        # [n_rec, 4]
     lastpos_idx: np.ndarray
     lastpos_val: np.ndarray
+    ov_key: np.ndarray         # uint64, every key once
+    ov_dst: np.ndarray
     new_tokens: np.ndarray
-    n_overlay: int             # transitions in the overlay log since the last sam_flatten
+    n_overlay: int             # transitions in the log since the last sam_flatten
     flat_states: int
 
 
 def sam_delta_sizes(s: Sam):
-    v = [ctypes.c_int64() for _ in range(5)]
+    v = [ctypes.c_int64() for _ in range(6)]
     _check(lib().sam_delta_sizes(s._h, *[ctypes.byref(x) for x in v]), "sam_delta_sizes")
-    return tuple(x.value for x in v)      # n_rec, n_lastpos, n_overlay, n_new_tokens, flat_states
+    return tuple(x.value for x in v)      # n_rec, n_lastpos, n_overlay, n_overlay_new, n_new_tokens, flat_states
 
 
-def overlay_table(cap: int):
-    """An empty overlay table (host): keys ~0, capacity a power of two."""
+def sam_reflatten_due(s: Sam, max_overlay_fraction: float) -> bool:
+    due = ctypes.c_int32()
+    _check(lib().sam_reflatten_due(s._h, float(max_overlay_fraction), ctypes.byref(due)), "sam_reflatten_due")
+    return bool(due.value)
+
+
+def overlay_table(cap: int, device=None):
+    """An empty overlay table: keys ~0, capacity a power of two.  Host numpy arrays (uint64, int32), or with
+    `device` a pair of device tensors (int64 bit pattern of the keys, int32)."""
     assert cap >= 2 and cap & (cap - 1) == 0
-    return np.full(cap, np.uint64(0xFFFFFFFFFFFFFFFF), dtype=np.uint64), np.full(cap, -1, dtype=np.int32)
+    if device is None:
+        return np.full(cap, np.uint64(0xFFFFFFFFFFFFFFFF), dtype=np.uint64), np.full(cap, -1, dtype=np.int32)
+    import torch
+    return (torch.full((cap,), -1, dtype=torch.int64, device=device),
+            torch.full((cap,), -1, dtype=torch.int32, device=device))
 
 
-def sam_delta_export(s: Sam, overlay_key: np.ndarray, overlay_dst: np.ndarray, state_base: int = 0,
-                     corpus_base: int = 0) -> SamDelta:
-    n_rec, n_lp, n_ov, n_tok, flat_states = sam_delta_sizes(s)
+def sam_delta_export(s: Sam, state_base: int = 0, corpus_base: int = 0, overlay_all: bool = False) -> SamDelta:
+    n_rec, n_lp, n_ov, n_ov_new, n_tok, flat_states = sam_delta_sizes(s)
+    n_list = n_ov if overlay_all else n_ov_new
     d = SamDelta(np.zeros(n_rec, np.int32), np.zeros((n_rec, 4), np.int32), np.zeros(n_lp, np.int32),
-                 np.zeros(n_lp, np.int32), np.zeros(n_tok, np.int32), n_ov, flat_states)
-    assert overlay_key.dtype == np.uint64 and overlay_dst.dtype == np.int32 and overlay_key.flags.c_contiguous
+                 np.zeros(n_lp, np.int32), np.zeros(n_list, np.uint64), np.zeros(n_list, np.int32),
+                 np.zeros(n_tok, np.int32), n_ov, flat_states)
     ptr = lambda a: _vp(a.ctypes.data) if a.size else _vp(0)
+    nw = ctypes.c_int64()
     _check(lib().sam_delta_export(s._h, int(state_base), int(corpus_base), ptr(d.rec_idx), ptr(d.rec_val),
-                                  ptr(d.lastpos_idx), ptr(d.lastpos_val), ptr(overlay_key), ptr(overlay_dst),
-                                  overlay_key.shape[0], ptr(d.new_tokens)), "sam_delta_export")
+                                  ptr(d.lastpos_idx), ptr(d.lastpos_val), 1 if overlay_all else 0, ptr(d.ov_key),
+                                  ptr(d.ov_dst), ctypes.byref(nw), ptr(d.new_tokens)), "sam_delta_export")
+    d.ov_key, d.ov_dst = d.ov_key[:nw.value], d.ov_dst[:nw.value]
     return d
 
 
@@ -349,16 +383,26 @@ def sam_draft_merged(flat: FlatSam, root, corpus_end, weight, recent, recent_len
     return tuple(out)
 
 
-def sam_apply_delta(delta: SamDelta, state_rec, lastpos) -> None:
-    """Scatter an exported delta into the device arrays state_rec [4*cap] and lastpos [cap]."""
+def sam_apply_delta(delta: SamDelta, state_rec, lastpos, overlay_key=None, overlay_dst=None) -> None:
+    """Scatter an exported delta into the device arrays state_rec [4*cap] and lastpos [cap] and insert its
+    transitions into the device overlay table (overlay_key int64/uint64 bit patterns, overlay_dst int32).
+    The delta's arrays may be host numpy arrays (uploaded here) or device tensors."""
     import torch
     dev = state_rec.device
     ri, rv = _dev_i32(delta.rec_idx, dev), _dev_i32(delta.rec_val.reshape(-1), dev)
     li, lv = _dev_i32(delta.lastpos_idx, dev), _dev_i32(delta.lastpos_val, dev)
-    z = lambda t: _dp(t) if t.numel() else _vp(0)
-    _check(lib().sam_apply_delta(z(ri), z(rv), ri.numel(), z(li), z(lv), li.numel(), _dp(state_rec), _dp(lastpos),
-                                 _stream_ptr()), "sam_apply_delta")
-    torch.cuda.current_stream().synchronize()      # the staging tensors above die with this frame
+    ok = delta.ov_key
+    if not isinstance(ok, torch.Tensor):
+        ok = torch.as_tensor(np.ascontiguousarray(ok).view(np.int64)).to(dev)
+    od = _dev_i32(delta.ov_dst, dev)
+    if ok.numel() and overlay_key is None:
+        raise ValueError("the delta has transitions: pass the device overlay table")
+    z = lambda t: _dp(t) if t is not None and t.numel() else _vp(0)
+    # (the staging tensors are allocated, written and read on the current stream, and the caching allocator
+    # hands their memory out again in stream order, so nothing has to be awaited here)
+    _check(lib().sam_apply_delta(z(ri), z(rv), ri.numel(), z(li), z(lv), li.numel(), z(ok), z(od), ok.numel(),
+                                 _dp(state_rec), _dp(lastpos), z(overlay_key), z(overlay_dst),
+                                 overlay_key.numel() if overlay_key is not None else 0, _stream_ptr()), "sam_apply_delta")
 
 
 def sam_draft_delta(flat: FlatSam, overlay_key, overlay_dst, rows_end, root, corpus_end, recent, recent_len, k: int,

@@ -1,10 +1,12 @@
-// Asynchronous automaton construction (paper Sec. 5.4.2, "Asynchronous SAM construction"; Alg. 4 step 2).
+// Asynchronous automaton construction (paper Sec. 5.4.2, asynchronous SAM construction; Alg. 4 step 2).
 //
 // Building the automaton of a long prompt would sit on the time to first token, so it is handed to a
 // child thread: a request's prompt and, later, its generated tokens are put into a waiting queue and
 // the call returns at once; the child thread works through the queue; while a request still has
-// entries waiting, its automaton is "not yet available" and the caller decodes that request without
+// entries waiting, its automaton is not available yet and the caller decodes that request without
 // drafts.  One builder owns one child thread and the automata of all the requests submitted to it.
+// Flattening a grown automaton again (when its overlay of new transitions is no longer small) goes
+// through the same queue, so it too stays off the decoding thread and is ordered with the appends.
 #include <condition_variable>
 #include <cstdint>
 #include <deque>
@@ -24,13 +26,22 @@ struct Request {
     int64_t pending_entries = 0;     // queue entries (and the one being processed) not yet in the automaton
     int64_t pending_tokens = 0;
     int error = AGENTSAM_OK;         // first error of a background append (e.g. a negative token id)
+    int flatten_rc = AGENTSAM_ERR_ARG;   // result of the last background flatten (ERR_ARG: none yet)
     bool released = false;           // forget it as soon as nothing is pending
+};
+
+struct FlattenJob {                  // where a background flatten writes (the caller's host arrays) and how much fits
+    int32_t state_base, edge_base, corpus_base;
+    int32_t *len, *link, *row_ptr, *edge_tok, *edge_dst, *lastpos, *corpus, *state_rec;
+    int64_t cap_states, cap_edges, cap_tokens;
 };
 
 struct Entry {
     int64_t id;
     std::vector<int32_t> tokens;
     int32_t sep;
+    bool flatten = false;
+    FlattenJob job{};
 };
 
 }  // namespace
@@ -56,13 +67,25 @@ struct sam_builder {
             lk.unlock();
             // the automaton of a request with pending entries is touched by this thread only
             int rc = AGENTSAM_OK;
-            if (!skip) {
+            if (!skip && e.flatten) {
+                const FlattenJob &j = e.job;
+                int64_t ns = 0, ne = 0, nt = 0;
+                if (!target) rc = AGENTSAM_ERR_ARG;          // nothing was ever submitted for this request
+                else {
+                    sam_flat_sizes(target, &ns, &ne, &nt);
+                    if (ns > j.cap_states || ne > j.cap_edges || nt > j.cap_tokens) rc = AGENTSAM_ERR_WORKSPACE;
+                    else rc = sam_flatten(target, j.state_base, j.edge_base, j.corpus_base, j.len, j.link, j.row_ptr,
+                                          j.edge_tok, j.edge_dst, j.lastpos, j.corpus, j.state_rec);
+                }
+            } else if (!skip) {
                 if (!target) rc = sam_build(e.tokens.data(), (int64_t)e.tokens.size(), e.sep, &target);
                 else rc = sam_append(target, e.tokens.data(), (int64_t)e.tokens.size());
             }
             lk.lock();
             Request &r2 = req[e.id];
-            if (!skip) {
+            if (!skip && e.flatten) {
+                r2.flatten_rc = rc;                          // (a flatten that does not fit leaves the automaton usable)
+            } else if (!skip) {
                 if (rc != AGENTSAM_OK) r2.error = rc;
                 else r2.sam = target;
             }
@@ -110,6 +133,36 @@ int sam_builder_submit(sam_builder_t *b, int64_t request_id, const int32_t *toke
     }
     b->cv_work.notify_one();
     return AGENTSAM_OK;
+}
+
+int sam_builder_flatten(sam_builder_t *b, int64_t request_id, int32_t state_base, int32_t edge_base, int32_t corpus_base,
+                        int32_t *len, int32_t *link, int32_t *row_ptr, int32_t *edge_tok, int32_t *edge_dst,
+                        int32_t *lastpos, int32_t *corpus, int32_t *state_rec, int64_t cap_states, int64_t cap_edges,
+                        int64_t cap_tokens) {
+    if (!b || !len || !link || !row_ptr || !edge_tok || !edge_dst || !lastpos || !corpus || !state_rec) return AGENTSAM_ERR_NULL;
+    if (cap_states < 1 || cap_edges < 0 || cap_tokens < 0 || state_base < 0 || edge_base < 0 || corpus_base < 0) return AGENTSAM_ERR_ARG;
+    try {
+        Entry e{request_id, {}, 0, true,
+                FlattenJob{state_base, edge_base, corpus_base, len, link, row_ptr, edge_tok, edge_dst, lastpos, corpus,
+                           state_rec, cap_states, cap_edges, cap_tokens}};
+        std::lock_guard<std::mutex> lk(b->mu);
+        auto it = b->req.find(request_id);
+        if (it == b->req.end() || it->second.released) return AGENTSAM_ERR_ARG;
+        it->second.pending_entries += 1;
+        b->queue.push_back(std::move(e));
+    } catch (const std::bad_alloc &) {
+        return AGENTSAM_ERR_NOMEM;
+    }
+    b->cv_work.notify_one();
+    return AGENTSAM_OK;
+}
+
+int sam_builder_flatten_result(sam_builder_t *b, int64_t request_id) {
+    if (!b) return AGENTSAM_ERR_NULL;
+    std::lock_guard<std::mutex> lk(b->mu);
+    auto it = b->req.find(request_id);
+    if (it == b->req.end() || it->second.released) return AGENTSAM_ERR_ARG;
+    return it->second.flatten_rc;
 }
 
 int sam_builder_poll(sam_builder_t *b, int64_t request_id, sam_t **out, int64_t *pending_tokens) {

@@ -1,7 +1,7 @@
 // sam_draft: batched suffix-automaton draft lookup, one wavefront per session.
 //
-// Paper Sec. 5.4.2 / Alg. 4 (FollowTransitions): given the current verified suffix, follow
-// the automaton's transitions to retrieve a matching continuation of a specified length.
+// Paper Sec. 5.4.2 / Alg. 4 (FollowTransitions): the drafts are a continuation, of a given
+// length, of an earlier occurrence of the text verified so far, found by walking the automaton.
 //
 // The walk itself is a chain of dependent loads (state -> transition row -> next state), so a
 // session cannot be made faster by adding lanes; the 64 lanes are used where there is width:
@@ -9,6 +9,8 @@
 // transition row is searched 64 entries at a time (64-ary narrowing for the few very wide
 // states such as the root), and the continuation is read and cut with one load and a ballot.
 // Throughput comes from the sessions running side by side on different compute units.
+#include <algorithm>
+
 #include "common.h"
 #include "sam_hash.h"
 
@@ -356,27 +358,54 @@ extern "C" int sam_draft_step(const int32_t *row_ptr, const int32_t *edge_tok, c
 }
 
 namespace {
+// One thread per exported item: walk records and end positions are scattered; a new or redirected transition
+// is put into the overlay table (linear probing; the slot of its key is claimed with a compare-and-swap,
+// or found if an earlier delta put the key there, and the destination is overwritten).  The export hands
+// out every key once, so two threads never write one slot.  The probe count is bounded by the table size.
 __global__ __launch_bounds__(256) void sam_apply_delta_kernel(const int32_t *__restrict__ rec_idx, const int4 *__restrict__ rec_val,
                                                               int64_t n_rec, const int32_t *__restrict__ lp_idx,
                                                               const int32_t *__restrict__ lp_val, int64_t n_lp,
-                                                              int4 *__restrict__ state_rec, int32_t *__restrict__ lastpos) {
+                                                              const unsigned long long *__restrict__ ov_key,
+                                                              const int32_t *__restrict__ ov_dst, int64_t n_ov,
+                                                              int4 *__restrict__ state_rec, int32_t *__restrict__ lastpos,
+                                                              unsigned long long *__restrict__ table_key,
+                                                              int32_t *__restrict__ table_dst, unsigned table_mask) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n_rec) state_rec[rec_idx[i]] = rec_val[i];
     if (i < n_lp) lastpos[lp_idx[i]] = lp_val[i];
+    if (i < n_ov) {
+        const unsigned long long k = ov_key[i];
+        unsigned j = (unsigned)agentsam_hash64(k) & table_mask;
+        for (unsigned probes = 0; probes <= table_mask; ++probes) {
+            const unsigned long long was = atomicCAS(table_key + j, (unsigned long long)AGENTSAM_HASH_EMPTY, k);
+            if (was == AGENTSAM_HASH_EMPTY || was == k) {
+                table_dst[j] = ov_dst[i];
+                break;
+            }
+            j = (j + 1) & table_mask;
+        }
+    }
 }
 }  // namespace
 
 extern "C" int sam_apply_delta(const int32_t *rec_idx, const int32_t *rec_val, int64_t n_rec,
                                const int32_t *lastpos_idx, const int32_t *lastpos_val, int64_t n_lastpos,
-                               int32_t *state_rec, int32_t *lastpos, void *stream) {
-    if (n_rec < 0 || n_lastpos < 0) return AGENTSAM_ERR_ARG;
-    if ((n_rec > 0 && (!rec_idx || !rec_val || !state_rec)) || (n_lastpos > 0 && (!lastpos_idx || !lastpos_val || !lastpos)))
+                               const uint64_t *ov_key, const int32_t *ov_dst, int64_t n_ov,
+                               int32_t *state_rec, int32_t *lastpos,
+                               uint64_t *overlay_key, int32_t *overlay_dst, int64_t overlay_cap, void *stream) {
+    if (n_rec < 0 || n_lastpos < 0 || n_ov < 0) return AGENTSAM_ERR_ARG;
+    if ((n_rec > 0 && (!rec_idx || !rec_val || !state_rec)) || (n_lastpos > 0 && (!lastpos_idx || !lastpos_val || !lastpos)) ||
+        (n_ov > 0 && (!ov_key || !ov_dst || !overlay_key || !overlay_dst)))
         return AGENTSAM_ERR_NULL;
-    const int64_t n = n_rec > n_lastpos ? n_rec : n_lastpos;
+    if (n_ov > 0 && (overlay_cap < 2 || (overlay_cap & (overlay_cap - 1)) != 0 || overlay_cap > (1ll << 31) || 2 * n_ov > overlay_cap))
+        return AGENTSAM_ERR_ARG;
+    const int64_t n = std::max(n_rec, std::max(n_lastpos, n_ov));
     if (n == 0) return AGENTSAM_OK;
     if ((n + 255) / 256 > 0x7fffffffll) return AGENTSAM_ERR_ARG;
     AGENTSAM_LAUNCH(sam_apply_delta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), (hipStream_t)stream,
-                    rec_idx, (const int4 *)rec_val, n_rec, lastpos_idx, lastpos_val, n_lastpos, (int4 *)state_rec, lastpos);
+                    rec_idx, (const int4 *)rec_val, n_rec, lastpos_idx, lastpos_val, n_lastpos,
+                    (const unsigned long long *)ov_key, ov_dst, n_ov, (int4 *)state_rec, lastpos,
+                    (unsigned long long *)overlay_key, overlay_dst, (unsigned)(n_ov > 0 ? overlay_cap - 1 : 0));
     return AGENTSAM_OK;
 }
 

@@ -1,10 +1,9 @@
 // Host-side online suffix automaton over a token memory, and its flattening to the
 // arrays sam_draft reads on the device.
 //
-// Paper Sec. 5.4.2: the request context is indexed in a suffix automaton that is built
-// incrementally token by token (linear in the context length) and extended with verified
-// tokens as the context grows; Alg. 4: BuildSAM / "incrementally extend S with streamed
-// tokens".  The construction is the textbook online algorithm (new state, walk suffix
+// Paper Sec. 5.4.2: a request's context is indexed in a suffix automaton that grows one token at
+// a time (linear in the context length), the verified tokens of every step included; Alg. 4,
+// BuildSAM and step 2.  The construction is the textbook online algorithm (new state, walk suffix
 // links adding transitions, clone on a length mismatch).
 //
 // Storage is sized for memories of millions of tokens over vocabularies of ~150k ids:
@@ -31,28 +30,51 @@ struct sam {
     uint64_t h_used = 0;
     std::vector<int32_t> corpus;
 
-    // Incremental maintenance (Sec. 5.4.2: verified tokens are inserted as the context grows; Alg. 4,
-    // "incrementally extend S with streamed tokens").  After a full sam_flatten the automaton keeps
-    // track of what the device copy is missing: states whose walk record or last eligible end position
-    // changed, transitions added or redirected (they go into an overlay hash table that the draft
-    // lookup consults before the flattened transition rows), and the new tokens.
+    // Incremental maintenance (Sec. 5.4.2: what a step verifies goes into the automaton as the context
+    // grows; Alg. 4 step 2).  After a full sam_flatten the automaton keeps track of what the device copy
+    // is missing: states whose walk record or last eligible end position changed, transitions added or
+    // redirected (they go into an overlay hash table that the draft lookup consults before the flattened
+    // transition rows), and the new tokens.
     mutable bool track = false;
     mutable int32_t flat_states = 0;                 // states of the last full flatten: rows exist below this id
+    mutable int64_t flat_edges = 0;                  // transitions of the last full flatten
     mutable int64_t exported_tokens = 0;             // memory tokens the device copy already has
-    mutable std::vector<int32_t> lp;                 // last eligible end position per state, kept online
+    mutable std::vector<int32_t> lp;                 // last eligible end position per state, as of the last propagation
     mutable std::vector<uint8_t> rec_dirty, lp_dirty;
     mutable std::vector<int32_t> rec_list, lp_list;
-    mutable std::vector<int32_t> ov_state, ov_tok, ov_dst;
+    mutable std::vector<int32_t> ov_state, ov_tok, ov_dst;   // every transition added or redirected since the flatten, in order
+    mutable size_t ov_exported = 0;                  // log entries the last export has handed out
+    // End positions that became eligible since the last propagation: (state of the prefix that ends there,
+    // position), positions increasing.  Appending only logs the pair; propagate_lastpos() pushes them up
+    // the suffix links, once per export instead of once per token.
+    mutable std::vector<int32_t> pend_state, pend_pos;
 
     void mark_rec(int32_t v) {
         if (!track || rec_dirty[(size_t)v]) return;
         rec_dirty[(size_t)v] = 1;
         rec_list.push_back(v);
     }
-    void mark_lp(int32_t v) {
+    void mark_lp(int32_t v) const {
         if (!track || lp_dirty[(size_t)v]) return;
         lp_dirty[(size_t)v] = 1;
         lp_list.push_back(v);
+    }
+    // Position e is an end position of exactly the states on the suffix-link path from the state of the
+    // prefix T[0..e] to the root (in the automaton as it is NOW: states split since e arrived have their
+    // clones on that path), so its lastpos candidates are that path.  Newest position first: a walk stops
+    // at the first state that already holds a later position, because end-position sets grow towards the
+    // root and every state above holds at least as late a one.  A call therefore touches each state at
+    // most once per distinct chain, however many tokens were appended since the last call.
+    void propagate_lastpos() const {
+        for (size_t i = pend_pos.size(); i-- > 0;) {
+            const int32_t e = pend_pos[i];
+            for (int32_t v = pend_state[i]; v != -1 && lp[(size_t)v] < e; v = link[(size_t)v]) {
+                lp[(size_t)v] = e;
+                mark_lp(v);
+            }
+        }
+        pend_state.clear();
+        pend_pos.clear();
     }
 
     static constexpr uint64_t kEmpty = ~0ull;
@@ -126,7 +148,9 @@ struct sam {
             } else {
                 const int32_t cl = new_state(len[p] + 1, link[q], -1);
                 for (int32_t x = head[q]; x != -1; x = e_next[x]) add_edge(cl, e_tok[x], e_dst[x]);
-                if (track) lp[(size_t)cl] = lp[(size_t)q];   // the clone ends wherever q ended so far
+                // the clone ends wherever q ended so far (positions still waiting in the log reach it through
+                // the suffix links when they are propagated: q's link is the clone from now on)
+                if (track) lp[(size_t)cl] = lp[(size_t)q];
                 while (p != -1) {
                     const int32_t ee = find(p, c);
                     if (ee < 0 || e_dst[ee] != q) break;
@@ -144,13 +168,11 @@ struct sam {
         }
         last = cur;
         // The previous position now has a continuation (unless the new token is the separator): it is
-        // the most recent eligible end position of every string that ends there, i.e. of the state of
-        // the previous prefix and of all its suffix-link ancestors.
+        // the most recent eligible end position of every string that ends there.  Logged here in O(1),
+        // pushed up the suffix links by propagate_lastpos().
         if (track && pos >= 1 && c != sep) {
-            for (int32_t v = prev_last; v != -1; v = link[v]) {
-                lp[(size_t)v] = pos - 1;
-                mark_lp(v);
-            }
+            pend_state.push_back(prev_last);
+            pend_pos.push_back(pos - 1);
         }
     }
 };
@@ -269,11 +291,14 @@ int sam_flatten(const sam_t *s, int32_t state_base, int32_t edge_base, int32_t c
         // from here on the automaton records what a device copy of these arrays will be missing
         s->track = true;
         s->flat_states = (int32_t)ns;
+        s->flat_edges = ne;
         s->exported_tokens = nt;
         s->lp.swap(lp);
         s->rec_dirty.assign((size_t)ns, 0); s->lp_dirty.assign((size_t)ns, 0);
         s->rec_list.clear(); s->lp_list.clear();
         s->ov_state.clear(); s->ov_tok.clear(); s->ov_dst.clear();
+        s->ov_exported = 0;
+        s->pend_state.clear(); s->pend_pos.clear();
     } catch (const std::bad_alloc &) {
         return AGENTSAM_ERR_NOMEM;
     }
@@ -335,42 +360,74 @@ int sam_wide_table(const sam_t *s, int32_t state_base, int32_t *table, int64_t s
     return AGENTSAM_OK;
 }
 
-int sam_delta_sizes(const sam_t *s, int64_t *n_rec, int64_t *n_lastpos, int64_t *n_overlay,
+int sam_delta_sizes(const sam_t *s, int64_t *n_rec, int64_t *n_lastpos, int64_t *n_overlay, int64_t *n_overlay_new,
                     int64_t *n_new_tokens, int64_t *flat_states) {
     if (!s) return AGENTSAM_ERR_NULL;
     if (!s->track) return AGENTSAM_ERR_ARG;                  // nothing to be relative to: flatten first
+    try {
+        s->propagate_lastpos();                              // the count of changed end positions is known after this
+    } catch (const std::bad_alloc &) {
+        return AGENTSAM_ERR_NOMEM;
+    }
     if (n_rec) *n_rec = (int64_t)s->rec_list.size();
     if (n_lastpos) *n_lastpos = (int64_t)s->lp_list.size();
     if (n_overlay) *n_overlay = (int64_t)s->ov_state.size();
+    if (n_overlay_new) *n_overlay_new = (int64_t)(s->ov_state.size() - s->ov_exported);
     if (n_new_tokens) *n_new_tokens = (int64_t)s->corpus.size() - s->exported_tokens;
     if (flat_states) *flat_states = s->flat_states;
     return AGENTSAM_OK;
 }
 
+int sam_reflatten_due(const sam_t *s, double max_overlay_fraction, int32_t *due) {
+    if (!s || !due) return AGENTSAM_ERR_NULL;
+    if (!(max_overlay_fraction >= 0.0)) return AGENTSAM_ERR_ARG;
+    *due = (!s->track || (double)s->ov_state.size() > max_overlay_fraction * (double)std::max<int64_t>(1, s->flat_edges)) ? 1 : 0;
+    return AGENTSAM_OK;
+}
+
 int sam_delta_export(sam_t *s, int32_t state_base, int32_t corpus_base,
                      int32_t *rec_idx, int32_t *rec_val, int32_t *lastpos_idx, int32_t *lastpos_val,
-                     uint64_t *overlay_key, int32_t *overlay_dst, int64_t overlay_cap, int32_t *new_tokens) {
-    if (!s) return AGENTSAM_ERR_NULL;
+                     int32_t overlay_all, uint64_t *ov_key, int32_t *ov_dst, int64_t *n_ov_written, int32_t *new_tokens) {
+    if (!s || !n_ov_written) return AGENTSAM_ERR_NULL;
     if (!s->track) return AGENTSAM_ERR_ARG;
-    const size_t nr = s->rec_list.size(), nl = s->lp_list.size(), no = s->ov_state.size();
+    try {
+        s->propagate_lastpos();
+    } catch (const std::bad_alloc &) {
+        return AGENTSAM_ERR_NOMEM;
+    }
+    const size_t nr = s->rec_list.size(), nl = s->lp_list.size();
+    const size_t ov0 = overlay_all ? 0 : s->ov_exported, ov1 = s->ov_state.size();
     const int64_t ntok = (int64_t)s->corpus.size() - s->exported_tokens;
     if ((nr > 0 && (!rec_idx || !rec_val)) || (nl > 0 && (!lastpos_idx || !lastpos_val)) ||
-        (no > 0 && (!overlay_key || !overlay_dst)) || (ntok > 0 && !new_tokens))
+        (ov1 > ov0 && (!ov_key || !ov_dst)) || (ntok > 0 && !new_tokens))
         return AGENTSAM_ERR_NULL;
     if (state_base < 0 || corpus_base < 0) return AGENTSAM_ERR_ARG;
     if ((int64_t)state_base + (int64_t)s->len.size() > INT32_MAX ||
         (int64_t)corpus_base + (int64_t)s->corpus.size() > INT32_MAX) return AGENTSAM_ERR_ARG;
-    if (no > 0 && (overlay_cap < 2 || (overlay_cap & (overlay_cap - 1)) != 0 || (int64_t)no * 2 > overlay_cap))
-        return AGENTSAM_ERR_ARG;                             // power of two, at most half full
-    // transitions: later entries of the log override earlier ones with the same (state, token)
-    const uint64_t mask = (uint64_t)overlay_cap - 1;
-    for (size_t i = 0; i < no; ++i) {
-        const uint64_t key = ((uint64_t)(uint32_t)(s->ov_state[i] + state_base) << 32) | (uint32_t)s->ov_tok[i];
-        uint64_t j = agentsam_hash64(key) & mask;
-        while (overlay_key[j] != AGENTSAM_HASH_EMPTY && overlay_key[j] != key) j = (j + 1) & mask;
-        overlay_key[j] = key;
-        overlay_dst[j] = s->ov_dst[i] + state_base;
+    // transitions: a later entry of the log overrides an earlier one with the same (state, token), so only
+    // the last entry per key is handed out (newest first through a scratch table; the order of the list
+    // then no longer matters to whoever inserts it)
+    int64_t nw = 0;
+    if (ov1 > ov0) {
+        try {
+            uint64_t cap = 2;
+            while (cap < 2 * (uint64_t)(ov1 - ov0)) cap *= 2;
+            std::vector<uint64_t> seen((size_t)cap, AGENTSAM_HASH_EMPTY);
+            for (size_t i = ov1; i-- > ov0;) {
+                const uint64_t key = ((uint64_t)(uint32_t)(s->ov_state[i] + state_base) << 32) | (uint32_t)s->ov_tok[i];
+                uint64_t j = agentsam_hash64(key) & (cap - 1);
+                while (seen[(size_t)j] != AGENTSAM_HASH_EMPTY && seen[(size_t)j] != key) j = (j + 1) & (cap - 1);
+                if (seen[(size_t)j] == key) continue;
+                seen[(size_t)j] = key;
+                ov_key[nw] = key;
+                ov_dst[nw] = s->ov_dst[i] + state_base;
+                ++nw;
+            }
+        } catch (const std::bad_alloc &) {
+            return AGENTSAM_ERR_NOMEM;                       // nothing has been forgotten yet
+        }
     }
+    *n_ov_written = nw;
     for (size_t i = 0; i < nr; ++i) {
         const int32_t v = s->rec_list[i];
         const int32_t h = s->head[(size_t)v];
@@ -397,6 +454,7 @@ int sam_delta_export(sam_t *s, int32_t state_base, int32_t corpus_base,
     if (ntok > 0)
         std::memcpy(new_tokens, s->corpus.data() + s->exported_tokens, (size_t)ntok * sizeof(int32_t));
     s->rec_list.clear(); s->lp_list.clear();
+    s->ov_exported = ov1;
     s->exported_tokens = (int64_t)s->corpus.size();
     return AGENTSAM_OK;
 }

@@ -64,15 +64,18 @@ static void automaton_and_delta(int vocab) {
         const size_t n = 1 + rnd() % 300;
         REQUIRE(sam_append(s, text.data() + at, (int64_t)n) == 0);
         at += n;
-        int64_t n_rec, n_lp, n_ov, n_new, flat_states;
-        REQUIRE(sam_delta_sizes(s, &n_rec, &n_lp, &n_ov, &n_new, &flat_states) == 0);
+        int64_t n_rec, n_lp, n_ov, n_ov_new, n_new, flat_states, n_written = -1;
+        REQUIRE(sam_delta_sizes(s, &n_rec, &n_lp, &n_ov, &n_ov_new, &n_new, &flat_states) == 0);
         REQUIRE(n_new == (int64_t)n);
-        int64_t cap = 2;
-        while (cap < 2 * n_ov) cap *= 2;
-        std::vector<int32_t> rec_idx(n_rec), rec_val(4 * n_rec), lp_idx(n_lp), lp_val(n_lp), ov_dst(cap, -1), new_tok(n_new);
-        std::vector<uint64_t> ov_key(cap, ~0ull);
-        REQUIRE(sam_delta_export(s, 7, 13, rec_idx.data(), rec_val.data(), lp_idx.data(), lp_val.data(), ov_key.data(),
-                                 ov_dst.data(), cap, new_tok.data()) == 0);
+        const bool all = round % 3 == 2;                      // now and then everything since the flatten
+        const int64_t n_list = all ? n_ov : n_ov_new;         // exactly-sized arrays: an overrun is caught
+        std::vector<int32_t> rec_idx(n_rec), rec_val(4 * n_rec), lp_idx(n_lp), lp_val(n_lp), ov_dst(n_list), new_tok(n_new);
+        std::vector<uint64_t> ov_key(n_list);
+        REQUIRE(sam_delta_export(s, 7, 13, rec_idx.data(), rec_val.data(), lp_idx.data(), lp_val.data(), all ? 1 : 0,
+                                 ov_key.data(), ov_dst.data(), &n_written, new_tok.data()) == 0);
+        REQUIRE(n_written >= 0 && n_written <= n_list);
+        int32_t due = -1;
+        REQUIRE(sam_reflatten_due(s, 0.05, &due) == 0 && (due == 0 || due == 1));
         for (int64_t i = 0; i < n_new; ++i) REQUIRE(new_tok[i] == text[at - n + i]);
         if (round == 6) flatten(s);                           // a re-flatten in between starts a new log
     }

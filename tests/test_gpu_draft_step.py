@@ -249,3 +249,81 @@ def test_draft_step_full_size_memory(i):
         L, od, ond, oml, ome = draft_step_oracle(T[b], np.asarray(ctxs[b], np.int32), L_prev[b], int(n2[b]), cfg.k, cfg.sep, 1)
         assert (int(cl[b]), int(ml[b]), int(nd[b])) == (L, oml, ond), b
         assert (int(me[b]) - int(cbeg[b]) if me[b] >= 0 else -1) == ome and list(d[b, :ond]) == list(od[:ond])
+
+
+def test_carried_state_across_a_flatten_on_the_child_thread():
+    """The whole maintenance cycle: the memory grows through the builder's queue, the device copy follows by
+    deltas, and when the log of transitions exceeds the stated fraction the automaton is flattened again ON THE
+    CHILD THREAD into new arrays, which are uploaded and swapped in (with an empty overlay) between two steps.
+    The (state, length) pairs the sessions carry stay valid across the swap: every step equals the oracle."""
+    from paper_2512_18337_amd import binding
+    import ctypes
+    cfg = W.scaled(W.baseline_config(2), B=16, sam_sessions=4, sam_session_len=1500, vocab=1500, m=32, k=8)
+    rng = np.random.default_rng(909)
+    T = list(W.token_memory(cfg))
+    bld = A.SamBuilder()
+    bld.submit(1, np.asarray(T, np.int32), cfg.sep)
+    bld.wait(1)
+    sam, _ = bld.poll(1)
+    grow = 4000
+    flat = A.sam_flatten([sam], grow_tokens=grow)
+    fd = flat.to(DEV)
+    mems, owner, mem_len = [T], [0] * cfg.B, [len(T)]
+    root = np.zeros(cfg.B, np.int32)
+    cur_state = torch.full((cfg.B,), -1, dtype=torch.int32, device=DEV)
+    cur_len = torch.zeros((cfg.B,), dtype=torch.int32, device=DEV)
+    ctxs = [[] for _ in range(cfg.B)]
+    L_prev = [0] * cfg.B
+    swaps = 0
+    for step in range(14):
+        add = []
+        for b in range(cfg.B):
+            if ctxs[b] and rng.random() < 0.6:
+                add += ctxs[b][-int(rng.integers(2, 12)):] + [int(rng.integers(0, cfg.vocab))]
+        add += [int(x) for x in rng.integers(0, cfg.vocab, int(rng.integers(1, 6)))]
+        if step % 5 == 3:
+            add.append(cfg.sep)
+        bld.submit(1, np.asarray(add, np.int32), cfg.sep)
+        T += add
+        bld.wait(1)
+        sam, _ = bld.poll(1)
+        if A.sam_reflatten_due(sam, 0.04):
+            # flatten again off this thread, into arrays with room to grow, then swap the device copy
+            ns, ne, nt = A.sam_flat_sizes(sam)
+            fill = lambda n: np.full(n, -1, np.int32)
+            cap_s, cap_t = ns + 2 * grow, nt + grow
+            out = A.FlatSam(fill(cap_s), fill(cap_s), np.zeros(cap_s + 1, np.int32), fill(max(ne, 1)), fill(max(ne, 1)),
+                            fill(cap_s), fill(cap_t), fill(4 * cap_s), np.zeros(1, np.int32), np.zeros(1, np.int32),
+                            np.array([nt], np.int32), np.array([ns], np.int32))
+            bld.flatten(1, out)
+            bld.wait(1)
+            assert bld.flatten_result(1) == 0
+            sam, _ = bld.poll(1)
+            out.row_ptr[ns:] = ne                             # states without a row yet
+            slots = ctypes.c_int64()
+            assert binding.lib().sam_wide_slots(sam._h, ctypes.byref(slots)) == 0
+            out.wide_table = np.full(4 * slots.value, -1, np.int32)
+            assert binding.lib().sam_wide_table(sam._h, 0, out.wide_table.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                                slots.value) == 0
+            flat, fd = out, out.to(DEV)                       # the swap: new arrays, no overlay yet
+            mem_len = [nt]
+            swaps += 1
+            assert A.sam_delta_sizes(sam)[:5] == (0, 0, 0, 0, 0)
+        keys, dsts = _sync([sam], fd, flat, mem_len)
+        rows_end = np.full(cfg.B, int(flat.rows_end[0]), np.int32)
+        cend = np.full(cfg.B, mem_len[0], np.int32)
+        lo, hi = ((40, 80) if step == 0 else (0, 9))
+        new = [[t for t in _next_tokens(rng, T, ctxs[b], cfg.vocab, lo, hi) if t != cfg.sep] for b in range(cfg.B)]
+        max_new = max(1, max(len(x) for x in new))
+        tok = np.full((cfg.B, max_new), -7, np.int32)
+        n_new = np.array([len(x) for x in new], np.int32)
+        for b in range(cfg.B):
+            tok[b, :len(new[b])] = new[b]
+            ctxs[b] += new[b]
+        print(f"draft step {step}: flattened again {swaps} times, overlay capacity {keys.numel()}", flush=True)
+        got = A.sam_draft_step(fd, root, cend, tok, n_new, cur_state, cur_len, cfg.k, cfg.sep,
+                               overlay_key=keys, overlay_dst=dsts, rows_end=rows_end)
+        torch.cuda.synchronize()
+        _check_step(step, mems, owner, ctxs, L_prev, n_new, got, cur_len, flat.corpus_begin, cfg.k, cfg.sep)
+    assert swaps >= 2
+    bld.close()

@@ -14,22 +14,27 @@ DEV = "cuda:0"
 
 
 def _sync(sams, fd, flat, mem_len):
-    """Export every automaton's delta into one overlay table and bring the device copy up to date."""
+    """Bring the device copy up to date: every automaton's delta is uploaded and applied with one launch, its new
+    transitions going into the one device overlay table (kept on `fd` between calls; re-created larger, and
+    refilled with everything since the flatten, when it would get more than half full)."""
     n_ov = sum(A.sam_delta_sizes(s)[2] for s in sams)
-    cap = 2
-    while cap < 2 * n_ov:
-        cap *= 2
-    keys, dsts = A.overlay_table(cap)
+    table = getattr(fd, "overlay", None)
+    grow = table is None or 2 * n_ov > table[0].numel()
+    if grow:
+        cap = 2
+        while cap < 2 * n_ov:
+            cap *= 2
+        table = fd.overlay = A.overlay_table(cap, device=DEV)
     for i, s in enumerate(sams):
-        d = A.sam_delta_export(s, keys, dsts, int(flat.roots[i]), int(flat.corpus_begin[i]))
+        d = A.sam_delta_export(s, int(flat.roots[i]), int(flat.corpus_begin[i]), overlay_all=grow)
         assert int(flat.roots[i]) + d.flat_states == int(flat.rows_end[i])
-        A.sam_apply_delta(d, fd.state_rec, fd.lastpos)
+        A.sam_apply_delta(d, fd.state_rec, fd.lastpos, table[0], table[1])
         n = d.new_tokens.shape[0]
         if n:
             at = int(flat.corpus_begin[i]) + mem_len[i]
             fd.corpus[at:at + n] = torch.as_tensor(d.new_tokens, device=DEV)
             mem_len[i] += n
-    return torch.as_tensor(keys.view(np.int64), device=DEV), torch.as_tensor(dsts, device=DEV)
+    return table
 
 
 def _windows(rng, mems, owner, m, vocab):

@@ -77,6 +77,48 @@ def test_maintained_copy_fed_by_the_builder():
     b.submit(1, [4, 5], 9)
     b.wait(1)
     sam, _ = b.poll(1)
-    n_rec, n_lp, n_ov, n_tok, flat_states = A.sam_delta_sizes(sam)
-    assert n_tok == 2 and flat_states == 4 and n_ov > 0
+    n_rec, n_lp, n_ov, n_ov_new, n_tok, flat_states = A.sam_delta_sizes(sam)
+    assert n_tok == 2 and flat_states == 4 and n_ov > 0 and n_ov_new == n_ov
+    b.close()
+
+
+def test_flatten_again_on_the_child_thread():
+    """A grown automaton is flattened again through the queue: ordered after the appends submitted before it,
+    into the caller's arrays, with the same result as a flatten on the calling thread; too-small arrays are
+    reported and leave the automaton usable."""
+    rng = np.random.default_rng(3)
+    T = rng.integers(0, 50, 5000).astype(np.int32)
+    b = A.SamBuilder()
+    b.submit(1, T[:3000], 99)
+    b.wait(1)
+    sam, _ = b.poll(1)
+    A.sam_flatten([sam])
+    assert b.flatten_result(1) == -2                          # none yet
+    b.submit(1, T[3000:], 99)                                 # the flatten below must see these tokens
+    ns_cap, ne_cap, nt_cap = 2 * 5000 + 2, 3 * 5000, 5000
+    fill = lambda n: np.full(n, -1, np.int32)
+    out = A.FlatSam(fill(ns_cap), fill(ns_cap), np.zeros(ns_cap + 1, np.int32), fill(ne_cap), fill(ne_cap), fill(ns_cap),
+                    fill(nt_cap), fill(4 * ns_cap), np.zeros(1, np.int32), np.zeros(1, np.int32), np.zeros(1, np.int32))
+    b.flatten(1, out)
+    assert b.poll(1)[0] is None or b.flatten_result(1) == 0   # not available while the flatten is pending
+    b.wait(1)
+    assert b.flatten_result(1) == 0
+    sam, pending = b.poll(1)
+    assert sam is not None and pending == 0
+    ns, ne, nt = A.sam_flat_sizes(sam)
+    assert nt == 5000
+    assert A.sam_delta_sizes(sam) == (0, 0, 0, 0, 0, ns)      # the flatten has reset the log
+    ref = A.sam_flatten([A.sam_build(T, 99)])
+    for name in ("len", "link", "lastpos", "corpus"):
+        assert np.array_equal(getattr(out, name)[:getattr(ref, name).shape[0]], getattr(ref, name)), name
+    assert np.array_equal(out.row_ptr[:ns + 1], ref.row_ptr) and np.array_equal(out.edge_tok[:ne], ref.edge_tok)
+    assert np.array_equal(out.edge_dst[:ne], ref.edge_dst) and np.array_equal(out.state_rec[:4 * ns], ref.state_rec)
+    small = A.FlatSam(fill(10), fill(10), np.zeros(11, np.int32), fill(10), fill(10), fill(10), fill(10), fill(40),
+                      np.zeros(1, np.int32), np.zeros(1, np.int32), np.zeros(1, np.int32))
+    b.flatten(1, small)
+    b.wait(1)
+    assert b.flatten_result(1) == -4                          # does not fit; nothing was written past the arrays
+    assert b.poll(1)[0] is not None
+    with pytest.raises(A.AgentSamError):
+        b.flatten(77, out)                                    # unknown request
     b.close()

@@ -32,6 +32,18 @@ def _overlay_find(keys, dsts, s, c):
     return -1
 
 
+def _overlay_insert(keys, dsts, new_keys, new_dsts):
+    """What sam_apply_delta does with the exported transitions, on host arrays."""
+    mask = len(keys) - 1
+    for key, d in zip(new_keys, new_dsts):
+        key = int(key)
+        j = _hash64(key) & mask
+        while int(keys[j]) != M64 and int(keys[j]) != key:
+            j = (j + 1) & mask
+        keys[j] = np.uint64(key)
+        dsts[j] = d
+
+
 class Live:
     """Host emulation of a maintained device copy: the arrays sam_draft_delta reads."""
 
@@ -48,11 +60,15 @@ class Live:
 
     def sync(self):
         n_ov = A.sam_delta_sizes(self.sam)[2]
-        cap = 2
-        while cap < 2 * n_ov:
-            cap *= 2
-        self.keys, self.dsts = A.overlay_table(cap)
-        d = A.sam_delta_export(self.sam, self.keys, self.dsts)
+        grow = 2 * n_ov > len(self.keys)
+        if grow:                                              # a larger table: everything since the flatten goes in again
+            cap = len(self.keys)
+            while cap < 2 * n_ov:
+                cap *= 2
+            self.keys, self.dsts = A.overlay_table(cap)
+        d = A.sam_delta_export(self.sam, overlay_all=grow)
+        assert len(set(int(k) for k in d.ov_key)) == len(d.ov_key)      # every key once
+        _overlay_insert(self.keys, self.dsts, d.ov_key, d.ov_dst)
         assert d.flat_states == self.rows_end
         self.rec[d.rec_idx] = d.rec_val
         self.lastpos[d.lastpos_idx] = d.lastpos_val
@@ -106,10 +122,9 @@ def test_no_delta_before_a_flatten_and_empty_delta_after():
     with pytest.raises(A.AgentSamError):
         A.sam_delta_sizes(s)
     A.sam_flatten([s])
-    assert A.sam_delta_sizes(s) == (0, 0, 0, 0, 4)
-    k, d = A.overlay_table(2)
-    dl = A.sam_delta_export(s, k, d)
-    assert dl.rec_idx.size == 0 and dl.new_tokens.size == 0 and (k == np.uint64(M64)).all()
+    assert A.sam_delta_sizes(s) == (0, 0, 0, 0, 0, 4)
+    dl = A.sam_delta_export(s)
+    assert dl.rec_idx.size == 0 and dl.new_tokens.size == 0 and dl.ov_key.size == 0
 
 
 def test_hand_example_tail_becomes_eligible():
@@ -165,21 +180,69 @@ def test_maintained_copy_answers_like_the_oracle(seed):
     assert np.array_equal(unflag(live.rec[:ns]), unflag(f.state_rec.reshape(ns, 4)))
     assert np.array_equal(live.corpus[:live.nt], f.corpus) and live.nt == len(T)
     # and the flatten has reset the log
-    assert A.sam_delta_sizes(sam) == (0, 0, 0, 0, ns)
+    assert A.sam_delta_sizes(sam) == (0, 0, 0, 0, 0, ns)
+
+
+def test_export_hands_out_new_transitions_once_and_all_on_request():
+    s = A.sam_build([1, 2, 1, 2], 9)
+    A.sam_flatten([s])
+    A.sam_append(s, [3, 1, 2, 3])
+    _, _, n_ov, n_new, _, _ = A.sam_delta_sizes(s)
+    assert n_ov == n_new > 0
+    d1 = A.sam_delta_export(s)
+    assert 0 < d1.ov_key.size <= n_ov
+    assert A.sam_delta_sizes(s)[2:4] == (n_ov, 0)              # the log stays, nothing new
+    assert A.sam_delta_export(s).ov_key.size == 0
+    A.sam_append(s, [1, 2, 3, 4])
+    d2 = A.sam_delta_export(s)
+    every = A.sam_delta_export(s, overlay_all=True)           # everything since the flatten, latest destination per key
+    merged = dict(zip(d1.ov_key.tolist(), d1.ov_dst.tolist())); merged.update(zip(d2.ov_key.tolist(), d2.ov_dst.tolist()))
+    assert dict(zip(every.ov_key.tolist(), every.ov_dst.tolist())) == merged
+    # the policy: due once the log exceeds the stated fraction of the flattened transitions (6 here)
+    assert A.sam_reflatten_due(s, 0.1) and not A.sam_reflatten_due(s, 100.0)
+    A.sam_flatten([s])
+    assert not A.sam_reflatten_due(s, 0.0)
+    fresh = A.sam_build([1, 2], 9)
+    assert A.sam_reflatten_due(fresh, 100.0)                  # never flattened
+
+
+def test_periodic_memory_appends_cost_one_chain_walk_per_export_not_per_token():
+    """A continuously repetitive 30k-token memory (the case Sec. 6's TTFT / TPOT table measures): the suffix-link
+    chains are thousands of states long.  Appending with a maintained copy must stay within a small factor of
+    appending without one, and the export must still give what a fresh flatten gives."""
+    import time
+    base = np.tile(np.array([5, 6, 7], np.int32), 10000)
+    more = np.tile(np.array([5, 6, 7], np.int32), 3000)
+    plain = A.sam_build(base, 9)
+    t0 = time.perf_counter(); A.sam_append(plain, more); t_plain = time.perf_counter() - t0
+    s = A.sam_build(base, 9)
+    f0 = A.sam_flatten([s])
+    lastpos = np.full(2 * (base.size + more.size) + 2, -1, np.int32); lastpos[:f0.lastpos.size] = f0.lastpos
+    t0 = time.perf_counter()
+    for i in range(0, more.size, 3):                          # a step commits a few tokens, then the delta is taken
+        A.sam_append(s, more[i:i + 3])
+        if i % 300 == 0:
+            d = A.sam_delta_export(s)
+            lastpos[d.lastpos_idx] = d.lastpos_val
+    d = A.sam_delta_export(s)
+    lastpos[d.lastpos_idx] = d.lastpos_val
+    t_tracked = time.perf_counter() - t0
+    f1 = A.sam_flatten([s])
+    assert np.array_equal(lastpos[:f1.lastpos.size], f1.lastpos)
+    print(f"9000 tokens appended to a period-3 memory of 30000: {t_plain * 1e3:.1f} ms plain, {t_tracked * 1e3:.1f} ms with "
+          f"31 exports ({t_tracked / more.size * 1e6:.2f} us per token)")
+    assert t_tracked < 0.15                                   # (one chain walk per token took 0.5 s here)
 
 
 def test_export_argument_errors():
     s = A.sam_build([1, 2, 1, 2], 9)
     A.sam_flatten([s])
     A.sam_append(s, [3, 1, 2, 3])
-    n_ov = A.sam_delta_sizes(s)[2]
-    assert n_ov > 0
-    k, d = A.overlay_table(2)                                     # too small: must stay at most half full
-    with pytest.raises(A.AgentSamError):
-        A.sam_delta_export(s, k, d)
-    k = np.full(24, np.uint64(M64), np.uint64); d = np.full(24, -1, np.int32)      # not a power of two
-    with pytest.raises(A.AgentSamError):
-        A.sam_delta_export(s, k, d)
-    k, d = A.overlay_table(64)
-    A.sam_delta_export(s, k, d)                                   # a failed export loses nothing
-    assert (k != np.uint64(M64)).sum() > 0
+    from paper_2512_18337_amd import binding
+    import ctypes
+    nw = ctypes.c_int64()
+    # transitions to hand out but no arrays for them
+    rc = binding.lib().sam_delta_export(s._h, 0, 0, None, None, None, None, 0, None, None, ctypes.byref(nw), None)
+    assert rc == -1
+    d = A.sam_delta_export(s)                                 # a failed export loses nothing
+    assert d.ov_key.size > 0 and d.rec_idx.size > 0
