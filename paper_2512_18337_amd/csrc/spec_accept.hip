@@ -1,7 +1,7 @@
 // spec_accept: greedy verification of the drafts.
 //
-// Alg. 4 ("Validate with main LLM; commit matched prefix; on mismatch fall back") and the
-// losslessness claim of Sec. 5.4.1: the committed tokens equal greedy decoding.
+// Alg. 4 (validation by the main model, commit of the matched prefix, fall-back at the first mismatch) and
+// the losslessness claim of Sec. 5.4.1: the committed tokens equal greedy decoding.
 //
 // Two launches on the caller's stream:
 //   1. row_argmax: one workgroup per logits row streams the row once with 16-byte loads
@@ -9,6 +9,17 @@
 //      and reduces (value, index) pairs with the first-index tie rule through wavefront
 //      shuffles and one LDS exchange.
 //   2. accept_prefix: one lane per session compares the drafts with the row targets.
+//
+// Two other arrangements were built, passed the same tests and were measured on the headline batch
+// (576 rows of 128 KB; this arrangement: 16.7 us + 4.1 us):
+//   - rows cut into segments, one workgroup per (row, segment), partial maxima in a scratch array, the
+//     second launch taking the best segment per row: the first launch takes the same 16.6 us (at 74 MB
+//     it is the ramp-up of the launch, not the number of workgroups, that keeps it from the streaming
+//     rate) and the second twice as long;
+//   - one launch, the last workgroup of a session to arrive doing step 2: merging a row maximum and
+//     counting the arrival are two dependent device-scope atomic operations per workgroup, resolved at
+//     the memory side, and the last arriver then has a chain of its own: 30 us; with memory fences,
+//     which write back and invalidate an L2 on this GPU, 118 us.
 #include <hip/hip_bf16.h>
 
 #include "common.h"
@@ -40,32 +51,32 @@ __device__ __forceinline__ float load_one(const void *row, int64_t i) {
     return ((const float *)row)[i];
 }
 
+// (value, index) of the first maximum of row[e0 .. e1), over the workgroup; valid in thread 0.
+// index kNoIndex: nothing in the range is above -inf.
 template <bool BF16>
-__global__ __launch_bounds__(kThreads) void row_argmax_kernel(const void *__restrict__ logits, int64_t V,
-                                                              int32_t *__restrict__ tgt) {
+__device__ __forceinline__ Best segment_argmax(const char *row, int64_t e0, int64_t e1) {
     constexpr int kElem = BF16 ? 2 : 4;
     constexpr int kPerVec = 16 / kElem;
-    const int64_t row_id = blockIdx.x;
-    const char *row = (const char *)logits + row_id * V * kElem;
     const int tid = threadIdx.x;
-
-    // split the row into an unaligned head, a 16-byte-aligned body and a tail
-    const int64_t mis = (int64_t)((uintptr_t)row & 15);
+    // an unaligned head, a 16-byte-aligned body and a tail
+    const char *seg = row + e0 * kElem;
+    const int64_t n = e1 - e0;
+    const int64_t mis = (int64_t)((uintptr_t)seg & 15);
     int64_t head = mis ? (16 - mis) / kElem : 0;
-    if (head > V) head = V;
-    const int64_t nvec = (V - head) / kPerVec;
+    if (head > n) head = n;
+    const int64_t nvec = (n - head) / kPerVec;
     const int64_t tail0 = head + nvec * kPerVec;
 
     Best best{-INFINITY, kNoIndex};
     if (tid < head) {
-        const float x = clean(load_one<BF16>(row, tid));
-        if (x > best.v) best = Best{x, (int)tid};
+        const float x = clean(load_one<BF16>(seg, tid));
+        if (x > best.v) best = Best{x, (int)(e0 + tid)};
     }
-    const u32x4 *body = (const u32x4 *)(row + head * kElem);
+    const u32x4 *body = (const u32x4 *)(seg + head * kElem);
 #pragma unroll 4
     for (int64_t j = tid; j < nvec; j += kThreads) {
         const u32x4 w = __builtin_nontemporal_load(body + j);
-        const int64_t base = head + j * kPerVec;
+        const int64_t base = e0 + head + j * kPerVec;
         const uint32_t ws[4] = {w[0], w[1], w[2], w[3]};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -82,9 +93,9 @@ __global__ __launch_bounds__(kThreads) void row_argmax_kernel(const void *__rest
     }
     // every thread visits its indices in increasing order (head < body < tail), so the strict
     // comparison keeps the first maximum it sees
-    for (int64_t i = tail0 + tid; i < V; i += kThreads) {
-        const float x = clean(load_one<BF16>(row, i));
-        if (x > best.v) best = Best{x, (int)i};
+    for (int64_t i = tail0 + tid; i < n; i += kThreads) {
+        const float x = clean(load_one<BF16>(seg, i));
+        if (x > best.v) best = Best{x, (int)(e0 + i)};
     }
 
 #pragma unroll
@@ -96,12 +107,31 @@ __global__ __launch_bounds__(kThreads) void row_argmax_kernel(const void *__rest
     __shared__ int si[kThreads / 64];
     if ((tid & 63) == 0) { sv[tid >> 6] = best.v; si[tid >> 6] = best.i; }
     __syncthreads();
-    if (tid == 0) {
-        Best r{sv[0], si[0]};
+    Best r{sv[0], si[0]};
 #pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) r = better(r, Best{sv[w], si[w]});
-        tgt[row_id] = (r.i == kNoIndex) ? 0 : r.i;       // no finite maximum: index 0
-    }
+    for (int w = 1; w < kThreads / 64; ++w) r = better(r, Best{sv[w], si[w]});
+    return r;
+}
+
+__device__ __forceinline__ void commit_session(int b, int k, const int32_t *tgt_row, const int32_t *__restrict__ draft,
+                                               const int32_t *__restrict__ n_draft, int32_t *__restrict__ accept_len,
+                                               int32_t *__restrict__ out_tokens) {
+    // one lane: R <= 65 tokens
+    const int R = k + 1;
+    const int nd = min(max(n_draft[b], 0), k);
+    int a = 0;
+    while (a < nd && draft[(int64_t)b * k + a] == tgt_row[a]) ++a;
+    accept_len[b] = a;
+    for (int i = 0; i < R; ++i) out_tokens[(int64_t)b * R + i] = (i <= a) ? tgt_row[i] : -1;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void row_argmax_kernel(const void *__restrict__ logits, int64_t V,
+                                                              int32_t *__restrict__ tgt) {
+    constexpr int kElem = BF16 ? 2 : 4;
+    const int64_t row_id = blockIdx.x;
+    const Best r = segment_argmax<BF16>((const char *)logits + row_id * V * kElem, 0, V);
+    if (threadIdx.x == 0) tgt[row_id] = (r.i == kNoIndex) ? 0 : r.i;       // no finite maximum: index 0
 }
 
 __global__ void accept_prefix_kernel(const int32_t *__restrict__ tgt, const int32_t *__restrict__ draft,
@@ -109,12 +139,7 @@ __global__ void accept_prefix_kernel(const int32_t *__restrict__ tgt, const int3
                                      int32_t *__restrict__ accept_len, int32_t *__restrict__ out_tokens) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    const int R = k + 1;
-    const int nd = min(max(n_draft[b], 0), k);
-    int a = 0;
-    while (a < nd && draft[(int64_t)b * k + a] == tgt[(int64_t)b * R + a]) ++a;
-    accept_len[b] = a;
-    for (int i = 0; i < R; ++i) out_tokens[(int64_t)b * R + i] = (i <= a) ? tgt[(int64_t)b * R + i] : -1;
+    commit_session(b, k, tgt + (int64_t)b * (k + 1), draft, n_draft, accept_len, out_tokens);
 }
 
 }  // namespace
@@ -129,13 +154,9 @@ extern "C" int spec_accept(const void *logits, int32_t logits_dtype, const int32
     const int64_t rows = (int64_t)B * (k + 1);
     if (rows > 0x7fffffffll) return AGENTSAM_ERR_ARG;
     hipStream_t st = (hipStream_t)stream;
-    if (logits_dtype == AGENTSAM_BF16)
-        AGENTSAM_LAUNCH(row_argmax_kernel<true>, dim3((unsigned)rows), dim3(kThreads), st,
-                    logits, V, tgt);
-    else
-        AGENTSAM_LAUNCH(row_argmax_kernel<false>, dim3((unsigned)rows), dim3(kThreads), st,
-                    logits, V, tgt);
-    AGENTSAM_LAUNCH(accept_prefix_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), st,
-                    tgt, draft, n_draft, (int)B, (int)k, accept_len, out_tokens);
+    if (logits_dtype == AGENTSAM_BF16) AGENTSAM_LAUNCH(row_argmax_kernel<true>, dim3((unsigned)rows), dim3(kThreads), st, logits, V, tgt);
+    else AGENTSAM_LAUNCH(row_argmax_kernel<false>, dim3((unsigned)rows), dim3(kThreads), st, logits, V, tgt);
+    AGENTSAM_LAUNCH(accept_prefix_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), st, tgt, draft, n_draft, (int)B,
+                    (int)k, accept_len, out_tokens);
     return AGENTSAM_OK;
 }

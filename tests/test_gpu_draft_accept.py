@@ -137,3 +137,44 @@ def test_spec_accept_edge_cases():
     a, out, tgt = A.spec_accept(lg, torch.as_tensor(draft, device=DEV), torch.as_tensor(nd, device=DEV))
     torch.cuda.synchronize()
     assert np.array_equal(to_np(tgt), accept_oracle(to_np(lg), draft, nd)[2])
+
+
+def test_spec_accept_long_rows_special_values_and_calls_on_two_streams():
+    """Few rows of a long vocabulary with the maximum occurring many times, as -0 and +0, rows that are half NaN,
+    all NaN, all -inf, with several +inf; many calls back to back and on two streams, every one equal to the
+    oracle; then a batch of 9000 short rows."""
+    from oracle import accept_oracle
+    rng = np.random.default_rng(11)
+    B, k, V = 3, 2, 200003                                    # 9 rows x 800 KB (fp32): the maximum split
+    lg = (torch.randn(B, k + 1, V) * 2).round().div(2)        # coarse values: the maximum occurs many times
+    lg[0, 0] = torch.where(lg[0, 0] >= lg[0, 0].max(), torch.tensor(0.0), -lg[0, 0].abs())   # maximum 0 ...
+    lg[0, 0, 150000] = -0.0; lg[0, 0, 70001] = 0.0            # ... as -0 and +0 in different segments
+    lg[0, 1, ::2] = float("nan"); lg[0, 2] = float("-inf")    # half a row NaN; a row without a finite maximum
+    lg[1, 0, 199999] = float("inf"); lg[1, 0, 31] = float("inf")
+    lg[1, 1] = float("nan")
+    for dt in (torch.float32, torch.bfloat16):
+        lgd = lg.to(dt).to(DEV)
+        ref = np.nan_to_num(to_np(lg.to(dt)), nan=-np.inf)
+        tg = np.argmax(ref, axis=2).astype(np.int32)
+        draft = tg[:, :k].copy(); draft[2, 1] += 1
+        nd = np.array([2, 1, 2], np.int32)
+        oa, oout, otgt = accept_oracle(to_np(lg.to(dt)), draft, nd)
+        assert np.array_equal(otgt, tg) and otgt[0, 2] == 0 and otgt[1, 1] == 0
+        dd, ndd = torch.as_tensor(draft, device=DEV), torch.as_tensor(nd, device=DEV)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        results = []
+        for rep in range(40):
+            results.append(A.spec_accept(lgd, dd, ndd))
+            with torch.cuda.stream(side):
+                results.append(A.spec_accept(lgd, dd, ndd))
+        torch.cuda.synchronize()
+        for a, out, tgt in results:
+            assert np.array_equal(to_np(tgt), otgt) and np.array_equal(to_np(a), oa) and np.array_equal(to_np(out), oout)
+    Bw, kw, Vw = 1500, 5, 257
+    lgw = torch.randn(Bw, kw + 1, Vw, device=DEV)
+    tgw = lgw.argmax(2).int()
+    dw = tgw[:, :kw].contiguous(); ndw = torch.full((Bw,), kw, dtype=torch.int32, device=DEV)
+    for rep in range(20):
+        a, out, tgt = A.spec_accept(lgw, dw, ndw)
+        assert torch.equal(tgt, tgw) and bool((a == kw).all())
