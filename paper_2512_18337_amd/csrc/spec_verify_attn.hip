@@ -1296,10 +1296,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const AttnParams p, int
 // Workgroup i keeps the partial of its first segment in record 2i and that of its last in 2i+1.
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_balanced_kernel(const AttnParams p, int nslots) {
-    const int kvh = blockIdx.x, b = blockIdx.y;
+    constexpr int kRowsPerWg = 256 / (D / 4);                // one thread per (row, 4 output values)
+    const int kvh = blockIdx.x, b = blockIdx.y, slab = blockIdx.z;
     const int nt_b = tiles_of(session_len(p, b));
     if (nt_b == 0) {                                         // an empty session: no workgroup had any of it
-        zero_session_heads(p.out, p.out_bf16, b, p.R, p.Hq, D, kvh * p.G, p.G);
+        if (slab == 0) zero_session_heads(p.out, p.out_bf16, b, p.R, p.Hq, D, kvh * p.G, p.G);
         return;
     }
     const int T = p.plan[p.B] * p.Hkv;
@@ -1311,25 +1312,25 @@ __global__ __launch_bounds__(256) void attn_merge_balanced_kernel(const AttnPara
     // the stream's piece is the first segment of every workgroup but possibly the first one
     const int first_slot = (i0 * share < g0) ? 1 : 0;
     auto record = [&](int i) { return p.wsr + (2 * (int64_t)i + (i == i0 ? first_slot : 0)) * recf; };
-    for (int idx = threadIdx.x; idx < p.rows * (D / 4); idx += 256) {
-        const int pr = idx / (D / 4), c4 = idx % (D / 4);
-        float M = kNegBig;
-        for (int i = i0; i <= i1; ++i) M = fmaxf(M, record(i)[(int64_t)p.rows_pad * D + pr]);
-        float L = 0.f;
-        float4 acc{0.f, 0.f, 0.f, 0.f};
-        for (int i = i0; i <= i1; ++i) {
-            const float *rec = record(i);
-            const float w = exp2f(rec[(int64_t)p.rows_pad * D + pr] - M);
-            L += w * rec[(int64_t)p.rows_pad * D + p.rows_pad + pr];
-            const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
-            acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
-        }
-        const float inv = inv_or_zero(L);
-        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-        const int hh = pr / p.R, i = pr % p.R;
-        const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
-        store_out(p.out, o, acc, p.out_bf16);
+    const int pr = slab * kRowsPerWg + (int)threadIdx.x / (D / 4), c4 = (int)threadIdx.x % (D / 4);
+    if (pr >= p.rows) return;
+    float M = kNegBig;
+    for (int i = i0; i <= i1; ++i) M = fmaxf(M, record(i)[(int64_t)p.rows_pad * D + pr]);
+    float L = 0.f;
+    float4 acc{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int i = i0; i <= i1; ++i) {
+        const float *rec = record(i);
+        const float w = exp2f(rec[(int64_t)p.rows_pad * D + pr] - M);
+        L += w * rec[(int64_t)p.rows_pad * D + p.rows_pad + pr];
+        const float4 o = *(const float4 *)(rec + (int64_t)pr * D + c4 * 4);
+        acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
     }
+    const float inv = inv_or_zero(L);
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    const int hh = pr / p.R, i = pr % p.R;
+    const int64_t o = (((int64_t)b * p.R + i) * p.Hq + (int64_t)kvh * p.G + hh) * D + c4 * 4;
+    store_out(p.out, o, acc, p.out_bf16);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1768,8 +1769,10 @@ int run_attn(const void *q, const void *k_cache, const void *v_cache, const int3
     ATTN_TRY(D == 64 ? launch_bf16<64>(p, pl.wide, grid, st) : launch_bf16<128>(p, pl.wide, grid, st));
     dim3 mg((unsigned)Hkv, (unsigned)B);
     if (pl.balanced) {
-        ATTN_TRY(D == 64 ? launch(attn_merge_balanced_kernel<64>, mg, dim3(256), st, p, pl.nslots)
-                         : launch(attn_merge_balanced_kernel<128>, mg, dim3(256), st, p, pl.nslots));
+        const int slabs = (p.rows + (256 / (D / 4)) - 1) / (256 / (D / 4));
+        dim3 mgb((unsigned)Hkv, (unsigned)B, (unsigned)slabs);
+        ATTN_TRY(D == 64 ? launch(attn_merge_balanced_kernel<64>, mgb, dim3(256), st, p, pl.nslots)
+                         : launch(attn_merge_balanced_kernel<128>, mgb, dim3(256), st, p, pl.nslots));
     } else if (pl.nchunks_max > 1) {
         ATTN_TRY(D == 64 ? launch(attn_merge_kernel<64>, mg, dim3(256), st, p, (int)Hkv, p.G)
                          : launch(attn_merge_kernel<128>, mg, dim3(256), st, p, (int)Hkv, p.G));
