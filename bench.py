@@ -37,8 +37,8 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=2, help="baseline workload index (default: the headline one)")
     ap.add_argument("--seed", type=int, default=None, help="seed of the synthetic inputs (default: the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -227,8 +227,10 @@ class AttnInputs:
         self.A.spec_verify_attn(self.q, self.kc, self.vc, self.bt, self.seq, self.scale, out=self.out, workspace=self.ws,
                                 tuning=self.tuning)
 
-    def time_attn(self, launches, warmup=3):
-        """Mean HIP-event time of one spec_verify_attn call (all its launches), in ms, on the launch stream."""
+    def time_attn(self, launches, warmup=10):
+        """Mean HIP-event time of one spec_verify_attn call (all its launches), in ms, on the launch stream.
+        (An idle GPU takes some 15 ms of work to reach its clocks: the first ten launches of the headline
+        workload run 9 % slower than the ones after them, so the warm-up is that long.)"""
         import torch
         for _ in range(warmup):
             self.attn()

@@ -553,10 +553,18 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, int *tmp, 
     }
 }
 
-// The page id of every 32-position tile of a chunk, fetched once at kernel start (lane i of register
-// r holds the id for tile 64*r + i) and handed out with v_readlane: the tile loop never waits on a
-// block-table load, and no vector load of its own sits between the streaming loads whose completion
-// it counts.  A chunk therefore spans at most 256 tiles (8192 positions).
+// A session's row of the block table, read through the constant address space: the table does not change
+// during a launch, so a load with a uniform index is a scalar load, which neither takes vector registers
+// nor counts among the vector loads in flight.
+typedef const int32_t __attribute__((address_space(4))) *BlockTableRow;
+__device__ __forceinline__ BlockTableRow block_table_row(const AttnParams &p, int b) {
+    return (BlockTableRow)(uintptr_t)(p.bt + (int64_t)b * p.max_pages);
+}
+
+// Wide kernel: the page id of every 32-position tile of a chunk, fetched once per 256 tiles (lane i of
+// register r holds the id for tile 64*r + i) and handed out with v_readlane, so the wavefront that requests
+// a tile has its page id at once.  (Scalar loads of the block table, as the narrow kernel makes them, were
+// measured here too: 1 to 2 % slower, the request being on the critical path of a tile.)
 constexpr int kMaxChunk = 256 * kTile;
 struct ChunkPages {
     int r0, r1, r2, r3;          // named members, not an array: an indexable private array would be
@@ -581,28 +589,6 @@ __device__ __forceinline__ int tile_page(const ChunkPages &cp, int t /* uniform 
     const int sel = t >> 6;
     const int v = sel == 0 ? cp.r0 : sel == 1 ? cp.r1 : sel == 2 ? cp.r2 : cp.r3;
     return __builtin_amdgcn_readlane(v, t & 63);
-}
-
-// Start of a tile's first row in the K and V caches, and whether its page id is usable.
-template <int D>
-struct TileSrc {
-    const __hip_bfloat16 *kbase, *vbase;
-    int pos0;
-    bool page_ok;
-};
-
-template <int D>
-__device__ __forceinline__ TileSrc<D> tile_src(const AttnParams &p, const ChunkPages &cp, int kvh, int c0, int t) {
-    TileSrc<D> ts;
-    const int pos0 = c0 + t * kTile;
-    const int slot = p.log2P >= 0 ? (pos0 & (p.P - 1)) : (pos0 % p.P);
-    const int page = tile_page(cp, t);
-    ts.page_ok = page >= 0 && (int64_t)page < p.num_pages;
-    const int64_t base = (((int64_t)(ts.page_ok ? page : 0) * p.Hkv + kvh) * p.P + slot) * D;
-    ts.kbase = (const __hip_bfloat16 *)p.kc + base;
-    ts.vbase = (const __hip_bfloat16 *)p.vc + base;
-    ts.pos0 = pos0;
-    return ts;
 }
 
 // -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the segment
@@ -630,82 +616,99 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
         WaveState<D, MT> w;
         init_state<D, MT>(w, p, b, kvh, 0, p.rows, n, g);
 
-        // page ids are held for 256 tiles at a time
-        for (int sub = 0; sub < sg.nt; sub += kMaxChunk / kTile) {
-            const int c0 = (sg.t0 + sub) * kTile;
-            const int ntiles = min(sg.nt - sub, kMaxChunk / kTile);
-            const int c1 = min(S, c0 + ntiles * kTile);
-            const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
-            // Nothing else may be outstanding when the tile pipeline starts (the page ids are needed at
-            // once anyway): with only its own loads in flight, in a known order, the compiler's waits
-            // inside the loop count exactly; a pending store of the previous segment would make every
-            // wait at the top of the loop a wait for everything.
+        // My tiles of the segment: i-th one is tile t_first + 4*i of the stream.  Its page id comes from the
+        // block table with a scalar load (uniform address, read-only for the whole launch), fetched one step
+        // before the tile is requested, so the tile loop neither waits for it nor has a vector load of its
+        // own between the streaming loads whose completion it counts, and a segment of any length runs
+        // as one uninterrupted pipeline.
+        const BlockTableRow bt_row = block_table_row(p, b);
+        const int t_first = sg.t0 + wave;
+        const int n_my = wave < sg.nt ? (sg.nt - wave + kWaves - 1) / kWaves : 0;   // tiles of this wavefront
+        auto page_of = [&](int i) {                              // uniform; -1 past my last tile
+            if (i >= n_my) return -1;
+            const int pos0 = (t_first + kWaves * i) * kTile;
+            return (int)bt_row[p.log2P >= 0 ? (pos0 >> p.log2P) : (pos0 / p.P)];
+        };
+        auto usable = [&](int page) { return page >= 0 && (int64_t)page < p.num_pages; };
+
+        // Two tiles are kept in flight in registers while a third is being computed from LDS.  The
+        // loads are issued unconditionally (past the wavefront's last tile every lane re-reads the first
+        // bytes of q, one hot cache line; an unusable page id reads page 0) and what must not be seen
+        // is zeroed when the tile is staged:
+        // with a fixed number of loads per step the compiler can wait for exactly the older of the two
+        // tiles in flight instead of for everything outstanding.
+        uint4 kreg[2][C::kLoads], vreg[2][C::kLoads];
+        auto issue_loads = [&](int i, int page, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
+            const bool live = i < n_my;                          // uniform
+            const int pos0 = (t_first + kWaves * i) * kTile;
+            const int slot = p.log2P >= 0 ? (pos0 & (p.P - 1)) : (pos0 % p.P);
+            const int64_t base = (((int64_t)(usable(page) ? page : 0) * p.Hkv + kvh) * p.P + slot) * D;
+            const __hip_bfloat16 *kb = live ? (const __hip_bfloat16 *)p.kc + base : (const __hip_bfloat16 *)p.q;
+            const __hip_bfloat16 *vb = live ? (const __hip_bfloat16 *)p.vc + base : (const __hip_bfloat16 *)p.q;
+            const int lane_off = live ? ld_row * D + ld_col * 8 : 0;
+            const int step = live ? C::kRowsPerLoad * D : 0;
+#pragma unroll
+            for (int j = 0; j < C::kLoads; ++j) {
+                kr[j] = ld_stream(kb + lane_off + j * step);
+                vr[j] = ld_stream(vb + lane_off + j * step);
+            }
+        };
+        auto stage = [&](int i, int page, const uint4 (&kr)[C::kLoads], const uint4 (&vr)[C::kLoads]) {
+            const int pos0 = (t_first + kWaves * i) * kTile;
+            const bool page_ok = usable(page);
+            if (page_ok && pos0 + kTile <= S) {                  // the usual case: a full tile
+#pragma unroll
+                for (int j = 0; j < C::kLoads; ++j) {
+                    const int row = j * C::kRowsPerLoad + ld_row;
+                    *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[j];
+                    *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[j];
+                }
+            } else {                                             // rows past the end, or a page of zeros
+#pragma unroll
+                for (int j = 0; j < C::kLoads; ++j) {
+                    const int row = j * C::kRowsPerLoad + ld_row;
+                    const bool ok = page_ok && pos0 + row < S;
+                    *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = ok ? kr[j] : uint4{0u, 0u, 0u, 0u};
+                    *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = ok ? vr[j] : uint4{0u, 0u, 0u, 0u};
+                }
+            }
+        };
+
+        if (n_my > 0) {
+            int pg0 = page_of(0), pg1 = page_of(1), pg_next = page_of(2);
+            // Nothing else may be outstanding when the tile pipeline starts: with only its own loads in
+            // flight, in a known order, the compiler's waits inside the loop count exactly; a pending load
+            // of the query fragments or a store of the previous segment would make every wait at the top of
+            // the loop a wait for everything.
             wait_vmcnt0();
-
-            // Two tiles are kept in flight in registers while a third is being computed from LDS.  The
-            // loads are issued unconditionally (past the wavefront's last tile every lane re-reads the first
-            // bytes of q, one hot cache line; an unusable page id reads page 0) and what must not be seen
-            // is zeroed when the tile is staged:
-            // with a fixed number of loads per step the compiler can wait for exactly the older of the two
-            // tiles in flight instead of for everything outstanding.
-            uint4 kreg[2][C::kLoads], vreg[2][C::kLoads];
-            auto issue_loads = [&](int t, int last, uint4 (&kr)[C::kLoads], uint4 (&vr)[C::kLoads]) {
-                const bool live = t <= last;                     // uniform
-                const TileSrc<D> src = tile_src<D>(p, cp, kvh, c0, live ? t : last);
-                const __hip_bfloat16 *kb = live ? src.kbase : (const __hip_bfloat16 *)p.q;
-                const __hip_bfloat16 *vb = live ? src.vbase : (const __hip_bfloat16 *)p.q;
-                const int lane_off = live ? ld_row * D + ld_col * 8 : 0;
-                const int step = live ? C::kRowsPerLoad * D : 0;
-#pragma unroll
-                for (int i = 0; i < C::kLoads; ++i) {
-                    kr[i] = ld_stream(kb + lane_off + i * step);
-                    vr[i] = ld_stream(vb + lane_off + i * step);
-                }
-            };
-            auto stage = [&](int t, const uint4 (&kr)[C::kLoads], const uint4 (&vr)[C::kLoads]) {
-                const int pos0 = c0 + t * kTile;
-                const int page = tile_page(cp, t);
-                const bool page_ok = page >= 0 && (int64_t)page < p.num_pages;
-                if (page_ok && pos0 + kTile <= S) {              // the usual case: a full tile
-#pragma unroll
-                    for (int i = 0; i < C::kLoads; ++i) {
-                        const int row = i * C::kRowsPerLoad + ld_row;
-                        *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[i];
-                        *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[i];
-                    }
-                } else {                                         // rows past the end, or a page of zeros
-#pragma unroll
-                    for (int i = 0; i < C::kLoads; ++i) {
-                        const int row = i * C::kRowsPerLoad + ld_row;
-                        const bool ok = page_ok && pos0 + row < S;
-                        *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = ok ? kr[i] : uint4{0u, 0u, 0u, 0u};
-                        *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = ok ? vr[i] : uint4{0u, 0u, 0u, 0u};
-                    }
-                }
-            };
-
-            const int n_my = wave < ntiles ? (ntiles - wave + kWaves - 1) / kWaves : 0;   // tiles of this wavefront
-            if (n_my > 0) {
-                const int last = wave + kWaves * (n_my - 1);
-                int t = wave;
-                issue_loads(t, last, kreg[0], vreg[0]);
-                issue_loads(t + kWaves, last, kreg[1], vreg[1]);
-                for (int i = 0;; i += 2) {
-                    stage(t, kreg[0], vreg[0]);
-                    wave_lds_fence();
-                    issue_loads(t + 2 * kWaves, last, kreg[0], vreg[0]);
-                    compute_tile<D, MT>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
-                    wave_lds_fence();
-                    t += kWaves;
-                    if (i + 1 >= n_my) break;
-                    stage(t, kreg[1], vreg[1]);
-                    wave_lds_fence();
-                    issue_loads(t + 2 * kWaves, last, kreg[1], vreg[1]);
-                    compute_tile<D, MT>(w, Ks, Vs, c0 + t * kTile, S, R, p.scale_log2, n, g);
-                    wave_lds_fence();
-                    t += kWaves;
-                    if (i + 2 >= n_my) break;
-                }
+            issue_loads(0, pg0, kreg[0], vreg[0]);
+            issue_loads(1, pg1, kreg[1], vreg[1]);
+            // Two tiles per round, so that the two register sets keep their roles; an odd last tile follows
+            // the loop.  The loop has one exit, at its end: an exit between the two halves would give the
+            // first half a path on which its own loads are the newest in flight, and the waits in front of
+            // its staging would then have to cover the other tile's loads as well.
+            int i = 0;
+            for (; i + 1 < n_my; i += 2) {
+                stage(i, pg0, kreg[0], vreg[0]);
+                wave_lds_fence();
+                pg0 = pg_next;
+                issue_loads(i + 2, pg0, kreg[0], vreg[0]);
+                pg_next = page_of(i + 3);
+                compute_tile<D, MT>(w, Ks, Vs, (t_first + kWaves * i) * kTile, S, R, p.scale_log2, n, g);
+                wave_lds_fence();
+                stage(i + 1, pg1, kreg[1], vreg[1]);
+                wave_lds_fence();
+                pg1 = pg_next;
+                issue_loads(i + 3, pg1, kreg[1], vreg[1]);
+                pg_next = page_of(i + 4);
+                compute_tile<D, MT>(w, Ks, Vs, (t_first + kWaves * (i + 1)) * kTile, S, R, p.scale_log2, n, g);
+                wave_lds_fence();
+            }
+            if (i < n_my) {
+                stage(i, pg0, kreg[0], vreg[0]);
+                wave_lds_fence();
+                compute_tile<D, MT>(w, Ks, Vs, (t_first + kWaves * i) * kTile, S, R, p.scale_log2, n, g);
+                wave_lds_fence();
             }
         }
 
