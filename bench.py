@@ -182,7 +182,7 @@ def measured_traffic(workload: str):
     return float(rec["hbm_bytes_per_call"])
 
 
-def attention_roofline(cfg, lay, t_attn_ms, stream_gbs=None):
+def attention_roofline(cfg, lay, t_attn_ms, stream_gbs=None, paged_gbs=None):
     """What bounds spec_verify_attn on this workload and how close the launch came.  Pages that several sessions
     list are needed from HBM once, so the memory bound counts the DISTINCT pages; the bound of the workload is the
     larger of that and the matrix work at the dense bf16 rate, and `frac` = bound / measured time."""
@@ -204,6 +204,9 @@ def attention_roofline(cfg, lay, t_attn_ms, stream_gbs=None):
     if stream_gbs:
         r["stream_read_GBs"] = stream_gbs
         r["frac_of_stream_read"] = unique_bytes / t / 1e9 / stream_gbs
+    if paged_gbs:                                            # the same loads through the block table, nothing else
+        r["paged_read_GBs"] = paged_gbs
+        r["frac_of_paged_read"] = unique_bytes / t / 1e9 / paged_gbs
     return r
 
 
@@ -263,6 +266,41 @@ def stream_read_rate(dev):
     e1.record()
     torch.cuda.synchronize()
     return buf.numel() * 4 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def paged_read_rate(inp, dev):
+    """The rate at which a kernel that makes the narrow attention kernel's loads through the block table and nothing
+    else reads this workload's K and V (sessions of one length, bf16 only), GB/s; None for other workloads."""
+    import torch
+    from paper_2512_18337_amd.build import BENCH_LIB
+    cfg, lay = inp.cfg, inp.lay
+    if cfg.dtype != "bf16" or int(lay.seq_lens.min()) != int(lay.seq_lens.max()) or cfg.page % 32 != 0:
+        return None
+    tiles = int(lay.seq_lens.min()) // 32
+    if tiles < 1:
+        return None
+    probe_lib = ctypes.CDLL(BENCH_LIB)
+    probe_lib.bench_paged_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                                 ctypes.c_longlong, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                 ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+
+    def probe():
+        rc = probe_lib.bench_paged_read_probe(inp.kc.data_ptr(), inp.vc.data_ptr(), inp.bt.data_ptr(), inp.bt.shape[1],
+                                              int(lay.num_pages), cfg.B, cfg.Hkv, cfg.page, cfg.D, tiles,
+                                              sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+
+    for _ in range(3):
+        probe()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        probe()
+    e1.record()
+    torch.cuda.synchronize()
+    nbytes = 2.0 * cfg.B * cfg.Hkv * tiles * 32 * cfg.D * 2
+    return nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
 def measure_targets(A, W, dev, stream_gbs, seed):
@@ -570,7 +608,7 @@ def main():
                    "sam_tokens": int(sum(len(m) for m in mems)), "vocab": cfg.vocab, "seed": cfg.seed,
                    "step": "sam_draft + spec_verify_attn + spec_accept", "attn_only": bool(args.attn_only),
                    "cold_caches": bool(args.cold)},
-        "roofline": attention_roofline(cfg, lay, t_attn, stream_gbs),
+        "roofline": attention_roofline(cfg, lay, t_attn, stream_gbs, paged_read_rate(inp, dev)),
         "detail": {"t_draft_us": t_draft * 1e3, "t_attn_us": t_attn * 1e3, "t_accept_us": t_accept * 1e3,
                    "sessions_per_s_sam_draft": (cfg.B / (t_draft * 1e-3)) if t_draft else None,
                    # the walk makes at least one dependent 16-byte record load per window token

@@ -674,6 +674,35 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
             }
         };
 
+        // Stage tile i_st out of (kr, vr) and request tile i_rq into the same registers.  For a full tile each
+        // register is written to LDS and loaded again at once, so the first requests of the new tile go out
+        // before the staging of the old one is over.
+        auto stage_and_issue = [&](int i_st, int page_st, int i_rq, int page_rq, uint4 (&kr)[C::kLoads],
+                                   uint4 (&vr)[C::kLoads]) {
+            const int pos_st = (t_first + kWaves * i_st) * kTile;
+            if (!(usable(page_st) && pos_st + kTile <= S)) {
+                stage(i_st, page_st, kr, vr);
+                issue_loads(i_rq, page_rq, kr, vr);
+                return;
+            }
+            const bool live = i_rq < n_my;                       // uniform
+            const int pos0 = (t_first + kWaves * i_rq) * kTile;
+            const int slot = p.log2P >= 0 ? (pos0 & (p.P - 1)) : (pos0 % p.P);
+            const int64_t base = (((int64_t)(usable(page_rq) ? page_rq : 0) * p.Hkv + kvh) * p.P + slot) * D;
+            const __hip_bfloat16 *kb = live ? (const __hip_bfloat16 *)p.kc + base : (const __hip_bfloat16 *)p.q;
+            const __hip_bfloat16 *vb = live ? (const __hip_bfloat16 *)p.vc + base : (const __hip_bfloat16 *)p.q;
+            const int lane_off = live ? ld_row * D + ld_col * 8 : 0;
+            const int step = live ? C::kRowsPerLoad * D : 0;
+#pragma unroll
+            for (int j = 0; j < C::kLoads; ++j) {
+                const int row = j * C::kRowsPerLoad + ld_row;
+                *(uint4 *)(Ks + row * C::kKStr + ld_col * 16) = kr[j];
+                *(uint4 *)(Vs + row * C::kVStr + ld_col * 16) = vr[j];
+                kr[j] = ld_stream(kb + lane_off + j * step);
+                vr[j] = ld_stream(vb + lane_off + j * step);
+            }
+        };
+
         if (n_my > 0) {
             int pg0 = page_of(0), pg1 = page_of(1), pg_next = page_of(2);
             // Nothing else may be outstanding when the tile pipeline starts: with only its own loads in
@@ -689,17 +718,15 @@ __global__ __launch_bounds__(256) void attn_bf16_narrow_kernel(const AttnParams 
             // its staging would then have to cover the other tile's loads as well.
             int i = 0;
             for (; i + 1 < n_my; i += 2) {
-                stage(i, pg0, kreg[0], vreg[0]);
-                wave_lds_fence();
+                stage_and_issue(i, pg0, i + 2, pg_next, kreg[0], vreg[0]);
                 pg0 = pg_next;
-                issue_loads(i + 2, pg0, kreg[0], vreg[0]);
+                wave_lds_fence();
                 pg_next = page_of(i + 3);
                 compute_tile<D, MT>(w, Ks, Vs, (t_first + kWaves * i) * kTile, S, R, p.scale_log2, n, g);
                 wave_lds_fence();
-                stage(i + 1, pg1, kreg[1], vreg[1]);
-                wave_lds_fence();
+                stage_and_issue(i + 1, pg1, i + 3, pg_next, kreg[1], vreg[1]);
                 pg1 = pg_next;
-                issue_loads(i + 3, pg1, kreg[1], vreg[1]);
+                wave_lds_fence();
                 pg_next = page_of(i + 4);
                 compute_tile<D, MT>(w, Ks, Vs, (t_first + kWaves * (i + 1)) * kTile, S, R, p.scale_log2, n, g);
                 wave_lds_fence();
