@@ -37,6 +37,19 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 MIN_WARMUP_S = 0.03
 
 
+def warm_up(fn, min_calls=3):
+    """Calls fn (which queues GPU work) at least min_calls times and for at least MIN_WARMUP_S of GPU time."""
+    import torch
+    t_w, n = time.perf_counter(), 0
+    while n < min_calls or time.perf_counter() - t_w < MIN_WARMUP_S:
+        fn()
+        n += 1
+        if n >= min_calls:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    return n
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,12 +251,7 @@ class AttnInputs:
         (An idle GPU takes some 15 ms of work to reach its clocks: the first ten launches of the headline
         workload run 9 % slower than the ones after them, so the warm-up is that long.)"""
         import torch
-        t_w, n = time.perf_counter(), 0
-        while n < warmup or time.perf_counter() - t_w < MIN_WARMUP_S:
-            self.attn()
-            n += 1
-            if n >= warmup:
-                torch.cuda.synchronize()
+        warm_up(self.attn, warmup)
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
         for e0, e1 in evs:
             e0.record(); self.attn(); e1.record()
@@ -421,10 +429,10 @@ def measure_maintenance(A, W, cfg, mems, recent_d, rlen_d, idx, steps, dev, rest
         cur_state = torch.full((recent_d.shape[0],), -1, dtype=torch.int32, device=dev)
         cur_len = torch.zeros((recent_d.shape[0],), dtype=torch.int32, device=dev)
         # the bare step on the same maintained copy, nothing appended: what a round is compared with
-        for _ in range(3):
+        def bare_step():
             d, nd, _, _ = A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
             rest(d, nd)
-        torch.cuda.synchronize()
+        warm_up(bare_step)
         tr0 = time.perf_counter()
         for _ in range(steps):
             d, nd, _, _ = A.sam_draft_delta(fd, keys_d, dsts_d, rows_end_d, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
@@ -579,14 +587,7 @@ def main():
             return res
         return None
 
-    t_w = time.perf_counter()
-    n_warm = 0
-    while n_warm < args.warmup or (args.warmup > 0 and time.perf_counter() - t_w < MIN_WARMUP_S):
-        step()
-        n_warm += 1
-        if n_warm >= args.warmup:
-            torch.cuda.synchronize()                          # small workloads: the clock above must see GPU time
-    torch.cuda.synchronize()
+    n_warm = warm_up(step, args.warmup) if args.warmup > 0 else 0
     evs = [[ev() for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -662,9 +663,7 @@ def main():
             d, nd, _, _ = A.sam_draft_step(fd, root_d, cend_d, tok1_d, nn_d, cur_state, cur_len, cfg.k, cfg.sep)
             inp.attn()
             return A.spec_accept(logits, d, nd)
-        for _ in range(3):
-            step_stateful()
-        torch.cuda.synchronize()
+        warm_up(step_stateful)
         t0s = time.perf_counter()
         for _ in range(args.steps):
             step_stateful()
@@ -680,9 +679,7 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
+        warm_up(graph.replay)
         tg0 = time.perf_counter()
         for _ in range(args.steps):
             graph.replay()
