@@ -561,35 +561,13 @@ __device__ __forceinline__ BlockTableRow block_table_row(const AttnParams &p, in
     return (BlockTableRow)(uintptr_t)(p.bt + (int64_t)b * p.max_pages);
 }
 
-// Wide kernel: the page id of every 32-position tile of a chunk, fetched once per 256 tiles (lane i of
-// register r holds the id for tile 64*r + i) and handed out with v_readlane, so the wavefront that requests
-// a tile has its page id at once.  (Scalar loads of the block table, as the narrow kernel makes them, were
-// measured here too: 1 to 2 % slower, the request being on the critical path of a tile.)
+// Largest chunk of the chunk grid, in KV positions.
 constexpr int kMaxChunk = 256 * kTile;
-struct ChunkPages {
-    int r0, r1, r2, r3;          // named members, not an array: an indexable private array would be
-};                               // demoted to LDS by the compiler
-
-__device__ __forceinline__ ChunkPages load_chunk_pages(const AttnParams &p, int b, int c0, int c1, int lane) {
-    ChunkPages cp;
-    const int32_t *row = p.bt + (int64_t)b * p.max_pages;
-    auto page_of_tile = [&](int tile) {
-        const int pos = c0 + tile * kTile;
-        if (pos >= c1) return -1;
-        return row[p.log2P >= 0 ? (pos >> p.log2P) : (pos / p.P)];
-    };
-    cp.r0 = page_of_tile(lane);
-    cp.r1 = page_of_tile(64 + lane);
-    cp.r2 = page_of_tile(128 + lane);
-    cp.r3 = page_of_tile(192 + lane);
-    return cp;
-}
-
-__device__ __forceinline__ int tile_page(const ChunkPages &cp, int t /* uniform */) {
-    const int sel = t >> 6;
-    const int v = sel == 0 ? cp.r0 : sel == 1 ? cp.r1 : sel == 2 ? cp.r2 : cp.r3;
-    return __builtin_amdgcn_readlane(v, t & 63);
-}
+// Wide kernel: the page ids of this many tiles of a segment are held in LDS (15 KB; with the tile ring 79 KB per
+// workgroup, two workgroups per compute unit).  (Scalar loads of the block table at the point of the request, as
+// the narrow kernel makes them one step ahead, were measured here too: 1 to 2 % slower, the request being on the
+// critical path of a tile.)
+constexpr int kPageIds = 3840;
 
 // -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the segment
 template <int D, int MT>
@@ -922,7 +900,7 @@ __device__ __forceinline__ void lds_dma_tile(const char *kb, const char *vb, con
 #undef AGENTSAM_DMA_GROUP
 
 template <int D, int MT, int NS, bool XT>
-__device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *sched_tmp, int wg, int nwg) {
+__device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *page_lds, int *sched_tmp, int wg, int nwg) {
     using W = WideCfg<D>;
     // (opaque: a kernel that runs two bodies one after the other computes each body's lane constants when
     // that body starts, instead of keeping both sets in registers across both)
@@ -974,21 +952,28 @@ __device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *
     // attempt: 0 optimistic (fixed references), 1 exact row maxima only, 2 final pass with those
     for (int attempt = 0;; ++attempt) {
       const bool raise_always = attempt == 1;
-      // page ids are held for 256 tiles at a time; the ring drains and refills at such a boundary
-      for (int sub = 0; sub < sg.nt; sub += kMaxChunk / kTile) {
+      // The page id of every tile of the segment sits in LDS (kPageIds at a time: only a segment longer than
+      // that drains and refills the ring in between); the wavefront that requests a tile reads the id of the
+      // tile it will request next right after a request, so the id is in a register when it is needed.
+      for (int sub = 0; sub < sg.nt; sub += kPageIds) {
         const int c0 = (sg.t0 + sub) * kTile;
-        const int ntiles = min(sg.nt - sub, kMaxChunk / kTile);
-        const int c1 = min(S, c0 + ntiles * kTile);
-        const ChunkPages cp = load_chunk_pages(p, b, c0, c1, lane);
-        // The query fragments and the page ids are needed at once; waiting for them here, explicitly,
-        // keeps the compiler from guarding their first use inside the tile loop with a wait that would
-        // also drain the tile this wavefront has just started to fetch.
+        const int ntiles = min(sg.nt - sub, kPageIds);
+        {
+            const BlockTableRow bt_row = block_table_row(p, b);
+            for (int i = tid; i < ntiles; i += 256) {
+                const int pos = c0 + i * kTile;
+                page_lds[i] = bt_row[p.log2P >= 0 ? (pos >> p.log2P) : (pos / p.P)];
+            }
+        }
+        // The query fragments are needed at once; waiting for them here, explicitly, keeps the compiler from
+        // guarding their first use inside the tile loop with a wait that would also drain the tile this
+        // wavefront has just started to fetch.
         wait_vmcnt0();
+        __syncthreads();                                     // the page ids are in place
 
     // fetch tile t into its ring slot (called by one wavefront)
-    auto issue = [&](int t, int slot_idx) {
+    auto issue = [&](int t, int page, int slot_idx) {
         const int pos0 = c0 + t * kTile;
-        const int page = tile_page(cp, t);
         const bool page_ok = page >= 0 && (int64_t)page < p.num_pages;
         const int slot_in_page = p.log2P >= 0 ? (pos0 & (p.P - 1)) : (pos0 % p.P);
         const int64_t base = (int64_t)(page_ok ? page : 0) * page_bytes + head_bytes + (int64_t)slot_in_page * (D * 2);
@@ -1017,7 +1002,10 @@ __device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *
     };
 
         for (int t = 0; t < NS - 1; ++t)
-            if (t < ntiles && wave == (t & (kWaves - 1))) issue(t, t);
+            if (t < ntiles && wave == (t & (kWaves - 1))) issue(t, __builtin_amdgcn_readfirstlane(page_lds[t]), t);
+        // the first tile this wavefront requests inside the loop: NS-1 .. NS+2, whichever is its turn
+        int next_request = NS - 1 + ((wave - (NS - 1)) & (kWaves - 1));
+        int next_page = next_request < ntiles ? page_lds[next_request] : -1;
         int slot_cur = 0;                                    // ring slot of tile t (t mod NS, kept incrementally)
         for (int t = 0; t < ntiles; ++t, slot_cur = (slot_cur + 1 == NS) ? 0 : slot_cur + 1) {
             if (wave == (t & (kWaves - 1))) wait_vmcnt0();   // the tile I fetched has landed
@@ -1061,7 +1049,10 @@ __device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *
             }
             // The next tile is requested here rather than right after the barrier: the address arithmetic
             // and the load instructions of the fetching wavefront then run while its multiplications drain.
-            if (tn < ntiles && wave == (tn & (kWaves - 1))) issue(tn, slot_cur == 0 ? NS - 1 : slot_cur - 1);
+            if (tn < ntiles && wave == (tn & (kWaves - 1))) {
+                issue(tn, __builtin_amdgcn_readfirstlane(next_page), slot_cur == 0 ? NS - 1 : slot_cur - 1);
+                next_page = tn + kWaves < ntiles ? page_lds[tn + kWaves] : -1;
+            }
             // ---- first half of the V fragments: issued now so their LDS latency hides under the softmax
             auto load_vf = [&](int dt) {
                 const char *a0 = smem + (vx ^ (dt << 5));
@@ -1256,8 +1247,9 @@ __device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *
 template <int D, int MT, int NS, bool XT>
 __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams p) {
     __shared__ __align__(16) char smem[NS * WideCfg<D>::kSlot];
+    __shared__ int page_lds[kPageIds];
     __shared__ int sched_tmp[8];
-    wide_body<D, MT, NS, XT>(p, smem, sched_tmp, (int)blockIdx.x, (int)gridDim.x);
+    wide_body<D, MT, NS, XT>(p, smem, page_lds, sched_tmp, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // Shared-prefix ("cascade") run in one launch.  Every workgroup has a share of the prefix phase (the wide
@@ -1269,6 +1261,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_wide_kernel(const AttnParams
 template <int D, int MTP, bool XTP, int NS>
 __global__ __launch_bounds__(256, 2) void attn_cascade_fused_kernel(const AttnParams p) {
     __shared__ __align__(16) char smem[NS * WideCfg<D>::kSlot];
+    __shared__ int page_lds[kPageIds];
     __shared__ int sched_tmp[8];
     const int wg = (int)blockIdx.x, nwg = (int)gridDim.x;
 #pragma nounroll
@@ -1278,9 +1271,9 @@ __global__ __launch_bounds__(256, 2) void attn_cascade_fused_kernel(const AttnPa
             pp.phase = 1;
             pp.rows = p.gs * p.rows1;                        // rows1 stays the rows of one session
             pp.balanced = 0;
-            wide_body<D, MTP, NS, XTP>(pp, smem, sched_tmp, wg, nwg);
+            wide_body<D, MTP, NS, XTP>(pp, smem, page_lds, sched_tmp, wg, nwg);
         } else {
-            wide_body<D, 1, NS, false>(p, smem, sched_tmp, wg, nwg);
+            wide_body<D, 1, NS, false>(p, smem, page_lds, sched_tmp, wg, nwg);
         }
         __syncthreads();
     }
@@ -1582,7 +1575,7 @@ struct Plan {
     size_t lcp_bytes, own_bytes; // workspace: [lcp][plan][own records][prefix records]
 };
 
-// Workgroups an MI355X keeps resident at once: 256 compute units x 2 (wide kernel, 64 KB of LDS and
+// Workgroups an MI355X keeps resident at once: 256 compute units x 2 (wide kernel, 79 KB of LDS and
 // <= 256 registers) or x 1 (narrow kernel, which takes the whole register file of a SIMD).
 constexpr int kComputeUnits = 256;
 
@@ -1688,7 +1681,7 @@ hipError_t launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st
     if (wide) {
         const int rpw = (p.rows + kWaves - 1) / kWaves;
         const int mt = (rpw + 15) / 16;
-        // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS
+        // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS (and 15 KB of page ids)
         constexpr int NS = 65536 / WideCfg<D>::kSlot;
         // 4 x 16 x (mt-1) rows owned outright plus at most one shared extra row tile, when that fits
         const int extra = p.rows - kWaves * 16 * (mt - 1);
