@@ -937,12 +937,10 @@ __device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *
         const int bq = n & 3, jq = n >> 2, vrow = 4 * g + jq;    // transpose-read lane roles, see pv_mfma
         voff0 = W::kKT + vrow * W::kRowBytes + (((bq >> 1) ^ (vrow & (W::kCPR - 1))) * 16) + (bq & 1) * 8;
     }
-    const int64_t page_bytes = (int64_t)p.Hkv * p.P * D * 2;
     const unsigned smem_addr = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem;   // LDS byte address
 
     for_each_segment(p, sched_tmp, wg, nwg, [&](const Segment &sg) __attribute__((always_inline)) {
     const int b = sg.b, kvh = sg.kvh, S = sg.S;
-    const int64_t head_bytes = (int64_t)kvh * p.P * D * 2;
     const int row_end = min(sg.rows, row0 + rpw);            // (a short last group of the prefix phase has fewer rows)
     WaveState<D, MT> w;
     init_state<D, MT>(w, p, b, kvh, row0, row_end, n, g);
@@ -952,17 +950,23 @@ __device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *
     // attempt: 0 optimistic (fixed references), 1 exact row maxima only, 2 final pass with those
     for (int attempt = 0;; ++attempt) {
       const bool raise_always = attempt == 1;
-      // The page id of every tile of the segment sits in LDS (kPageIds at a time: only a segment longer than
-      // that drains and refills the ring in between); the wavefront that requests a tile reads the id of the
-      // tile it will request next right after a request, so the id is in a register when it is needed.
+      // Where every tile of the segment lies in the caches sits in LDS (kPageIds tiles at a time: only a segment
+      // longer than that drains and refills the ring in between); the wavefront that requests a tile reads the
+      // place of the tile it will request next right after a request, so it is in a register when it is needed.
       for (int sub = 0; sub < sg.nt; sub += kPageIds) {
         const int c0 = (sg.t0 + sub) * kTile;
         const int ntiles = min(sg.nt - sub, kPageIds);
         {
+            // what is kept per tile is its place in the caches, counted in tiles: ((page * Hkv + kv head) * P + slot) / 32,
+            // or -1 for an unusable page id; the request then needs one shift and two additions
             const BlockTableRow bt_row = block_table_row(p, b);
+            const int tiles_per_page = p.P / kTile;
             for (int i = tid; i < ntiles; i += 256) {
                 const int pos = c0 + i * kTile;
-                page_lds[i] = bt_row[p.log2P >= 0 ? (pos >> p.log2P) : (pos / p.P)];
+                const int page = bt_row[p.log2P >= 0 ? (pos >> p.log2P) : (pos / p.P)];
+                const int slot = p.log2P >= 0 ? (pos & (p.P - 1)) : (pos % p.P);
+                const bool ok = page >= 0 && (int64_t)page < p.num_pages;
+                page_lds[i] = ok ? (page * p.Hkv + kvh) * tiles_per_page + slot / kTile : -1;
             }
         }
         // The query fragments are needed at once; waiting for them here, explicitly, keeps the compiler from
@@ -972,11 +976,10 @@ __device__ __forceinline__ void wide_body(const AttnParams &p, char *smem, int *
         __syncthreads();                                     // the page ids are in place
 
     // fetch tile t into its ring slot (called by one wavefront)
-    auto issue = [&](int t, int page, int slot_idx) {
+    auto issue = [&](int t, int place, int slot_idx) {
         const int pos0 = c0 + t * kTile;
-        const bool page_ok = page >= 0 && (int64_t)page < p.num_pages;
-        const int slot_in_page = p.log2P >= 0 ? (pos0 & (p.P - 1)) : (pos0 % p.P);
-        const int64_t base = (int64_t)(page_ok ? page : 0) * page_bytes + head_bytes + (int64_t)slot_in_page * (D * 2);
+        const bool page_ok = place >= 0;
+        const int64_t base = (int64_t)(page_ok ? place : 0) * (kTile * D * 2);
         const char *kb = (const char *)uniform_ptr((const char *)p.kc + base);
         const char *vb = (const char *)uniform_ptr((const char *)p.vc + base);
         const int slot_off = slot_idx * W::kSlot;
