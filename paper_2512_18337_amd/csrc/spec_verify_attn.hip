@@ -563,11 +563,12 @@ __device__ __forceinline__ BlockTableRow block_table_row(const AttnParams &p, in
 
 // Largest chunk of the chunk grid, in KV positions.
 constexpr int kMaxChunk = 256 * kTile;
-// Wide kernel: the page ids of this many tiles of a segment are held in LDS (15 KB; with the tile ring 79 KB per
-// workgroup, two workgroups per compute unit).  (Scalar loads of the block table at the point of the request, as
+// Wide kernel: where this many tiles of a segment lie in the caches is held in LDS (4 KB; with the tile ring 68 KB
+// per workgroup, two workgroups per compute unit).  A longer segment (more than 32768 positions of one stream in
+// one workgroup's share) is taken in pieces of this size, the ring draining and refilling in between.  (Scalar loads of the block table at the point of the request, as
 // the narrow kernel makes them one step ahead, were measured here too: 1 to 2 % slower, the request being on the
 // critical path of a tile.)
-constexpr int kPageIds = 3840;
+constexpr int kPageIds = 1024;
 
 // -------- narrow kernel: up to 48 packed rows; the 4 wavefronts take different tiles of the segment
 template <int D, int MT>
@@ -1578,7 +1579,7 @@ struct Plan {
     size_t lcp_bytes, own_bytes; // workspace: [lcp][plan][own records][prefix records]
 };
 
-// Workgroups an MI355X keeps resident at once: 256 compute units x 2 (wide kernel, 79 KB of LDS and
+// Workgroups an MI355X keeps resident at once: 256 compute units x 2 (wide kernel, 68 KB of LDS and
 // <= 256 registers) or x 1 (narrow kernel, which takes the whole register file of a SIMD).
 constexpr int kComputeUnits = 256;
 
@@ -1684,7 +1685,7 @@ hipError_t launch_bf16(const AttnParams &p, bool wide, dim3 grid, hipStream_t st
     if (wide) {
         const int rpw = (p.rows + kWaves - 1) / kWaves;
         const int mt = (rpw + 15) / 16;
-        // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS (and 15 KB of page ids)
+        // two workgroups per compute unit, each with a ring of tile slots in 64 KB of LDS (and 4 KB for the tiles' places)
         constexpr int NS = 65536 / WideCfg<D>::kSlot;
         // 4 x 16 x (mt-1) rows owned outright plus at most one shared extra row tile, when that fits
         const int extra = p.rows - kWaves * 16 * (mt - 1);
