@@ -20,7 +20,7 @@ def _inputs(cfg):
 # (first call, second call with a smaller input): the second runs on whatever the first left in the array
 PAIRS = [
     # balanced schedule (512 streams), then fewer and shorter sessions through the chunk grid + merge kernel
-    (dict(B=70, Hq=32, Hkv=8, D=128, k=8, kv_mode="ragged", kv_len=(9, 1500)), {},
+    (dict(B=70, Hq=32, Hkv=8, D=128, k=8, kv_mode="ragged", kv_len=(9, 1500)), dict(schedule=2),
      dict(B=5, Hq=8, Hkv=2, D=128, k=8, kv_mode="ragged", kv_len=(9, 1200)), dict(kv_chunk=256)),
     # wide kernel, balanced; then a shared-prefix run that keeps page counts, prefix sums and records there
     (dict(B=40, Hq=8, Hkv=2, D=128, k=12, kv_mode="ragged", kv_len=(40, 3000)), dict(schedule=2),
