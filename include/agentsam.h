@@ -52,7 +52,8 @@ const char *agentsam_strerror(int code);
  * beyond rounding (the split decides what each softmax weight is rounded against).
  *   schedule   how a bf16 batch is spread over the GPU: CHUNKS = every (session, kv head) stream cut into
  *              chunks, one workgroup per chunk; BALANCED = all streams laid end to end and cut into one
- *              equal share per resident workgroup; default: BALANCED for large batches.
+ *              equal share per resident workgroup; default: BALANCED when there are at least two streams
+ *              per resident workgroup and the block table covers more than 8192 positions, else CHUNKS.
  *   cascade    shared-prefix run (bf16): ON = look for pages that all sessions list at the same place of
  *              their block tables and process them once per group of sessions instead of once per
  *              session; OFF = never; default: look when the K/V stream is large enough (>= 11 GB) for the
