@@ -35,6 +35,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 # An idle GPU takes some 15 ms of work to reach its clocks (the first ten launches of the headline workload run 9 %
 # slower than the ones after them): a warm-up lasts at least this long, however few steps were asked for.
 MIN_WARMUP_S = 0.03
+SEED_GEMM = 18337                # operands of the library-GEMM yardstick
 
 
 def warm_up(fn, min_calls=3):
@@ -318,10 +319,31 @@ def paged_read_rate(inp, dev):
     return nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def library_gemm_rate(dev, n=8192, launches=20):
+    """A yardstick for the matrix-bound workload, as the streaming probe is one for the HBM-bound ones: what the
+    vendor library's plain bf16 GEMM (torch.matmul, n x n x n, N(0,1) operands) sustains on this GPU, in TFLOP/s.
+    Not part of the path: nothing in the library calls it."""
+    import torch
+    g = torch.Generator(device=dev)
+    g.manual_seed(SEED_GEMM)
+    a = torch.randn(n, n, device=dev, dtype=torch.bfloat16, generator=g)
+    b = torch.randn(n, n, device=dev, dtype=torch.bfloat16, generator=g)
+    c = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
+    warm_up(lambda: torch.matmul(a, b, out=c), 10)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(launches):
+        torch.matmul(a, b, out=c)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n ** 3 * launches / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def measure_targets(A, W, dev, stream_gbs, seed):
     """spec_verify_attn alone (10 launches) on the two other workloads the bandwidth target names."""
     import torch
     out = {}
+    gemm_tflops = library_gemm_rate(dev)
     for i in (3, 4):
         cfg = W.baseline_config(i)
         if seed is not None:
@@ -329,6 +351,8 @@ def measure_targets(A, W, dev, stream_gbs, seed):
         inp = AttnInputs(A, W, cfg, dev, 0)
         t = inp.time_attn(10)
         out[cfg.name] = attention_roofline(cfg, inp.lay, t, stream_gbs)
+        out[cfg.name]["library_gemm_bf16_TFLOPs"] = gemm_tflops
+        out[cfg.name]["mfma_frac_of_library_gemm"] = out[cfg.name]["mfma_TFLOPs"] / gemm_tflops
         del inp
         torch.cuda.empty_cache()
     return out
