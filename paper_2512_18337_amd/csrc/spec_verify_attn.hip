@@ -44,6 +44,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;          // finite stand-in for -inf in running maxima
+constexpr float kPadRef = 1.0e30f;           // softmax reference of a row slot that holds no row
 constexpr int kTile = 32;                    // KV positions per wavefront step
 constexpr int kWaves = 4;
 constexpr int kRowsPerGroup = 48;            // packed rows one wavefront can hold (3 MFMA row tiles of 16)
@@ -186,7 +187,9 @@ __device__ __forceinline__ void init_state(WaveState<D, MT> &w, const AttnParams
             if (live) raw = *(const s16x8 *)(src + ks * 32 + g * 8);
             w.qf[rt][ks] = __builtin_bit_cast(bf16x8, raw);
         }
-        w.m_run[rt] = kNegBig;
+        // A row slot beyond the live rows gets a reference no score comes near: its weights are exact zeros, so the
+        // second contraction multiplies zeros for it instead of accumulating sums of V that nobody reads.
+        w.m_run[rt] = live ? kNegBig : kPadRef;
         w.l_part[rt] = 0.f;
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) w.oacc[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
