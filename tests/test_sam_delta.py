@@ -231,7 +231,7 @@ def test_periodic_memory_appends_cost_one_chain_walk_per_export_not_per_token():
     assert np.array_equal(lastpos[:f1.lastpos.size], f1.lastpos)
     print(f"9000 tokens appended to a period-3 memory of 30000: {t_plain * 1e3:.1f} ms plain, {t_tracked * 1e3:.1f} ms with "
           f"31 exports ({t_tracked / more.size * 1e6:.2f} us per token)")
-    assert t_tracked < 0.15                                   # (one chain walk per token took 0.5 s here)
+    assert t_tracked < 0.3                                    # (one chain walk per token took 0.5 s here; this takes 0.05 s)
 
 
 def test_export_argument_errors():
