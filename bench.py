@@ -76,6 +76,9 @@ def parse():
     ap.add_argument("--cold", action="store_true",
                     help="write a 512 MiB scratch buffer before every step (outside the timed events), so that nothing of "
                          "the previous step is left in the caches; ms_per_step is then the sum of the kernels' event times")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="experiments only, with --attn-only: K, V and Q all zero - the same instruction stream without "
+                         "data toggling in the matrix pipes, which shows what the GPU's power limit costs a workload")
     ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
                     help="override a workload field (experiments only), e.g. --set permute_pages=False")
     return ap.parse_args()
@@ -586,6 +589,10 @@ def main():
     rlen_d = torch.as_tensor(rlen, device=dev)
     inp = AttnInputs(A, W, cfg, dev, tuning)
     lay, q, kc, vc = inp.lay, inp.q, inp.kc, inp.vc
+    if args.zero_inputs:
+        if not args.attn_only:
+            sys.exit("--zero-inputs is an experiment on spec_verify_attn alone: add --attn-only")
+        q.zero_(); kc.zero_(); vc.zero_()
 
     # the logits stand in for the LM head: built once from the library's own drafts
     draft, n_draft, _, _ = A.sam_draft(fd, root_d, cend_d, recent_d, rlen_d, cfg.k, cfg.sep)
@@ -643,7 +650,7 @@ def main():
         "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "head_dim": cfg.D,
                    "kv_len": [int(lay.seq_lens.min()), int(lay.seq_lens.max())], "page": cfg.page, "k": cfg.k,
                    "sam_tokens": int(sum(len(m) for m in mems)), "vocab": cfg.vocab, "seed": cfg.seed,
-                   "step": "sam_draft + spec_verify_attn + spec_accept", "attn_only": bool(args.attn_only),
+                   "step": "sam_draft + spec_verify_attn + spec_accept", "attn_only": bool(args.attn_only), "zero_inputs": bool(args.zero_inputs),
                    "cold_caches": bool(args.cold)},
         "roofline": attention_roofline(cfg, lay, t_attn, stream_gbs, paged_read_rate(inp, dev)),
         "detail": {"t_draft_us": t_draft * 1e3, "t_attn_us": t_attn * 1e3, "t_accept_us": t_accept * 1e3,
